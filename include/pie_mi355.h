@@ -1,0 +1,182 @@
+/*
+ * pie_mi355 - C ABI of the inference-layer hot path of a programmable LLM serving system on one
+ * AMD MI355X (gfx950): the batched `forward` handler (one Llama-class decoder layer applied to a
+ * heterogeneous batch of commands against KvPage page tables with per-token attention masks and
+ * KV append) and the `get_next_dist` handler (next-token distribution truncated to top-K).
+ *
+ * Conventions for every call
+ *   - "host" pointers are ordinary CPU memory owned by the caller and read only during the call.
+ *   - "dev" pointers are device memory on the GPU the context was created on, owned by the
+ *     caller; the library reads/writes them on the context's stream.
+ *   - bf16 tensors are raw 16-bit patterns.  Nothing here is a torch type.
+ *   - All GPU work is enqueued on the HIP stream given to pie_create and is complete only after
+ *     pie_synchronize (or a stream synchronisation by the caller).
+ *   - Every call returns a pie_status; on error nothing has been launched for that call unless
+ *     stated otherwise, and pie_last_error gives a message.  The library never aborts.
+ *   - One context <-> one stream <-> one GPU.  A context is not thread-safe.
+ */
+#ifndef PIE_MI355_H
+#define PIE_MI355_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pie_ctx pie_ctx;     /* owns the Embed pool, the KvPage pool, packed weights, workspace */
+typedef struct pie_batch pie_batch; /* a validated forward batch resident on the device */
+typedef int32_t pie_status;
+
+enum {
+  PIE_OK = 0,
+  PIE_EINVAL = -1,       /* null pointer, bad shape, non-positive temperature, ... */
+  PIE_ERANGE = -2,       /* page id, embed id, slot, layer or top_k out of range */
+  PIE_EBATCH = -3,       /* more tokens or requests than the context was sized for */
+  PIE_ECONFLICT = -4,    /* two tokens of one batch write the same (page, slot) */
+  PIE_ENOMEM = -5,       /* device allocation failed */
+  PIE_EHIP = -6,         /* a HIP call failed (asynchronous faults surface at pie_synchronize) */
+  PIE_EUNSUPPORTED = -7  /* shape outside what the kernels are built for */
+};
+
+/* Model shape: a Llama-family decoder layer (Implementation section: the handlers support the
+ * Llama family) - RMSNorm, grouped-query attention with rotary positions, SwiGLU MLP, no biases.
+ * Supported: head_dim 64 or 128, page_size 16 (KvPage sizes of 8-32 tokens are named in the
+ * Resources paragraph), n_q_heads a multiple of n_kv_heads with ratio <= 8, hidden / mlp_dim /
+ * vocab multiples of 32. */
+typedef struct {
+  int32_t hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, vocab, page_size;
+  float rms_eps, rope_theta;
+  int32_t n_layers; /* layers resident in this context (weights + one KvPage pool each) */
+} pie_model_desc;
+
+/* Resource pools, sized once at start-up (Control layer, Resource management: a global pool of
+ * Embed and KvPage resources physically located in the inference layer). */
+typedef struct {
+  int32_t n_kv_pages, n_embeds, max_batch_tokens, max_batch_requests, max_top_k, max_dist_rows;
+} pie_pool_desc;
+
+/* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (NULL = default
+ * stream).  Allocates pools (zero-filled) and workspace; nothing is allocated afterwards by
+ * pie_forward / pie_get_next_dist. */
+pie_status pie_create(const pie_model_desc* model, const pie_pool_desc* pool, void* hip_stream, pie_ctx** out);
+pie_status pie_destroy(pie_ctx* ctx);
+/* Message of the last failing call on ctx (ctx may be NULL for pie_create failures); storage
+ * is owned by the library and valid until the next call. */
+const char* pie_last_error(const pie_ctx* ctx);
+
+/* Weights: dev pointers, bf16, Linear layout [out, in]; gains [hidden].  The library copies them
+ * into its own tiled storage, so the caller may free its tensors once the stream has drained. */
+pie_status pie_load_layer(pie_ctx* ctx, int32_t layer, const void* g1, const void* wq, const void* wk,
+                          const void* wv, const void* wo, const void* g2, const void* wgate, const void* wup,
+                          const void* wdown);
+/* g_final may be NULL: get_next_dist then applies no final norm. */
+pie_status pie_load_head(pie_ctx* ctx, const void* g_final, const void* w_lm /* [vocab, hidden] */);
+
+/* Resource seeding / inspection.  Stand-ins for what `embed_txt` and earlier `forward` calls
+ * leave in the pools (Table 1; Embed API), used by tests and the benchmark.  ids/slots: host
+ * int32 [n]; data: dev bf16.  KV rows are token-major [n, n_kv_heads, head_dim]; K is stored as
+ * given (already rotated).  The pool layout itself is private to the library. */
+pie_status pie_embed_write(pie_ctx* ctx, const int32_t* embed_ids, int32_t n, const void* src /* dev [n, hidden] */);
+pie_status pie_embed_read(pie_ctx* ctx, const int32_t* embed_ids, int32_t n, void* dst /* dev [n, hidden] */);
+pie_status pie_kv_write(pie_ctx* ctx, int32_t layer, const int32_t* page_ids, const int32_t* slots, int32_t n,
+                        const void* k /* dev */, const void* v /* dev */);
+pie_status pie_kv_read(pie_ctx* ctx, int32_t layer, const int32_t* page_ids, const int32_t* slots, int32_t n,
+                       void* k /* dev */, void* v /* dev */);
+
+/* One batch of `forward(q, ikv, iemb, okv, oemb, mask)` commands as the batch scheduler hands it
+ * to the handler (Table 1 `forward`; Forward API; Batch scheduler: horizontal + vertical
+ * batching).  The command queue argument is gone: batching has been done.  All arrays are host.
+ *
+ *   request r owns tokens tok_indptr[r] .. tok_indptr[r+1)  (its input Embeds, in order)
+ *   page table of r: page_ids[page_indptr[r] .. page_indptr[r+1)) = input KvPages followed by
+ *     output KvPages, in logical order; logical KV index j lives in page j / page_size, slot
+ *     j % page_size of that list
+ *   kv_len[r]: KV length AFTER this call's append; new token i of r is stored at logical index
+ *     kv_len[r] - n_new_r + i, whatever its position
+ *   positions[t]: explicit rotary position of token t (Forward API: explicit sequence positions)
+ *   out_embed_ids[t]: Embed that receives the layer output of token t, or -1 to drop the row
+ *     (fewer output than input Embeds: the example with 9 inputs and 1 output).  An Embed may be
+ *     both input and output of one call (autoregressive-loop example).
+ *   mask: boolean matrix, one row per new token over logical KV index [0, kv_len[r]) including
+ *     the tokens appended by this call; row = ceil(kv_len[r]/32) uint32 words, bit (j % 32) of
+ *     word j / 32, LSB first, bits >= kv_len ignored.  mask_indptr (word offsets, [R+1]) may be
+ *     NULL, and a request with an empty word range has its mask inferred: causal on logical
+ *     order (token i sees j <= kv_len - n_new + i).  A row with no visible key outputs zeros.
+ *
+ * Effects of a call, in order: read all input Embeds; append every new K/V; attend; write output
+ * Embeds.  Two tokens of one batch must not write the same (page, slot) (vertical batching is
+ * only done when calls do not conflict); checked when validate != 0.
+ */
+typedef struct {
+  int32_t n_requests, n_tokens;
+  const int32_t* tok_indptr;    /* [R+1] */
+  const int32_t* in_embed_ids;  /* [T] */
+  const int32_t* out_embed_ids; /* [T] */
+  const int32_t* positions;     /* [T] */
+  const int32_t* page_indptr;   /* [R+1] */
+  const int32_t* page_ids;      /* [page_indptr[R]] */
+  const int32_t* kv_len;        /* [R] */
+  const int64_t* mask_indptr;   /* [R+1] or NULL */
+  const uint32_t* mask_words;   /* [mask_indptr[R]] or NULL */
+} pie_forward_batch;
+
+/* Deserialise a batch: check shapes and id ranges on the host (validate != 0 adds the
+ * write-conflict check), derive the attention work lists (pages with no visible key are
+ * dropped, so cost follows the mask and not the context length), and copy everything the
+ * kernels need to the device.  Allocates device memory owned by the returned pie_batch.
+ * Errors: PIE_EINVAL, PIE_ERANGE, PIE_EBATCH, PIE_ECONFLICT, PIE_ENOMEM, PIE_EHIP. */
+pie_status pie_batch_create(pie_ctx* ctx, const pie_forward_batch* batch, int32_t validate, pie_batch** out);
+pie_status pie_batch_destroy(pie_ctx* ctx, pie_batch* batch);
+
+/* Run one decoder layer over the batch (Forward API: attention and transformation steps):
+ * RMSNorm, QKV projection, rotary step + KV append into pages, paged masked GQA attention,
+ * output projection + residual, RMSNorm, SwiGLU MLP + residual, output Embeds.  Enqueues only;
+ * allocates nothing.  The batch may be reused across calls and layers. */
+pie_status pie_forward(pie_ctx* ctx, int32_t layer, const pie_batch* batch);
+
+/* Convenience: pie_batch_create + pie_forward + pie_batch_destroy (synchronises the stream). */
+pie_status pie_forward_host(pie_ctx* ctx, int32_t layer, const pie_forward_batch* batch, int32_t validate);
+
+/* `get_next_dist(q, emb) -> Dist` for n Embeds (Table 1; Sample API): final RMSNorm when the head
+ * has a gain, LM head in fp32 logits, softmax(logits / temperature) over the whole vocabulary,
+ * truncated to the top_k entries (Sample API: top-K truncation, K configurable, default 256).
+ * Output per row: ids and probabilities by descending probability, equal values by ascending id;
+ * probabilities are those of the full distribution (no renormalisation).
+ * embed_ids: host int32 [n]; out_ids dev int32 [n, top_k]; out_probs dev float [n, top_k].
+ * Errors: PIE_EINVAL (temperature <= 0, n <= 0), PIE_ERANGE (top_k, ids), PIE_EBATCH (n). */
+pie_status pie_get_next_dist(pie_ctx* ctx, const int32_t* embed_ids, int32_t n, int32_t top_k, float temperature,
+                             int32_t* out_ids, float* out_probs);
+
+pie_status pie_synchronize(pie_ctx* ctx);
+
+/* ---- observation points for parity tests and per-kernel timing (not part of the serving path) ---- */
+
+/* Copy an intermediate of the last pie_forward / pie_get_next_dist to `dst` (dev).  Sizes in
+ * elements: Q [T, Hq*D] bf16 (after the rotary step), ATTN [T, Hq*D] bf16, RESID [T, hidden]
+ * fp32 (after the attention block), ACT [T, mlp_dim] bf16, LOGITS [n, vocab] fp32. */
+enum { PIE_TAP_Q = 0, PIE_TAP_ATTN = 1, PIE_TAP_RESID = 2, PIE_TAP_ACT = 3, PIE_TAP_LOGITS = 4 };
+pie_status pie_read_tap(pie_ctx* ctx, int32_t which, void* dst, int64_t n_elements);
+
+/* Stage timing.  When enabled, pie_forward / pie_get_next_dist bracket each stage with HIP events
+ * on the context's stream; pie_stage_times synchronises and returns the milliseconds of the last
+ * call per stage (host float[PIE_N_STAGES]; 0 for stages that did not run). */
+enum {
+  PIE_STAGE_NORM1 = 0, PIE_STAGE_QKV = 1, PIE_STAGE_ROPE_APPEND = 2, PIE_STAGE_ATTN_DECODE = 3,
+  PIE_STAGE_ATTN_PREFILL = 4, PIE_STAGE_ATTN_MERGE = 5, PIE_STAGE_OPROJ = 6, PIE_STAGE_NORM2 = 7,
+  PIE_STAGE_GATEUP = 8, PIE_STAGE_DOWN = 9, PIE_STAGE_HEAD_NORM = 10, PIE_STAGE_LM_HEAD = 11,
+  PIE_STAGE_TOPK = 12, PIE_N_STAGES = 13
+};
+pie_status pie_set_stage_timing(pie_ctx* ctx, int32_t enabled);
+pie_status pie_stage_times(pie_ctx* ctx, float* ms_out);
+
+/* Algorithmic work of a batch for roofline accounting: out[0] = KV bytes the attention stage has
+ * to read (visible pages x page bytes, K and V, all kv heads), out[1] = decode-path share of
+ * out[0], out[2] = attention flops (QK^T and PV over visible pages), out[3] = number of visited
+ * (request, page) pairs.  Host int64[4]. */
+pie_status pie_batch_work(const pie_batch* batch, int64_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIE_MI355_H */

@@ -304,11 +304,15 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
 # --------------------------------------------------------------------------------------------
 
 
-def logits_from_embeds(model, head, emb: EmbedPool, embed_ids) -> np.ndarray:
-    """Final norm (when the head carries a gain) and LM head on stored Embeds -> float64 logits."""
+def logits_from_embeds(model, head, emb: EmbedPool, embed_ids, round_intermediates: bool = False) -> np.ndarray:
+    """Final norm (when the head carries a gain) and LM head on stored Embeds -> float64 logits.
+
+    `round_intermediates` rounds the normalised activation to bf16 before the LM head, the
+    precision the paper states for activations (Evaluation, Setup: weights, KV cache and
+    activations in BF16); the logits themselves stay wide."""
     e = bf16_decode(emb.bits[np.asarray(embed_ids, dtype=np.int64)])
     if head.g_final is not None:
-        e = rmsnorm(e, bf16_decode(head.g_final), model.rms_eps)
+        e = _maybe_round(rmsnorm(e, bf16_decode(head.g_final), model.rms_eps), round_intermediates)
     return e @ bf16_decode(head.w_lm).T
 
 
@@ -333,8 +337,9 @@ def top_k_dist(logits: np.ndarray, top_k: int, temperature: float = 1.0):
     return ids, probs
 
 
-def get_next_dist(model, head, emb: EmbedPool, embed_ids, top_k: int, temperature: float = 1.0):
+def get_next_dist(model, head, emb: EmbedPool, embed_ids, top_k: int, temperature: float = 1.0,
+                  round_intermediates: bool = False):
     """Sample API `get_next_dist`: next-token distribution of each Embed, truncated to top-K."""
-    z = logits_from_embeds(model, head, emb, embed_ids)
+    z = logits_from_embeds(model, head, emb, embed_ids, round_intermediates)
     ids, probs = top_k_dist(z, top_k, temperature)
     return ids, probs, z

@@ -1,0 +1,52 @@
+// Shared device/host helpers for the gfx950 kernels: vector types, bf16 conversion, MFMA wrappers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define WAVE 64
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return (float)x; }
+__device__ __forceinline__ bf16_t f32_to_bf16(float x) { return (bf16_t)x; }  // v_cvt_pk_bf16_f32: round to nearest even
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// 16-byte views
+union Pack16 {
+  u32x4 u;
+  bf16x8 h;
+  uint16_t s[8];
+};
+
+// D = A(32x16) * B(16x32) + C.  Lane l carries, for A, row (l % 32) and the 8 contraction
+// elements of lane group (l / 32); for B, column (l % 32) and the same 8 contraction elements.
+// C/D: lane l carries column (l % 32); register v is row (v / 4) * 8 + (l / 32) * 4 + (v % 4).
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+// Tiled weight storage: W[N, K] (Linear layout) is cut into tiles of 32 output rows x 16 inputs,
+// 1 KiB each, stored [N/32][K/16]; inside a tile lane l = g * 32 + n holds W[nb*32 + n][kb*16 + g*8 .. +8].
+// One 16-byte load per lane is then exactly the B operand of mfma32.
+__host__ __device__ __forceinline__ int64_t packed_tile_offset(int nb, int kb, int kblocks) {
+  return ((int64_t)nb * kblocks + kb) * 512;  // in bf16 elements
+}

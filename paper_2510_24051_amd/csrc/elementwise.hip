@@ -1,0 +1,229 @@
+// Memory-bound helper kernels: weight tiling, RMSNorm, rotary step + KV append into pages,
+// Embed / KvPage pool copies.
+#include "internal.h"
+
+// ---------------------------------------------------------------------------------------------
+// Weight tiling: up to three [rows_i, K] matrices stacked (or two interleaved in 32-row blocks)
+// into the tiled layout described in common.h.  One thread moves one 16-byte piece.
+// ---------------------------------------------------------------------------------------------
+__global__ void pack_weight_kernel(const bf16_t* __restrict__ s0, int r0, const bf16_t* __restrict__ s1, int r1,
+                                   const bf16_t* __restrict__ s2, int r2, int K, int interleave,
+                                   bf16_t* __restrict__ dst, int NB) {
+  const int KB = K / 16;
+  int64_t piece = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one per (nb, kb, lane)
+  int64_t total = (int64_t)NB * KB * 64;
+  if (piece >= total) return;
+  int lane = (int)(piece & 63);
+  int64_t tile = piece >> 6;
+  int kb = (int)(tile % KB);
+  int nb = (int)(tile / KB);
+  int n = nb * 32 + (lane & 31);
+  int k = kb * 16 + (lane >> 5) * 8;
+  const bf16_t* src = nullptr;
+  if (interleave) {  // block 2b <- s0 rows [32b, 32b+32), block 2b+1 <- s1 rows [32b, 32b+32)
+    int row = (nb >> 1) * 32 + (lane & 31);
+    if (row < r0) src = ((nb & 1) ? s1 : s0) + (int64_t)row * K + k;
+  } else {
+    if (n < r0) src = s0 + (int64_t)n * K + k;
+    else if (n < r0 + r1) src = s1 + (int64_t)(n - r0) * K + k;
+    else if (n < r0 + r1 + r2) src = s2 + (int64_t)(n - r0 - r1) * K + k;
+  }
+  u32x4 v = {0, 0, 0, 0};
+  if (src) v = *reinterpret_cast<const u32x4*>(src);
+  *reinterpret_cast<u32x4*>(dst + piece * 8) = v;
+}
+
+hipError_t launch_pack_weight(const bf16_t* s0, int r0, const bf16_t* s1, int r1, const bf16_t* s2, int r2, int K,
+                              int interleave, bf16_t* dst, int NB, hipStream_t s) {
+  int64_t total = (int64_t)NB * (K / 16) * 64;
+  int64_t blocks = (total + 255) / 256;
+  pack_weight_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(s0, r0, s1, r1, s2, r2, K, interleave, dst, NB);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm: one workgroup per row, values kept in registers between the two passes.
+// ---------------------------------------------------------------------------------------------
+template <bool FROM_EMBED>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ xin, const int32_t* __restrict__ ids,
+                                                      const bf16_t* __restrict__ gain, bf16_t* __restrict__ out,
+                                                      int H, float eps) {
+  __shared__ float red[4];
+  const int row = blockIdx.x;
+  const int tid = threadIdx.x;
+  constexpr int MAXV = 8;  // 8 elements per thread per pass of 2048 columns
+  float vals[4][MAXV];
+  float ss = 0.f;
+  const int npass = (H + 2047) / 2048;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    int c = p * 2048 + tid * 8;
+    if (p < npass && c < H) {
+      if (FROM_EMBED) {
+        const bf16_t* x = reinterpret_cast<const bf16_t*>(xin) + (int64_t)ids[row] * H + c;
+        Pack16 pk;
+        pk.u = *reinterpret_cast<const u32x4*>(x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vals[p][e] = bf16_bits_to_f32(pk.s[e]);
+      } else {
+        const float* x = reinterpret_cast<const float*>(xin) + (int64_t)row * H + c;
+        f32x4 a = *reinterpret_cast<const f32x4*>(x);
+        f32x4 b = *reinterpret_cast<const f32x4*>(x + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { vals[p][e] = a[e]; vals[p][4 + e] = b[e]; }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += vals[p][e] * vals[p][e];
+    }
+  }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  float tot = red[0] + red[1] + red[2] + red[3];
+  float rstd = 1.0f / sqrtf(tot / (float)H + eps);
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    int c = p * 2048 + tid * 8;
+    if (p < npass && c < H) {
+      Pack16 g, o;
+      g.u = *reinterpret_cast<const u32x4*>(gain + c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o.h[e] = f32_to_bf16(vals[p][e] * rstd * bf16_bits_to_f32(g.s[e]));
+      *reinterpret_cast<u32x4*>(out + (int64_t)row * H + c) = o.u;
+    }
+  }
+}
+
+hipError_t launch_rmsnorm_embed(const bf16_t* embeds, const int32_t* ids, const bf16_t* gain, bf16_t* out, int rows,
+                                int H, float eps, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  rmsnorm_kernel<true><<<dim3(rows), dim3(256), 0, s>>>(embeds, ids, gain, out, H, eps);
+  return hipGetLastError();
+}
+hipError_t launch_rmsnorm_f32(const float* x, const bf16_t* gain, bf16_t* out, int rows, int H, float eps,
+                              hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  rmsnorm_kernel<false><<<dim3(rows), dim3(256), 0, s>>>(x, nullptr, gain, out, H, eps);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rotary step + KV append.  qkv is [T, (Hq + 2 Hkv) * D] bf16.  One thread handles, for a query or
+// key head, the 8 pairs (c*8 + e, D/2 + c*8 + e); for a value head, 16 consecutive elements.
+// Angles are pos * theta^(-2i/D) evaluated in double (positions reach tens of thousands).
+// Rotated queries are written back in place; rotated keys and values go to the token's page slot.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ qkv, int T, int Hq, int Hkv, int D,
+                                                          const int32_t* __restrict__ pos,
+                                                          const int32_t* __restrict__ tok_page,
+                                                          const int32_t* __restrict__ tok_slot,
+                                                          const double* __restrict__ inv_freq,
+                                                          bf16_t* __restrict__ kv_layer) {
+  const int cpt = D / 16;  // work pieces per head
+  const int heads = Hq + 2 * Hkv;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t total = (int64_t)T * heads * cpt;
+  if (idx >= total) return;
+  int c = (int)(idx % cpt);
+  int h = (int)((idx / cpt) % heads);
+  int t = (int)(idx / ((int64_t)cpt * heads));
+  bf16_t* row = qkv + (int64_t)t * heads * D + (int64_t)h * D;
+  const int page = tok_page[t], slot = tok_slot[t];
+  if (h < Hq + Hkv) {
+    Pack16 lo, hi, olo, ohi;
+    lo.u = *reinterpret_cast<const u32x4*>(row + c * 8);
+    hi.u = *reinterpret_cast<const u32x4*>(row + D / 2 + c * 8);
+    const double p = (double)pos[t];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      double sn, cs;
+      sincos(p * inv_freq[c * 8 + e], &sn, &cs);
+      float a = bf16_bits_to_f32(lo.s[e]), b = bf16_bits_to_f32(hi.s[e]);
+      float fc = (float)cs, fs = (float)sn;
+      olo.h[e] = f32_to_bf16(a * fc - b * fs);
+      ohi.h[e] = f32_to_bf16(b * fc + a * fs);
+    }
+    if (h < Hq) {
+      *reinterpret_cast<u32x4*>(row + c * 8) = olo.u;
+      *reinterpret_cast<u32x4*>(row + D / 2 + c * 8) = ohi.u;
+    } else {
+      bf16_t* blk = kv_layer + ((int64_t)page * Hkv + (h - Hq)) * (2 * PAGE * D);
+      *reinterpret_cast<u32x4*>(blk + k_elem_offset(slot, c * 8)) = olo.u;
+      *reinterpret_cast<u32x4*>(blk + k_elem_offset(slot, D / 2 + c * 8)) = ohi.u;
+    }
+  } else {
+    bf16_t* blk = kv_layer + ((int64_t)page * Hkv + (h - Hq - Hkv)) * (2 * PAGE * D);
+    Pack16 a, b;
+    a.u = *reinterpret_cast<const u32x4*>(row + c * 16);
+    b.u = *reinterpret_cast<const u32x4*>(row + c * 16 + 8);
+    uint16_t* dst = reinterpret_cast<uint16_t*>(blk);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dst[v_elem_offset(slot, c * 16 + e, D)] = a.s[e];
+      dst[v_elem_offset(slot, c * 16 + 8 + e, D)] = b.s[e];
+    }
+  }
+}
+
+hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const int32_t* pos, const int32_t* tok_page,
+                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, hipStream_t s) {
+  int64_t total = (int64_t)T * (Hq + 2 * Hkv) * (D / 16);
+  if (total <= 0) return hipSuccess;
+  rope_append_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(qkv, T, Hq, Hkv, D, pos, tok_page,
+                                                                                   tok_slot, inv_freq, kv_layer);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pool copies for seeding and inspection.
+// ---------------------------------------------------------------------------------------------
+__global__ void embed_copy_kernel(bf16_t* __restrict__ embeds, const int32_t* __restrict__ ids, int n, int H,
+                                  bf16_t* __restrict__ buf, int to_pool) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 16-byte piece
+  int per_row = H / 8;
+  if (idx >= (int64_t)n * per_row) return;
+  int r = (int)(idx / per_row), c = (int)(idx % per_row) * 8;
+  bf16_t* p = embeds + (int64_t)ids[r] * H + c;
+  bf16_t* b = buf + (int64_t)r * H + c;
+  if (to_pool) *reinterpret_cast<u32x4*>(p) = *reinterpret_cast<const u32x4*>(b);
+  else *reinterpret_cast<u32x4*>(b) = *reinterpret_cast<const u32x4*>(p);
+}
+
+hipError_t launch_embed_copy(bf16_t* embeds, const int32_t* ids, int n, int H, bf16_t* buf, int to_pool,
+                             hipStream_t s) {
+  int64_t total = (int64_t)n * (H / 8);
+  if (total <= 0) return hipSuccess;
+  embed_copy_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(embeds, ids, n, H, buf, to_pool);
+  return hipGetLastError();
+}
+
+__global__ void kv_copy_kernel(bf16_t* __restrict__ kv_layer, const int32_t* __restrict__ pages,
+                               const int32_t* __restrict__ slots, int n, int Hkv, int D, bf16_t* __restrict__ k,
+                               bf16_t* __restrict__ v, int to_pool) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one (token, head, d) element
+  int64_t total = (int64_t)n * Hkv * D;
+  if (idx >= total) return;
+  int d = (int)(idx % D);
+  int h = (int)((idx / D) % Hkv);
+  int i = (int)(idx / ((int64_t)D * Hkv));
+  uint16_t* blk = reinterpret_cast<uint16_t*>(kv_layer + ((int64_t)pages[i] * Hkv + h) * (2 * PAGE * D));
+  uint16_t* kk = reinterpret_cast<uint16_t*>(k);
+  uint16_t* vv = reinterpret_cast<uint16_t*>(v);
+  int ko = k_elem_offset(slots[i], d), vo = v_elem_offset(slots[i], d, D);
+  if (to_pool) {
+    blk[ko] = kk[idx];
+    blk[vo] = vv[idx];
+  } else {
+    kk[idx] = blk[ko];
+    vv[idx] = blk[vo];
+  }
+}
+
+hipError_t launch_kv_copy(bf16_t* kv_layer, const int32_t* pages, const int32_t* slots, int n, int Hkv, int D,
+                          bf16_t* k, bf16_t* v, int to_pool, hipStream_t s) {
+  int64_t total = (int64_t)n * Hkv * D;
+  if (total <= 0) return hipSuccess;
+  kv_copy_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(kv_layer, pages, slots, n, Hkv, D, k, v,
+                                                                               to_pool);
+  return hipGetLastError();
+}

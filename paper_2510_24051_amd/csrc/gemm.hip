@@ -1,0 +1,372 @@
+// bf16 MFMA GEMMs  C[M, N] = A[M, K] x W[N, K]^T  with fused epilogues.
+//
+//   gemm_skinny : M <= 256 (decode batches, LM head).  HBM-bound on the weight stream: every wave owns one
+//                 32-column block of W and reads its tiles straight from global memory into MFMA B operands
+//                 (each load is 1 KiB contiguous thanks to the tiled weight layout); the activation tile is
+//                 shared by the workgroup through LDS.  K is split across gridDim.y when N alone gives too
+//                 few workgroups; partial sums go to a workspace and a second kernel applies the epilogue.
+//   gemm_large  : M > 256 (prefill).  MFMA-bound: 256x256x64 workgroup tile, 8 waves of 128x64, LDS double
+//                 buffering, swizzled A tile, W tile kept in operand order.
+#include <type_traits>
+
+#include "internal.h"
+
+// ------------------------------------------------------------------------------------------------
+// epilogue on one 32x32 accumulator tile (rows m0.., columns n0..), see mfma32 for the lane layout
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+template <int MODE>
+__device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, const f32x16& acc2, int m0, int n0,
+                                         int M, int N, int lane) {
+  const int n = n0 + (lane & 31);
+  const int g = lane >> 5;
+  if (n >= N) return;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int m = m0 + (v >> 2) * 8 + g * 4 + (v & 3);
+    if (m >= M) continue;
+    const float x = acc[v];
+    if (MODE == EPI_STORE_BF16) {
+      reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + n] = f32_to_bf16(x);
+    } else if (MODE == EPI_STORE_F32) {
+      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + n] = x;
+    } else if (MODE == EPI_RESID_EMBED) {
+      float r = bf16_to_f32(e.embeds[(int64_t)e.ids[m] * e.H + n]);
+      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + n] = r + x;
+    } else if (MODE == EPI_RESID_OUT) {
+      int id = e.ids[m];
+      if (id >= 0) e.embeds[(int64_t)id * e.H + n] = f32_to_bf16(e.resid[(int64_t)m * e.H + n] + x);
+    } else if (MODE == EPI_SWIGLU) {  // acc = gate block, acc2 = up block; n0 is the gate block's packed column
+      const int nc = (n0 >> 1) + (lane & 31);
+      reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + nc] = f32_to_bf16(silu_f(x) * acc2[v]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// gemm_skinny
+// ------------------------------------------------------------------------------------------------
+#define SK_BK 128  // contraction elements per main-loop iteration (8 MFMA steps)
+
+template <int MB, int MODE, bool PARTIAL>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restrict__ A, int lda, int M,
+                                                          const bf16_t* __restrict__ Wp, int N, int NB, int K,
+                                                          int iters_per_split, EpiArgs epi, float* __restrict__ part) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);  // [2][MB*32][SK_BK], 16-byte chunks swizzled by row
+  constexpr int BM = MB * 32;
+  constexpr int A_ELEMS = BM * SK_BK;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int KB = K / 16;
+  const int total_iters = (K + SK_BK - 1) / SK_BK;
+  const int it0 = blockIdx.y * iters_per_split;
+  const int it1 = min(total_iters, it0 + iters_per_split);
+  // SWIGLU waves own a gate/up block pair; other modes one block per wave
+  constexpr int NBW = (MODE == EPI_SWIGLU) ? 2 : 1;
+  int nb0 = (blockIdx.x * 4 + wave) * NBW;
+  const bool wave_active = nb0 < NB;
+  if (!wave_active) nb0 = 0;  // keep loads in bounds; results are dropped
+
+  f32x16 acc[NBW][MB];
+#pragma unroll
+  for (int j = 0; j < NBW; ++j)
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
+
+  // A tile loader: BM rows x 16 chunks (16 B) per iteration; chunk c of row r is stored at chunk (c ^ (r & 15))
+  constexpr int A_CHUNKS = BM * 16;
+  constexpr int A_PER_THREAD = (A_CHUNKS + 255) / 256;
+  u32x4 areg[A_PER_THREAD];
+  auto load_a = [&](int it) {
+#pragma unroll
+    for (int j = 0; j < A_PER_THREAD; ++j) {
+      int c = tid + j * 256;
+      int r = c >> 4, kc = c & 15;
+      int k = it * SK_BK + kc * 8;
+      u32x4 v = {0, 0, 0, 0};
+      if (c < A_CHUNKS && r < M && k < K) v = *reinterpret_cast<const u32x4*>(A + (int64_t)r * lda + k);
+      areg[j] = v;
+    }
+  };
+  auto store_a = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < A_PER_THREAD; ++j) {
+      int c = tid + j * 256;
+      int r = c >> 4, kc = c & 15;
+      if (c < A_CHUNKS) *reinterpret_cast<u32x4*>(As + buf * A_ELEMS + r * SK_BK + ((kc ^ (r & 15)) << 3)) = areg[j];
+    }
+  };
+  bf16x8 breg[2][NBW][8];
+  auto load_b = [&](int it, const int slot) {
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        int kb = it * 8 + s;
+        kb = kb < KB ? kb : KB - 1;  // tail steps read a valid tile; their A operand is zero
+        breg[slot][j][s] = *reinterpret_cast<const bf16x8*>(Wp + packed_tile_offset(nb0 + j, kb, KB) + lane * 8);
+      }
+  };
+
+  // one main-loop iteration; SLOT is the register set holding this iteration's W operands (compile-time so
+  // the operand arrays stay in registers)
+  auto step = [&](auto slot_c, int it) {
+    constexpr int SLOT = decltype(slot_c)::value;
+    const int cur = (it - it0) & 1;
+    const bool more = it + 1 < it1;
+    if (more) {
+      load_a(it + 1);
+      load_b(it + 1, SLOT ^ 1);
+    }
+    const bf16_t* Ab = As + cur * A_ELEMS;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int kc = s * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        const int r = i * 32 + (lane & 31);
+        bf16x8 af = *reinterpret_cast<const bf16x8*>(Ab + r * SK_BK + ((kc ^ (r & 15)) << 3));
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) acc[j][i] = mfma32(af, breg[SLOT][j][s], acc[j][i]);
+      }
+    }
+    if (more) store_a(cur ^ 1);
+    __syncthreads();
+  };
+  if (it0 < it1) {
+    load_a(it0);
+    load_b(it0, 0);
+    store_a(0);
+  }
+  __syncthreads();
+  for (int it = it0; it < it1; it += 2) {
+    step(std::integral_constant<int, 0>{}, it);
+    if (it + 1 < it1) step(std::integral_constant<int, 1>{}, it + 1);
+  }
+  if (!wave_active) return;
+  if (PARTIAL) {
+    // raw partial sums: part[split][m][n_packed]
+    float* P = part + (int64_t)blockIdx.y * M * (NB * 32);
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          int m = i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          if (m < M) P[(int64_t)m * (NB * 32) + (nb0 + j) * 32 + (lane & 31)] = acc[j][i][v];
+        }
+  } else {
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      if (MODE == EPI_SWIGLU) epi_tile<MODE>(epi, acc[0][i], acc[NBW - 1][i], i * 32, nb0 * 32, M, NB * 32, lane);
+      else epi_tile<MODE>(epi, acc[0][i], acc[0][i], i * 32, nb0 * 32, M, N, lane);
+    }
+  }
+}
+
+// Sum split-K partials and apply the epilogue.  One thread per output element (SWIGLU: per gate/up pair).
+template <int MODE>
+__global__ void splitk_epilogue_kernel(const float* __restrict__ part, int splits, int M, int N, int NP, EpiArgs e) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int cols = (MODE == EPI_SWIGLU) ? NP / 2 : N;
+  if (idx >= (int64_t)M * cols) return;
+  int m = (int)(idx / cols), c = (int)(idx % cols);
+  auto total = [&](int n) {
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += part[((int64_t)k * M + m) * NP + n];
+    return s;
+  };
+  if (MODE == EPI_SWIGLU) {
+    int ng = (c >> 5) * 64 + (c & 31);  // gate column in packed order; up column is 32 further
+    reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + c] = f32_to_bf16(silu_f(total(ng)) * total(ng + 32));
+  } else {
+    float x = total(c);
+    if (MODE == EPI_STORE_BF16) reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + c] = f32_to_bf16(x);
+    else if (MODE == EPI_STORE_F32) reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = x;
+    else if (MODE == EPI_RESID_EMBED)
+      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = bf16_to_f32(e.embeds[(int64_t)e.ids[m] * e.H + c]) + x;
+    else if (MODE == EPI_RESID_OUT) {
+      int id = e.ids[m];
+      if (id >= 0) e.embeds[(int64_t)id * e.H + c] = f32_to_bf16(e.resid[(int64_t)m * e.H + c] + x);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// gemm_large
+// ------------------------------------------------------------------------------------------------
+#define LG_BM 256
+#define LG_BN 256
+#define LG_BK 64
+
+template <int MODE>
+__global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restrict__ A, int lda, int M,
+                                                         const bf16_t* __restrict__ Wp, int N, int NB, int K,
+                                                         EpiArgs epi) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);       // [2][256 rows][64], chunk c of row r at c ^ (r & 7)
+  bf16_t* Bs = As + 2 * LG_BM * LG_BK;                    // [2][8 blocks][4 k-steps][512], operand order
+  constexpr int TILE = LG_BM * LG_BK;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;  // wave tile: rows wm*128.., columns wn*64..
+  const int KB = K / 16;
+  const int m0 = blockIdx.y * LG_BM;
+  const int nb0 = blockIdx.x * (LG_BN / 32);
+  const int KT = (K + LG_BK - 1) / LG_BK;
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  u32x4 ra[4], rb[4];
+  auto load_g = [&](int kt) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int c = tid + j * 512;
+      int r = c >> 3, kc = c & 7;
+      int gr = m0 + r;
+      gr = gr < M ? gr : M - 1;  // rows past M read a valid row; their results are never stored
+      int k = kt * LG_BK + kc * 8;
+      u32x4 v = {0, 0, 0, 0};
+      if (k < K) v = *reinterpret_cast<const u32x4*>(A + (int64_t)gr * lda + k);
+      ra[j] = v;
+      // W: chunk c -> block c / 256, 16-byte piece c % 256 of that block's 4 consecutive k-tiles
+      int nbl = c >> 8, w = c & 255;
+      int nb = nb0 + nbl;
+      nb = nb < NB ? nb : NB - 1;
+      int kb = kt * 4 + (w >> 6);
+      u32x4 wv = {0, 0, 0, 0};
+      if (kb < KB) wv = *reinterpret_cast<const u32x4*>(Wp + packed_tile_offset(nb, kb, KB) + (w & 63) * 8);
+      rb[j] = wv;
+    }
+  };
+  auto store_s = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int c = tid + j * 512;
+      int r = c >> 3, kc = c & 7;
+      *reinterpret_cast<u32x4*>(As + buf * TILE + r * LG_BK + ((kc ^ (r & 7)) << 3)) = ra[j];
+      *reinterpret_cast<u32x4*>(Bs + buf * TILE + c * 8) = rb[j];
+    }
+  };
+
+  load_g(0);
+  store_s(0);
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = kt & 1;
+    const bool more = kt + 1 < KT;
+    if (more) load_g(kt + 1);
+    const bf16_t* Ab = As + cur * TILE;
+    const bf16_t* Bb = Bs + cur * TILE;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      bf16x8 af[4], bfr[2];
+      const int kc = s * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = wm * 128 + i * 32 + (lane & 31);
+        af[i] = *reinterpret_cast<const bf16x8*>(Ab + r * LG_BK + ((kc ^ (r & 7)) << 3));
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(Bb + ((wn * 2 + j) * 4 + s) * 512 + lane * 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(af[i], bfr[j], acc[i][j]);
+    }
+    if (more) store_s(cur ^ 1);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int mt = m0 + wm * 128 + i * 32;
+    if (MODE == EPI_SWIGLU) {
+      int nb = nb0 + wn * 2;
+      if (nb < NB) epi_tile<MODE>(epi, acc[i][0], acc[i][1], mt, nb * 32, M, NB * 32, lane);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        int nb = nb0 + wn * 2 + j;
+        if (nb < NB) epi_tile<MODE>(epi, acc[i][j], acc[i][j], mt, nb * 32, M, N, lane);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dispatch
+// ------------------------------------------------------------------------------------------------
+template <int MB, int MODE>
+static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
+                             size_t ws_elems, hipStream_t s) {
+  constexpr int NBW = (MODE == EPI_SWIGLU) ? 2 : 1;
+  const int wg_n = (W.NB + 4 * NBW - 1) / (4 * NBW);
+  const int total_iters = (W.K + SK_BK - 1) / SK_BK;
+  int splits = 1;
+  const int target_wgs = 512;
+  if (wg_n < target_wgs) splits = (target_wgs + wg_n - 1) / wg_n;
+  if (splits > total_iters / 2) splits = total_iters / 2;
+  if (splits < 1) splits = 1;
+  const int NP = W.NB * 32;
+  while (splits > 1 && (size_t)splits * M * NP > ws_elems) --splits;
+  int ips = (total_iters + splits - 1) / splits;
+  splits = (total_iters + ips - 1) / ips;
+  size_t smem = (size_t)2 * MB * 32 * SK_BK * sizeof(bf16_t);
+  dim3 grid(wg_n, splits), block(256);
+  if (splits == 1) {
+    auto kern = gemm_skinny_kernel<MB, MODE, false>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, nullptr);
+    return hipGetLastError();
+  }
+  auto kern = gemm_skinny_kernel<MB, MODE, true>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, ws);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int cols = (MODE == EPI_SWIGLU) ? NP / 2 : W.N;
+  int64_t total = (int64_t)M * cols;
+  splitk_epilogue_kernel<MODE><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(ws, splits, M, W.N, NP, epi);
+  return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
+                           size_t ws_elems, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (M <= 32) return run_skinny<1, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
+  if (M <= 64) return run_skinny<2, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
+  if (M <= 128) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
+  if (M <= 256 && MODE != EPI_SWIGLU) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
+  auto kern = gemm_large_kernel<MODE>;
+  size_t smem = (size_t)4 * LG_BM * LG_BK * sizeof(bf16_t);
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  dim3 grid((W.NB + 7) / 8, (M + LG_BM - 1) / LG_BM), block(512);
+  kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, epi);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* splitk_ws,
+                       size_t splitk_elems, hipStream_t s) {
+  switch (epi.mode) {
+    case EPI_STORE_BF16: return run_mode<EPI_STORE_BF16>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
+    case EPI_RESID_EMBED: return run_mode<EPI_RESID_EMBED>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
+    case EPI_SWIGLU: return run_mode<EPI_SWIGLU>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
+    case EPI_RESID_OUT: return run_mode<EPI_RESID_OUT>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
+    case EPI_STORE_F32: return run_mode<EPI_STORE_F32>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
+  }
+  return hipErrorInvalidValue;
+}

@@ -1,0 +1,154 @@
+// Internal structures and kernel launchers shared by the translation units of libpie_mi355.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/pie_mi355.h"
+#include "common.h"
+
+#define PAGE 16  // tokens per KvPage the kernels are built for
+
+// ---- tiled weights ---------------------------------------------------------------------------
+struct PackedWeight {
+  bf16_t* data = nullptr;
+  int N = 0;   // logical output rows
+  int K = 0;   // inputs (multiple of 16)
+  int NB = 0;  // number of 32-row blocks stored (N rounded up)
+};
+
+struct LayerWeights {
+  bool loaded = false;
+  bf16_t* g1 = nullptr;
+  bf16_t* g2 = nullptr;
+  PackedWeight wqkv, wo, wgu, wdown;  // wgu: gate/up interleaved in 32-row blocks
+};
+
+// ---- KvPage pool layout ----------------------------------------------------------------------
+// pool[layer][page][kv_head] is one block of 2 * PAGE * D bf16: a K part then a V part, both arranged
+// so that one 16-byte load per lane is an mfma32 A operand.
+//   K(token t, d): (d/16)*256 + ((d%16)/8)*128 + swap23(t)*8 + d%8      swap23 exchanges bits 2 and 3 of t
+//   V(token t, d): PAGE*D + (d/32)*512 + (t/8)*256 + (d%32)*8 + t%8
+__host__ __device__ __forceinline__ int swap23(int t) { return (t & 3) | ((t & 4) << 1) | ((t & 8) >> 1); }
+__host__ __device__ __forceinline__ int k_elem_offset(int t, int d) {
+  return (d >> 4) * 256 + ((d >> 3) & 1) * 128 + swap23(t) * 8 + (d & 7);
+}
+__host__ __device__ __forceinline__ int v_elem_offset(int t, int d, int D) {
+  return PAGE * D + (d >> 5) * 512 + (t >> 3) * 256 + (d & 31) * 8 + (t & 7);
+}
+
+// ---- batch plan ------------------------------------------------------------------------------
+struct ReqInfo {       // one per request, device + host
+  int32_t tok0;        // first token
+  int32_t n_new;       // new tokens
+  int32_t kv_len;      // after append
+  int32_t visit0;      // first entry of this request's visit list
+  int32_t n_visit;     // pages with at least one visible key, logical order
+  int32_t wpr;         // mask words per row (0: inferred causal)
+  int64_t mask_off;    // word offset of the request's first row
+  int32_t item0;       // first decode work item (decode path) or -1
+  int32_t n_items;     // decode work items (split-K chunks)
+};
+
+struct DecodeItem { int32_t r, v0, v1, pad; };   // visit-list range [v0, v1) of request r (absolute indices)
+struct PrefillItem { int32_t r, qb; };           // query block qb (32 tokens) of request r
+
+struct pie_batch {
+  int32_t R = 0, T = 0;
+  void* dev_blob = nullptr;  // single allocation holding every array below
+  int32_t *in_ids = nullptr, *out_ids = nullptr, *pos = nullptr, *tok_page = nullptr, *tok_slot = nullptr;
+  int32_t *visit_phys = nullptr, *visit_logical = nullptr;
+  uint32_t* mask_words = nullptr;
+  ReqInfo* reqs = nullptr;
+  DecodeItem* ditems = nullptr;
+  PrefillItem* pitems = nullptr;
+  int32_t* dec_reqs = nullptr;  // request indices on the decode path
+  int32_t n_ditems = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
+  float* part_o = nullptr;   // [n_ditems * Hkv * rows_cap, D]
+  float* part_ml = nullptr;  // [n_ditems * Hkv * rows_cap, 2]
+  int64_t work[4] = {0, 0, 0, 0};
+};
+
+struct pie_ctx {
+  pie_model_desc m;
+  pie_pool_desc p;
+  hipStream_t stream = nullptr;
+  int device = 0;
+  bf16_t* embeds = nullptr;
+  bf16_t* kv = nullptr;
+  size_t kv_layer_elems = 0;
+  std::vector<LayerWeights> layers;
+  bool head_loaded = false;
+  bf16_t* g_final = nullptr;
+  PackedWeight wlm;
+  double* inv_freq = nullptr;
+  // workspace
+  bf16_t *xn = nullptr, *qkv = nullptr, *attn = nullptr, *act = nullptr, *en = nullptr;
+  float *h = nullptr, *splitk = nullptr, *logits = nullptr;
+  size_t splitk_elems = 0;
+  int32_t* ids_dev = nullptr;  // staging for id lists of the small resource calls
+  size_t ids_cap = 0;
+  int last_T = 0, last_dist_n = 0;
+  // timing
+  bool timing = false;
+  hipEvent_t ev[2 * PIE_N_STAGES];
+  bool ev_used[PIE_N_STAGES];
+  char err[512];
+};
+
+// ---- launchers (all enqueue on `s`, return hipGetLastError) ------------------------------------
+hipError_t launch_pack_weight(const bf16_t* s0, int r0, const bf16_t* s1, int r1, const bf16_t* s2, int r2, int K,
+                              int interleave, bf16_t* dst, int NB, hipStream_t s);
+hipError_t launch_rmsnorm_embed(const bf16_t* embeds, const int32_t* ids, const bf16_t* gain, bf16_t* out, int rows,
+                                int H, float eps, hipStream_t s);
+hipError_t launch_rmsnorm_f32(const float* x, const bf16_t* gain, bf16_t* out, int rows, int H, float eps,
+                              hipStream_t s);
+hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const int32_t* pos, const int32_t* tok_page,
+                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, hipStream_t s);
+hipError_t launch_embed_copy(bf16_t* embeds, const int32_t* ids, int n, int H, bf16_t* buf, int to_pool,
+                             hipStream_t s);
+hipError_t launch_kv_copy(bf16_t* kv_layer, const int32_t* pages, const int32_t* slots, int n, int Hkv, int D,
+                          bf16_t* k, bf16_t* v, int to_pool, hipStream_t s);
+
+enum EpiMode {
+  EPI_STORE_BF16 = 0,    // out bf16 [M, N]
+  EPI_RESID_EMBED = 1,   // out fp32 [M, N] = embeds[in_ids[m]][n] + acc
+  EPI_SWIGLU = 2,        // out bf16 [M, N/2] = silu(gate) * up, gate/up interleaved in 32-column blocks
+  EPI_RESID_OUT = 3,     // embeds[out_ids[m]][n] = bf16(resid[m][n] + acc) when out_ids[m] >= 0
+  EPI_STORE_F32 = 4      // out fp32 [M, N]
+};
+struct EpiArgs {
+  int mode;
+  void* out;
+  int ldo;
+  bf16_t* embeds;
+  const int32_t* ids;
+  const float* resid;
+  int H;
+};
+// C[M, N] = A[M, K] (bf16 row-major, leading dimension lda) x W^T with the epilogue above.
+hipError_t launch_gemm(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* splitk_ws,
+                       size_t splitk_elems, hipStream_t s);
+
+struct AttnArgs {
+  const bf16_t* q;   // [T, q_stride] rotated queries
+  int q_stride;
+  const bf16_t* kv;  // layer pool
+  bf16_t* out;       // [T, Hq * D]
+  int Hq, Hkv, D;
+  float scale_log2;  // log2(e) / sqrt(D)
+  const ReqInfo* reqs;
+  const int32_t* visit_phys;
+  const int32_t* visit_logical;
+  const uint32_t* mask_words;
+};
+hipError_t launch_attn_decode(const AttnArgs& a, const DecodeItem* items, int n_items, int rows_cap, float* part_o,
+                              float* part_ml, hipStream_t s);
+hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, int rows_cap,
+                             const float* part_o, const float* part_ml, hipStream_t s);
+hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s);
+
+hipError_t launch_topk(const float* logits, int n, int V, int k, float inv_temp, int32_t* out_ids, float* out_probs,
+                       hipStream_t s);

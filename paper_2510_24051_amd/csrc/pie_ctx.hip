@@ -1,0 +1,647 @@
+// C ABI of libpie_mi355: context, resource pools, batch deserialisation and the per-layer launch sequence.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <unordered_set>
+
+#include "internal.h"
+
+static char g_create_err[512] = "";
+
+static pie_status fail(pie_ctx* ctx, pie_status code, const char* fmt, ...) {
+  char* dst = ctx ? ctx->err : g_create_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 512, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                          \
+  do {                                                                                              \
+    hipError_t _e = (expr);                                                                         \
+    if (_e != hipSuccess)                                                                           \
+      return fail(ctx, _e == hipErrorOutOfMemory ? PIE_ENOMEM : PIE_EHIP, "%s: %s", #expr, hipGetErrorString(_e)); \
+  } while (0)
+
+extern "C" const char* pie_last_error(const pie_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
+
+// ---------------------------------------------------------------------------------------------
+// create / destroy
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+static hipError_t dev_alloc(T** p, size_t elems, bool zero, hipStream_t s) {
+  *p = nullptr;
+  if (elems == 0) return hipSuccess;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(p), elems * sizeof(T));
+  if (e != hipSuccess) return e;
+  if (zero) e = hipMemsetAsync(*p, 0, elems * sizeof(T), s);
+  return e;
+}
+
+static int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p, void* hip_stream, pie_ctx** out) {
+  if (!m || !p || !out) return fail(nullptr, PIE_EINVAL, "pie_create: null argument");
+  *out = nullptr;
+  if (m->page_size != PAGE) return fail(nullptr, PIE_EUNSUPPORTED, "page_size %d: kernels are built for %d", m->page_size, PAGE);
+  if (m->head_dim != 64 && m->head_dim != 128) return fail(nullptr, PIE_EUNSUPPORTED, "head_dim %d: need 64 or 128", m->head_dim);
+  if (m->n_kv_heads <= 0 || m->n_q_heads % m->n_kv_heads != 0 || m->n_q_heads / m->n_kv_heads > 8)
+    return fail(nullptr, PIE_EUNSUPPORTED, "need n_q_heads = group * n_kv_heads with group <= 8");
+  if (m->hidden <= 0 || m->hidden % 32 || m->mlp_dim <= 0 || m->mlp_dim % 32 || m->vocab < 0 || m->vocab % 32 ||
+      m->hidden > 8192)
+    return fail(nullptr, PIE_EUNSUPPORTED, "hidden (<= 8192), mlp_dim and vocab must be multiples of 32");
+  if (m->n_layers <= 0 || !(m->rms_eps > 0.f) || !(m->rope_theta > 0.f))
+    return fail(nullptr, PIE_EINVAL, "n_layers, rms_eps and rope_theta must be positive");
+  if (p->n_kv_pages <= 0 || p->n_embeds <= 0 || p->max_batch_tokens <= 0 || p->max_batch_requests <= 0 ||
+      p->max_top_k < 0 || p->max_dist_rows < 0 || p->max_top_k > 1024)
+    return fail(nullptr, PIE_EINVAL, "pool sizes must be positive (max_top_k <= 1024)");
+
+  pie_ctx* c = new pie_ctx();
+  c->m = *m;
+  c->p = *p;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  c->err[0] = 0;
+  for (int i = 0; i < PIE_N_STAGES; ++i) c->ev_used[i] = false;
+  for (int i = 0; i < 2 * PIE_N_STAGES; ++i) c->ev[i] = nullptr;
+  hipError_t e = hipGetDevice(&c->device);
+  const int H = m->hidden, QD = m->n_q_heads * m->head_dim, KD = m->n_kv_heads * m->head_dim, I = m->mlp_dim;
+  const size_t T = (size_t)p->max_batch_tokens;
+  c->layers.resize(m->n_layers);
+  c->kv_layer_elems = (size_t)p->n_kv_pages * m->n_kv_heads * 2 * PAGE * m->head_dim;
+  auto chk = [&](hipError_t x) { if (e == hipSuccess) e = x; };
+  chk(dev_alloc(&c->embeds, (size_t)p->n_embeds * H, true, c->stream));
+  chk(dev_alloc(&c->kv, c->kv_layer_elems * m->n_layers, true, c->stream));
+  chk(dev_alloc(&c->xn, T * H, false, c->stream));
+  chk(dev_alloc(&c->qkv, T * (QD + 2 * KD), false, c->stream));
+  chk(dev_alloc(&c->attn, T * QD, false, c->stream));
+  chk(dev_alloc(&c->h, T * H, false, c->stream));
+  chk(dev_alloc(&c->act, T * I, false, c->stream));
+  // split-K workspace: only batches of <= 256 rows use it; 8 partial copies of the widest output
+  {
+    size_t rows = std::min<size_t>(std::max<size_t>(T, (size_t)p->max_dist_rows), 256);
+    size_t widest = std::max<size_t>((size_t)2 * I, (size_t)round_up(std::max(QD + 2 * KD, H), 32));
+    c->splitk_elems = rows * widest * 8;
+    chk(dev_alloc(&c->splitk, c->splitk_elems, false, c->stream));
+  }
+  if (m->vocab > 0 && p->max_dist_rows > 0) {
+    chk(dev_alloc(&c->logits, (size_t)p->max_dist_rows * m->vocab, false, c->stream));
+    chk(dev_alloc(&c->en, (size_t)p->max_dist_rows * H, false, c->stream));
+  }
+  c->ids_cap = std::max<size_t>(4096, 2 * T);
+  chk(dev_alloc(&c->ids_dev, c->ids_cap, false, c->stream));
+  chk(dev_alloc(&c->inv_freq, (size_t)m->head_dim / 2, false, c->stream));
+  if (e == hipSuccess) {
+    std::vector<double> f(m->head_dim / 2);
+    for (int i = 0; i < m->head_dim / 2; ++i) f[i] = std::pow((double)m->rope_theta, -2.0 * i / m->head_dim);
+    chk(hipMemcpyAsync(c->inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice, c->stream));
+    chk(hipStreamSynchronize(c->stream));
+  }
+  for (int i = 0; i < 2 * PIE_N_STAGES && e == hipSuccess; ++i) chk(hipEventCreate(&c->ev[i]));
+  if (e != hipSuccess) {
+    pie_status st = fail(nullptr, e == hipErrorOutOfMemory ? PIE_ENOMEM : PIE_EHIP, "pie_create: %s", hipGetErrorString(e));
+    pie_destroy(c);
+    return st;
+  }
+  *out = c;
+  return PIE_OK;
+}
+
+static void free_packed(PackedWeight& w) {
+  if (w.data) (void)hipFree(w.data);
+  w = PackedWeight();
+}
+
+extern "C" pie_status pie_destroy(pie_ctx* c) {
+  if (!c) return PIE_OK;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& L : c->layers) {
+    if (L.g1) (void)hipFree(L.g1);
+    if (L.g2) (void)hipFree(L.g2);
+    free_packed(L.wqkv); free_packed(L.wo); free_packed(L.wgu); free_packed(L.wdown);
+  }
+  free_packed(c->wlm);
+  void* bufs[] = {c->embeds, c->kv, c->xn, c->qkv, c->attn, c->h, c->act, c->splitk, c->logits, c->en,
+                  c->ids_dev, c->inv_freq, c->g_final};
+  for (void* b : bufs) if (b) (void)hipFree(b);
+  for (int i = 0; i < 2 * PIE_N_STAGES; ++i) if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  delete c;
+  return PIE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// weights
+// ---------------------------------------------------------------------------------------------
+static pie_status pack_into(pie_ctx* c, PackedWeight& w, int N, int K, const void* s0, int r0, const void* s1, int r1,
+                            const void* s2, int r2, int interleave) {
+  free_packed(w);
+  w.N = N;
+  w.K = K;
+  w.NB = (N + 31) / 32;
+  HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&w.data), (size_t)w.NB * 32 * K * sizeof(bf16_t)));
+  HIP_TRY(c, launch_pack_weight((const bf16_t*)s0, r0, (const bf16_t*)s1, r1, (const bf16_t*)s2, r2, K, interleave,
+                                w.data, w.NB, c->stream));
+  return PIE_OK;
+}
+
+static pie_status copy_gain(pie_ctx* c, bf16_t** dst, const void* src, int H) {
+  if (!*dst) HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(dst), (size_t)H * sizeof(bf16_t)));
+  HIP_TRY(c, hipMemcpyAsync(*dst, src, (size_t)H * sizeof(bf16_t), hipMemcpyDeviceToDevice, c->stream));
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_load_layer(pie_ctx* c, int32_t layer, const void* g1, const void* wq, const void* wk,
+                                     const void* wv, const void* wo, const void* g2, const void* wgate,
+                                     const void* wup, const void* wdown) {
+  if (!c) return PIE_EINVAL;
+  if (!g1 || !wq || !wk || !wv || !wo || !g2 || !wgate || !wup || !wdown) return fail(c, PIE_EINVAL, "pie_load_layer: null weight");
+  if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "pie_load_layer: layer %d of %d", layer, c->m.n_layers);
+  const int H = c->m.hidden, QD = c->m.n_q_heads * c->m.head_dim, KD = c->m.n_kv_heads * c->m.head_dim, I = c->m.mlp_dim;
+  LayerWeights& L = c->layers[layer];
+  L.loaded = false;
+  pie_status st;
+  if ((st = copy_gain(c, &L.g1, g1, H)) != PIE_OK) return st;
+  if ((st = copy_gain(c, &L.g2, g2, H)) != PIE_OK) return st;
+  if ((st = pack_into(c, L.wqkv, QD + 2 * KD, H, wq, QD, wk, KD, wv, KD, 0)) != PIE_OK) return st;
+  if ((st = pack_into(c, L.wo, H, QD, wo, H, nullptr, 0, nullptr, 0, 0)) != PIE_OK) return st;
+  if ((st = pack_into(c, L.wgu, 2 * I, H, wgate, I, wup, I, nullptr, 0, 1)) != PIE_OK) return st;
+  if ((st = pack_into(c, L.wdown, H, I, wdown, H, nullptr, 0, nullptr, 0, 0)) != PIE_OK) return st;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  L.loaded = true;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_load_head(pie_ctx* c, const void* g_final, const void* w_lm) {
+  if (!c) return PIE_EINVAL;
+  if (!w_lm) return fail(c, PIE_EINVAL, "pie_load_head: null weight");
+  if (c->m.vocab <= 0 || !c->logits) return fail(c, PIE_EINVAL, "pie_load_head: context created without vocab / dist rows");
+  c->head_loaded = false;
+  pie_status st;
+  if (g_final) {
+    if ((st = copy_gain(c, &c->g_final, g_final, c->m.hidden)) != PIE_OK) return st;
+  } else if (c->g_final) {
+    (void)hipFree(c->g_final);
+    c->g_final = nullptr;
+  }
+  if ((st = pack_into(c, c->wlm, c->m.vocab, c->m.hidden, w_lm, c->m.vocab, nullptr, 0, nullptr, 0, 0)) != PIE_OK) return st;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->head_loaded = true;
+  return PIE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// resource seeding / inspection
+// ---------------------------------------------------------------------------------------------
+static pie_status stage_ids(pie_ctx* c, const int32_t* a, const int32_t* b, int n) {
+  if ((size_t)n * (b ? 2 : 1) > c->ids_cap) {
+    (void)hipStreamSynchronize(c->stream);
+    if (c->ids_dev) (void)hipFree(c->ids_dev);
+    c->ids_dev = nullptr;
+    c->ids_cap = (size_t)n * 2;
+    HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&c->ids_dev), c->ids_cap * sizeof(int32_t)));
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->ids_dev, a, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+  if (b) HIP_TRY(c, hipMemcpyAsync(c->ids_dev + n, b, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+  return PIE_OK;
+}
+
+static pie_status embed_copy(pie_ctx* c, const int32_t* ids, int32_t n, void* buf, int to_pool) {
+  if (!c) return PIE_EINVAL;
+  if (n < 0 || (n > 0 && (!ids || !buf))) return fail(c, PIE_EINVAL, "embed copy: null argument");
+  if (n == 0) return PIE_OK;
+  for (int i = 0; i < n; ++i)
+    if (ids[i] < 0 || ids[i] >= c->p.n_embeds) return fail(c, PIE_ERANGE, "embed id %d at %d outside [0, %d)", ids[i], i, c->p.n_embeds);
+  pie_status st = stage_ids(c, ids, nullptr, n);
+  if (st != PIE_OK) return st;
+  HIP_TRY(c, launch_embed_copy(c->embeds, c->ids_dev, n, c->m.hidden, (bf16_t*)buf, to_pool, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));  // ids_dev is reused by the next call
+  return PIE_OK;
+}
+extern "C" pie_status pie_embed_write(pie_ctx* c, const int32_t* ids, int32_t n, const void* src) {
+  return embed_copy(c, ids, n, const_cast<void*>(src), 1);
+}
+extern "C" pie_status pie_embed_read(pie_ctx* c, const int32_t* ids, int32_t n, void* dst) {
+  return embed_copy(c, ids, n, dst, 0);
+}
+
+static pie_status kv_copy(pie_ctx* c, int32_t layer, const int32_t* pages, const int32_t* slots, int32_t n, void* k,
+                          void* v, int to_pool) {
+  if (!c) return PIE_EINVAL;
+  if (n < 0 || (n > 0 && (!pages || !slots || !k || !v))) return fail(c, PIE_EINVAL, "kv copy: null argument");
+  if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "kv copy: layer %d of %d", layer, c->m.n_layers);
+  if (n == 0) return PIE_OK;
+  for (int i = 0; i < n; ++i) {
+    if (pages[i] < 0 || pages[i] >= c->p.n_kv_pages) return fail(c, PIE_ERANGE, "page id %d at %d outside [0, %d)", pages[i], i, c->p.n_kv_pages);
+    if (slots[i] < 0 || slots[i] >= PAGE) return fail(c, PIE_ERANGE, "slot %d at %d outside [0, %d)", slots[i], i, PAGE);
+  }
+  pie_status st = stage_ids(c, pages, slots, n);
+  if (st != PIE_OK) return st;
+  HIP_TRY(c, launch_kv_copy(c->kv + (size_t)layer * c->kv_layer_elems, c->ids_dev, c->ids_dev + n, n, c->m.n_kv_heads,
+                            c->m.head_dim, (bf16_t*)k, (bf16_t*)v, to_pool, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PIE_OK;
+}
+extern "C" pie_status pie_kv_write(pie_ctx* c, int32_t layer, const int32_t* pages, const int32_t* slots, int32_t n,
+                                   const void* k, const void* v) {
+  return kv_copy(c, layer, pages, slots, n, const_cast<void*>(k), const_cast<void*>(v), 1);
+}
+extern "C" pie_status pie_kv_read(pie_ctx* c, int32_t layer, const int32_t* pages, const int32_t* slots, int32_t n,
+                                  void* k, void* v) {
+  return kv_copy(c, layer, pages, slots, n, k, v, 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// batch deserialisation
+// ---------------------------------------------------------------------------------------------
+namespace {
+struct Blob {  // host image of the device allocation
+  std::vector<unsigned char> bytes;
+  size_t add(const void* src, size_t n, size_t pad = 0) {  // n bytes copied from src, pad zero bytes after
+    size_t off = (bytes.size() + 255) / 256 * 256;
+    bytes.resize(off + n + pad, 0);
+    if (n && src) std::memcpy(bytes.data() + off, src, n);
+    return off;
+  }
+};
+}  // namespace
+
+extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, int32_t validate, pie_batch** out) {
+  if (!c) return PIE_EINVAL;
+  if (!b || !out) return fail(c, PIE_EINVAL, "pie_batch_create: null argument");
+  *out = nullptr;
+  const int R = b->n_requests, T = b->n_tokens;
+  if (R <= 0 || T <= 0) return fail(c, PIE_EINVAL, "empty batch (R=%d, T=%d)", R, T);
+  if (R > c->p.max_batch_requests || T > c->p.max_batch_tokens)
+    return fail(c, PIE_EBATCH, "batch of %d requests / %d tokens exceeds the context's %d / %d", R, T,
+                c->p.max_batch_requests, c->p.max_batch_tokens);
+  if (!b->tok_indptr || !b->in_embed_ids || !b->out_embed_ids || !b->positions || !b->page_indptr || !b->page_ids ||
+      !b->kv_len)
+    return fail(c, PIE_EINVAL, "pie_batch_create: null array");
+  if (b->mask_indptr && !b->mask_words && b->mask_indptr[R] > 0) return fail(c, PIE_EINVAL, "mask_indptr without mask_words");
+  const int G = c->m.n_q_heads / c->m.n_kv_heads, Hkv = c->m.n_kv_heads, D = c->m.head_dim;
+  if (b->tok_indptr[0] != 0 || b->tok_indptr[R] != T) return fail(c, PIE_EINVAL, "tok_indptr must run from 0 to n_tokens");
+  if (b->page_indptr[0] != 0) return fail(c, PIE_EINVAL, "page_indptr must start at 0");
+
+  std::vector<ReqInfo> reqs(R);
+  std::vector<int32_t> tok_page(T), tok_slot(T), visit_phys, visit_logical, dec_reqs;
+  std::vector<PrefillItem> pitems;
+  int rows_cap = 0;
+  int64_t kv_bytes = 0, kv_bytes_dec = 0, flops = 0;
+  const int64_t page_bytes = (int64_t)Hkv * 2 * PAGE * D * 2;
+  for (int r = 0; r < R; ++r) {
+    const int t0 = b->tok_indptr[r], t1 = b->tok_indptr[r + 1];
+    const int n_new = t1 - t0, L = b->kv_len[r];
+    const int p0 = b->page_indptr[r], p1 = b->page_indptr[r + 1];
+    if (n_new <= 0) return fail(c, PIE_EINVAL, "request %d has no tokens", r);
+    if (L < n_new) return fail(c, PIE_EINVAL, "request %d: kv_len %d < new tokens %d", r, L, n_new);
+    const int n_pages = (L + PAGE - 1) / PAGE;
+    if (p1 - p0 < n_pages) return fail(c, PIE_EINVAL, "request %d: %d pages listed, kv_len %d needs %d", r, p1 - p0, L, n_pages);
+    for (int p = p0; p < p1; ++p)
+      if (b->page_ids[p] < 0 || b->page_ids[p] >= c->p.n_kv_pages)
+        return fail(c, PIE_ERANGE, "request %d: page id %d outside [0, %d)", r, b->page_ids[p], c->p.n_kv_pages);
+    ReqInfo& q = reqs[r];
+    q.tok0 = t0; q.n_new = n_new; q.kv_len = L;
+    q.visit0 = (int32_t)visit_phys.size();
+    q.wpr = 0; q.mask_off = 0; q.item0 = -1; q.n_items = 0;
+    for (int i = 0; i < n_new; ++i) {
+      const int t = t0 + i, j = L - n_new + i;
+      if (b->in_embed_ids[t] < 0 || b->in_embed_ids[t] >= c->p.n_embeds)
+        return fail(c, PIE_ERANGE, "token %d: input embed id %d outside [0, %d)", t, b->in_embed_ids[t], c->p.n_embeds);
+      if (b->out_embed_ids[t] < -1 || b->out_embed_ids[t] >= c->p.n_embeds)
+        return fail(c, PIE_ERANGE, "token %d: output embed id %d outside [-1, %d)", t, b->out_embed_ids[t], c->p.n_embeds);
+      if (b->positions[t] < 0) return fail(c, PIE_ERANGE, "token %d: negative position", t);
+      tok_page[t] = b->page_ids[p0 + j / PAGE];
+      tok_slot[t] = j % PAGE;
+    }
+    const bool has_mask = b->mask_indptr && b->mask_indptr[r + 1] > b->mask_indptr[r];
+    if (has_mask) {
+      const int wpr = (L + 31) / 32;
+      if (b->mask_indptr[r + 1] - b->mask_indptr[r] != (int64_t)wpr * n_new)
+        return fail(c, PIE_EINVAL, "request %d: mask has %lld words, expected %lld", r,
+                    (long long)(b->mask_indptr[r + 1] - b->mask_indptr[r]), (long long)wpr * n_new);
+      q.wpr = wpr;
+      q.mask_off = b->mask_indptr[r];
+      // a page is visited when any row has a visible key in it
+      std::vector<uint32_t> any(wpr, 0u);
+      const uint32_t* w = b->mask_words + b->mask_indptr[r];
+      for (int i = 0; i < n_new; ++i)
+        for (int k = 0; k < wpr; ++k) any[k] |= w[(size_t)i * wpr + k];
+      for (int pg = 0; pg < n_pages; ++pg) {
+        uint32_t bits = (any[pg >> 1] >> ((pg & 1) * 16)) & 0xFFFFu;
+        int tail = L - pg * PAGE;
+        if (tail < PAGE) bits &= (1u << tail) - 1u;
+        if (bits) { visit_phys.push_back(b->page_ids[p0 + pg]); visit_logical.push_back(pg); }
+      }
+    } else {
+      for (int pg = 0; pg < n_pages; ++pg) { visit_phys.push_back(b->page_ids[p0 + pg]); visit_logical.push_back(pg); }
+    }
+    q.n_visit = (int32_t)visit_phys.size() - q.visit0;
+    const bool decode_path = n_new * G <= 32;
+    int64_t visited_pages = 0;
+    if (decode_path) {
+      dec_reqs.push_back(r);
+      rows_cap = std::max(rows_cap, n_new * G);
+      visited_pages = q.n_visit;
+      kv_bytes_dec += visited_pages * page_bytes;
+      flops += visited_pages * PAGE * (int64_t)n_new * c->m.n_q_heads * D * 4;
+    } else {
+      const int nqb = (n_new + 31) / 32;
+      for (int qb = 0; qb < nqb; ++qb) pitems.push_back(PrefillItem{r, qb});
+      visited_pages = q.n_visit;  // each page is needed at least once
+      if (q.wpr == 0) flops += (int64_t)c->m.n_q_heads * D * 4 * ((int64_t)n_new * (L - n_new) + (int64_t)n_new * (n_new + 1) / 2);
+      else flops += visited_pages * PAGE * (int64_t)n_new * c->m.n_q_heads * D * 4;
+    }
+    kv_bytes += visited_pages * page_bytes;
+  }
+  if (b->page_indptr[R] < 0) return fail(c, PIE_EINVAL, "bad page_indptr");
+  if (validate) {
+    std::unordered_set<int64_t> seen;
+    seen.reserve((size_t)T * 2);
+    for (int t = 0; t < T; ++t)
+      if (!seen.insert((int64_t)tok_page[t] * PAGE + tok_slot[t]).second)
+        return fail(c, PIE_ECONFLICT, "token %d writes (page %d, slot %d) that another token of the batch writes", t, tok_page[t], tok_slot[t]);
+  }
+  // split the decode-path visit lists into chunks of page pairs: aim for a few thousand waves
+  std::vector<DecodeItem> ditems;
+  {
+    int64_t total_pairs = 0;
+    for (int r : dec_reqs) total_pairs += (reqs[r].n_visit + 1) / 2;
+    total_pairs *= Hkv;
+    int64_t ch = total_pairs / 4096;
+    ch = std::max<int64_t>(2, std::min<int64_t>(64, ch));
+    for (int r : dec_reqs) {
+      ReqInfo& q = reqs[r];
+      q.item0 = (int32_t)ditems.size();
+      const int pages_per_item = (int)ch * 2;
+      int n_it = std::max(1, (q.n_visit + pages_per_item - 1) / pages_per_item);
+      // even split so the last chunk is not a sliver
+      int per = ((q.n_visit + n_it - 1) / n_it + 1) / 2 * 2;
+      if (per < 2) per = 2;
+      int made = 0;
+      for (int v = 0; v < q.n_visit || made == 0; v += per) {
+        ditems.push_back(DecodeItem{r, q.visit0 + v, q.visit0 + std::min(q.n_visit, v + per), 0});
+        ++made;
+        if (q.n_visit == 0) break;
+      }
+      q.n_items = made;
+    }
+  }
+  // heavy query blocks first
+  std::stable_sort(pitems.begin(), pitems.end(), [&](const PrefillItem& x, const PrefillItem& y) {
+    auto cost = [&](const PrefillItem& it) {
+      const ReqInfo& q = reqs[it.r];
+      return q.wpr ? (int64_t)q.n_visit : (int64_t)(q.kv_len - q.n_new + std::min(q.n_new, it.qb * 32 + 32));
+    };
+    return cost(x) > cost(y);
+  });
+
+  pie_batch* pb = new pie_batch();
+  pb->R = R; pb->T = T;
+  pb->n_ditems = (int32_t)ditems.size();
+  pb->n_pitems = (int32_t)pitems.size();
+  pb->n_dec_reqs = (int32_t)dec_reqs.size();
+  pb->rows_cap = std::max(rows_cap, 1);
+  pb->work[0] = kv_bytes; pb->work[1] = kv_bytes_dec; pb->work[2] = flops; pb->work[3] = (int64_t)visit_phys.size();
+  Blob blob;
+  const size_t o_in = blob.add(b->in_embed_ids, (size_t)T * 4), o_out = blob.add(b->out_embed_ids, (size_t)T * 4);
+  const size_t o_pos = blob.add(b->positions, (size_t)T * 4), o_tp = blob.add(tok_page.data(), (size_t)T * 4);
+  const size_t o_ts = blob.add(tok_slot.data(), (size_t)T * 4);
+  const size_t o_vp = blob.add(visit_phys.data(), visit_phys.size() * 4, 8);
+  const size_t o_vl = blob.add(visit_logical.data(), visit_logical.size() * 4, 8);
+  const size_t n_mask = b->mask_indptr ? (size_t)b->mask_indptr[R] : 0;
+  const size_t o_mw = blob.add(n_mask ? b->mask_words : nullptr, n_mask * 4, 4);
+  const size_t o_rq = blob.add(reqs.data(), reqs.size() * sizeof(ReqInfo));
+  const size_t o_di = blob.add(ditems.data(), ditems.size() * sizeof(DecodeItem), 16);
+  const size_t o_pi = blob.add(pitems.data(), pitems.size() * sizeof(PrefillItem), 8);
+  const size_t o_dr = blob.add(dec_reqs.data(), dec_reqs.size() * 4, 4);
+  const size_t part_rows = (size_t)pb->n_ditems * Hkv * pb->rows_cap;
+  const size_t o_po = blob.add(nullptr, 0, 0);  // metadata ends here; the partial buffers are device-only
+  const size_t o_pm = (o_po + part_rows * D * 4 + 255) / 256 * 256;
+  const size_t total_bytes = o_pm + part_rows * 2 * 4 + 256;
+  hipError_t e = hipMalloc(&pb->dev_blob, total_bytes);
+  if (e != hipSuccess) {
+    delete pb;
+    return fail(c, PIE_ENOMEM, "pie_batch_create: %s (%zu bytes)", hipGetErrorString(e), total_bytes);
+  }
+  // copy only the metadata part (everything before the partial buffers)
+  e = hipMemcpyAsync(pb->dev_blob, blob.bytes.data(), blob.bytes.size(), hipMemcpyHostToDevice, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) {
+    (void)hipFree(pb->dev_blob);
+    delete pb;
+    return fail(c, PIE_EHIP, "pie_batch_create: %s", hipGetErrorString(e));
+  }
+  unsigned char* d = reinterpret_cast<unsigned char*>(pb->dev_blob);
+  pb->in_ids = (int32_t*)(d + o_in); pb->out_ids = (int32_t*)(d + o_out); pb->pos = (int32_t*)(d + o_pos);
+  pb->tok_page = (int32_t*)(d + o_tp); pb->tok_slot = (int32_t*)(d + o_ts);
+  pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl);
+  pb->mask_words = (uint32_t*)(d + o_mw); pb->reqs = (ReqInfo*)(d + o_rq);
+  pb->ditems = (DecodeItem*)(d + o_di); pb->pitems = (PrefillItem*)(d + o_pi); pb->dec_reqs = (int32_t*)(d + o_dr);
+  pb->part_o = (float*)(d + o_po); pb->part_ml = (float*)(d + o_pm);
+  *out = pb;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_batch_destroy(pie_ctx* c, pie_batch* b) {
+  if (!b) return PIE_OK;
+  if (c) (void)hipStreamSynchronize(c->stream);
+  if (b->dev_blob) (void)hipFree(b->dev_blob);
+  delete b;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_batch_work(const pie_batch* b, int64_t* out) {
+  if (!b || !out) return PIE_EINVAL;
+  for (int i = 0; i < 4; ++i) out[i] = b->work[i];
+  return PIE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------------------------
+namespace {
+struct StageTimer {
+  pie_ctx* c;
+  StageTimer(pie_ctx* ctx, int first, int last) : c(ctx) {  // clears the stages this call owns
+    if (c->timing) for (int i = first; i <= last; ++i) c->ev_used[i] = false;
+  }
+  void begin(int s) { if (c->timing) (void)hipEventRecord(c->ev[2 * s], c->stream); }
+  void end(int s) { if (c->timing) { (void)hipEventRecord(c->ev[2 * s + 1], c->stream); c->ev_used[s] = true; } }
+};
+}  // namespace
+
+extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b) {
+  if (!c) return PIE_EINVAL;
+  if (!b) return fail(c, PIE_EINVAL, "pie_forward: null batch");
+  if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "pie_forward: layer %d of %d", layer, c->m.n_layers);
+  const LayerWeights& L = c->layers[layer];
+  if (!L.loaded) return fail(c, PIE_EINVAL, "pie_forward: layer %d has no weights", layer);
+  if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "batch larger than the context");
+  const pie_model_desc& m = c->m;
+  const int T = b->T, H = m.hidden, Hq = m.n_q_heads, Hkv = m.n_kv_heads, D = m.head_dim, I = m.mlp_dim;
+  const int QKV = (Hq + 2 * Hkv) * D;
+  hipStream_t s = c->stream;
+  bf16_t* kv_layer = c->kv + (size_t)layer * c->kv_layer_elems;
+  StageTimer tm(c, PIE_STAGE_NORM1, PIE_STAGE_DOWN);
+  EpiArgs e{};
+
+  tm.begin(PIE_STAGE_NORM1);
+  HIP_TRY(c, launch_rmsnorm_embed(c->embeds, b->in_ids, L.g1, c->xn, T, H, m.rms_eps, s));
+  tm.end(PIE_STAGE_NORM1);
+
+  tm.begin(PIE_STAGE_QKV);
+  e = EpiArgs{EPI_STORE_BF16, c->qkv, QKV, nullptr, nullptr, nullptr, 0};
+  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wqkv, e, c->splitk, c->splitk_elems, s));
+  tm.end(PIE_STAGE_QKV);
+
+  tm.begin(PIE_STAGE_ROPE_APPEND);
+  HIP_TRY(c, launch_rope_append(c->qkv, T, Hq, Hkv, D, b->pos, b->tok_page, b->tok_slot, c->inv_freq, kv_layer, s));
+  tm.end(PIE_STAGE_ROPE_APPEND);
+
+  AttnArgs a{};
+  a.q = c->qkv; a.q_stride = QKV; a.kv = kv_layer; a.out = c->attn; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+  a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
+  a.reqs = b->reqs; a.visit_phys = b->visit_phys; a.visit_logical = b->visit_logical; a.mask_words = b->mask_words;
+  if (b->n_ditems > 0) {
+    tm.begin(PIE_STAGE_ATTN_DECODE);
+    HIP_TRY(c, launch_attn_decode(a, b->ditems, b->n_ditems, b->rows_cap, b->part_o, b->part_ml, s));
+    tm.end(PIE_STAGE_ATTN_DECODE);
+    tm.begin(PIE_STAGE_ATTN_MERGE);
+    HIP_TRY(c, launch_attn_merge(a, b->dec_reqs, b->n_dec_reqs, b->rows_cap, b->part_o, b->part_ml, s));
+    tm.end(PIE_STAGE_ATTN_MERGE);
+  }
+  if (b->n_pitems > 0) {
+    tm.begin(PIE_STAGE_ATTN_PREFILL);
+    HIP_TRY(c, launch_attn_prefill(a, b->pitems, b->n_pitems, s));
+    tm.end(PIE_STAGE_ATTN_PREFILL);
+  }
+
+  tm.begin(PIE_STAGE_OPROJ);
+  e = EpiArgs{EPI_RESID_EMBED, c->h, H, c->embeds, b->in_ids, nullptr, H};
+  HIP_TRY(c, launch_gemm(c->attn, Hq * D, T, L.wo, e, c->splitk, c->splitk_elems, s));
+  tm.end(PIE_STAGE_OPROJ);
+
+  tm.begin(PIE_STAGE_NORM2);
+  HIP_TRY(c, launch_rmsnorm_f32(c->h, L.g2, c->xn, T, H, m.rms_eps, s));
+  tm.end(PIE_STAGE_NORM2);
+
+  tm.begin(PIE_STAGE_GATEUP);
+  e = EpiArgs{EPI_SWIGLU, c->act, I, nullptr, nullptr, nullptr, 0};
+  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wgu, e, c->splitk, c->splitk_elems, s));
+  tm.end(PIE_STAGE_GATEUP);
+
+  tm.begin(PIE_STAGE_DOWN);
+  e = EpiArgs{EPI_RESID_OUT, nullptr, 0, c->embeds, b->out_ids, c->h, H};
+  HIP_TRY(c, launch_gemm(c->act, I, T, L.wdown, e, c->splitk, c->splitk_elems, s));
+  tm.end(PIE_STAGE_DOWN);
+  c->last_T = T;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_forward_host(pie_ctx* c, int32_t layer, const pie_forward_batch* batch, int32_t validate) {
+  pie_batch* pb = nullptr;
+  pie_status st = pie_batch_create(c, batch, validate, &pb);
+  if (st != PIE_OK) return st;
+  st = pie_forward(c, layer, pb);
+  pie_status st2 = pie_synchronize(c);
+  pie_batch_destroy(c, pb);
+  return st != PIE_OK ? st : st2;
+}
+
+// ---------------------------------------------------------------------------------------------
+// get_next_dist
+// ---------------------------------------------------------------------------------------------
+extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, int32_t n, int32_t top_k,
+                                        float temperature, int32_t* out_ids, float* out_probs) {
+  if (!c) return PIE_EINVAL;
+  if (!embed_ids || n <= 0) return fail(c, PIE_EINVAL, "pie_get_next_dist: null ids or n <= 0");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(c, PIE_EINVAL, "temperature must be positive and finite");
+  if (!c->head_loaded) return fail(c, PIE_EINVAL, "pie_get_next_dist: no LM head loaded");
+  if (n > c->p.max_dist_rows) return fail(c, PIE_EBATCH, "%d rows exceed max_dist_rows %d", n, c->p.max_dist_rows);
+  if (top_k <= 0 || top_k > c->p.max_top_k || top_k > c->m.vocab)
+    return fail(c, PIE_ERANGE, "top_k %d outside [1, min(max_top_k %d, vocab %d)]", top_k, c->p.max_top_k, c->m.vocab);
+  if (!out_ids || !out_probs) return fail(c, PIE_EINVAL, "pie_get_next_dist: null output");
+  for (int i = 0; i < n; ++i)
+    if (embed_ids[i] < 0 || embed_ids[i] >= c->p.n_embeds) return fail(c, PIE_ERANGE, "embed id %d at %d outside [0, %d)", embed_ids[i], i, c->p.n_embeds);
+  const int H = c->m.hidden, V = c->m.vocab;
+  hipStream_t s = c->stream;
+  pie_status st = stage_ids(c, embed_ids, nullptr, n);
+  if (st != PIE_OK) return st;
+  StageTimer tm(c, PIE_STAGE_HEAD_NORM, PIE_STAGE_TOPK);
+  tm.begin(PIE_STAGE_HEAD_NORM);
+  if (c->g_final) {
+    HIP_TRY(c, launch_rmsnorm_embed(c->embeds, c->ids_dev, c->g_final, c->en, n, H, c->m.rms_eps, s));
+  } else {
+    HIP_TRY(c, launch_embed_copy(c->embeds, c->ids_dev, n, H, c->en, 0, s));
+  }
+  tm.end(PIE_STAGE_HEAD_NORM);
+  tm.begin(PIE_STAGE_LM_HEAD);
+  EpiArgs e{EPI_STORE_F32, c->logits, V, nullptr, nullptr, nullptr, 0};
+  HIP_TRY(c, launch_gemm(c->en, H, n, c->wlm, e, c->splitk, c->splitk_elems, s));
+  tm.end(PIE_STAGE_LM_HEAD);
+  tm.begin(PIE_STAGE_TOPK);
+  HIP_TRY(c, launch_topk(c->logits, n, V, top_k, 1.0f / temperature, out_ids, out_probs, s));
+  tm.end(PIE_STAGE_TOPK);
+  c->last_dist_n = n;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_synchronize(pie_ctx* c) {
+  if (!c) return PIE_EINVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PIE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// observation points
+// ---------------------------------------------------------------------------------------------
+extern "C" pie_status pie_read_tap(pie_ctx* c, int32_t which, void* dst, int64_t n_elements) {
+  if (!c || !dst) return PIE_EINVAL;
+  const pie_model_desc& m = c->m;
+  const int T = c->last_T, QD = m.n_q_heads * m.head_dim, QKV = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+  switch (which) {
+    case PIE_TAP_Q:
+      if (n_elements != (int64_t)T * QD) return fail(c, PIE_EINVAL, "tap Q holds %lld elements", (long long)T * QD);
+      HIP_TRY(c, hipMemcpy2DAsync(dst, (size_t)QD * 2, c->qkv, (size_t)QKV * 2, (size_t)QD * 2, T, hipMemcpyDeviceToDevice, c->stream));
+      break;
+    case PIE_TAP_ATTN:
+      if (n_elements != (int64_t)T * QD) return fail(c, PIE_EINVAL, "tap ATTN holds %lld elements", (long long)T * QD);
+      HIP_TRY(c, hipMemcpyAsync(dst, c->attn, (size_t)T * QD * 2, hipMemcpyDeviceToDevice, c->stream));
+      break;
+    case PIE_TAP_RESID:
+      if (n_elements != (int64_t)T * m.hidden) return fail(c, PIE_EINVAL, "tap RESID holds %lld elements", (long long)T * m.hidden);
+      HIP_TRY(c, hipMemcpyAsync(dst, c->h, (size_t)T * m.hidden * 4, hipMemcpyDeviceToDevice, c->stream));
+      break;
+    case PIE_TAP_ACT:
+      if (n_elements != (int64_t)T * m.mlp_dim) return fail(c, PIE_EINVAL, "tap ACT holds %lld elements", (long long)T * m.mlp_dim);
+      HIP_TRY(c, hipMemcpyAsync(dst, c->act, (size_t)T * m.mlp_dim * 2, hipMemcpyDeviceToDevice, c->stream));
+      break;
+    case PIE_TAP_LOGITS:
+      if (n_elements != (int64_t)c->last_dist_n * m.vocab) return fail(c, PIE_EINVAL, "tap LOGITS holds %lld elements", (long long)c->last_dist_n * m.vocab);
+      HIP_TRY(c, hipMemcpyAsync(dst, c->logits, (size_t)n_elements * 4, hipMemcpyDeviceToDevice, c->stream));
+      break;
+    default:
+      return fail(c, PIE_EINVAL, "unknown tap %d", which);
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_set_stage_timing(pie_ctx* c, int32_t enabled) {
+  if (!c) return PIE_EINVAL;
+  c->timing = enabled != 0;
+  for (int i = 0; i < PIE_N_STAGES; ++i) c->ev_used[i] = false;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_stage_times(pie_ctx* c, float* ms_out) {
+  if (!c || !ms_out) return PIE_EINVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int i = 0; i < PIE_N_STAGES; ++i) {
+    ms_out[i] = 0.f;
+    if (c->ev_used[i]) HIP_TRY(c, hipEventElapsedTime(&ms_out[i], c->ev[2 * i], c->ev[2 * i + 1]));
+  }
+  return PIE_OK;
+}

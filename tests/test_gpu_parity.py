@@ -1,0 +1,257 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Tolerances: layer outputs (bf16) max-abs <= 2e-2 and mean-abs <= 2e-3 against the oracle's wide value;
+integer/byte work (pool round trips, page slots, top-k ids outside logit ties < 1e-3) exact."""
+import copy
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import pie_oracle as O
+from gpu_helpers import (appended_positions, assert_bf16_close, assert_close, dec, gpu_forward, make_ctx, seed_ctx)
+from helpers import check_topk, oracle_pools, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def small_model(head_dim=64, n_q=4, n_kv=2, hidden=128, mlp=256, vocab=512):
+    return W.ModelDesc(hidden=hidden, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=head_dim, mlp_dim=mlp, vocab=vocab,
+                       page_size=16, rms_eps=1e-5, rope_theta=1e4, n_layers=1)
+
+
+def random_mask(p):
+    def f(n_new, L, rng):
+        m = rng.random((n_new, L)) < p
+        m &= W.causal_bitmap(n_new, L)
+        return m
+    return f
+
+
+def compare_layer(w, ctx=None, mode_b_only=False, check_taps=True, what=""):
+    """Full element-by-element comparison of one forward call (outputs, taps, appended KV)."""
+    ctx = ctx or make_ctx(w)
+    pb, stored, y_bits = gpu_forward(ctx, w)
+    T = w.batch.n_tokens
+    res_b, kv_b, _ = run_oracle(w, round_intermediates=True)
+    assert_close(dec(y_bits), res_b.y[stored], f"{what} y vs oracle (bf16 intermediates)")
+    if not mode_b_only:
+        res_a, _, _ = run_oracle(w)
+        assert_close(dec(y_bits), res_a.y[stored], f"{what} y vs oracle (wide intermediates)")
+    if check_taps:
+        from paper_2510_24051_amd import TAP_ACT, TAP_ATTN, TAP_Q, TAP_RESID
+        m = w.model
+        q = dec(ctx.read_tap(TAP_Q, T)).reshape(T, m.n_q_heads, m.head_dim)
+        assert_close(q, res_b.q, f"{what} q after rotary step", 4e-2 * max(1.0, np.abs(res_b.q).max() / 4), 2e-3 * max(1.0, np.abs(res_b.q).mean()))
+        o = dec(ctx.read_tap(TAP_ATTN, T)).reshape(T, m.n_q_heads, m.head_dim)
+        assert_close(o, res_b.o, f"{what} attention output", 2e-2 * max(1.0, np.abs(res_b.o).max()), 2e-3 * max(1.0, np.abs(res_b.o).mean() * 4))
+        h = ctx.read_tap(TAP_RESID, T)
+        assert_close(h, res_b.h, f"{what} residual after attention")
+    # appended K/V land in the right (page, slot), values equal up to bf16 rounding of an fp32 vs fp64 product
+    pages, slots = appended_positions(w)
+    k_gpu, v_gpu = ctx.kv_read(0, pages, slots)
+    assert_bf16_close(k_gpu, res_b.k_new, f"{what} appended K", ulps=2)
+    assert_bf16_close(v_gpu, res_b.v_new, f"{what} appended V", ulps=2)
+    # prior KV untouched (byte work: exact)
+    if len(w.prior.page_ids):
+        k0, v0 = ctx.kv_read(0, w.prior.page_ids, w.prior.slots)
+        assert np.array_equal(k0, w.prior.k_bits) and np.array_equal(v0, w.prior.v_bits)
+    return ctx, pb, y_bits, stored
+
+
+def compare_dist(ctx, w, what=""):
+    """get_next_dist on the GPU's own stored output Embeds (the resource boundary between the two calls)."""
+    ids_e = w.batch.out_embed_ids[w.dist_rows]
+    gi, gp = ctx.get_next_dist(ids_e, w.top_k, w.temperature)
+    emb = O.EmbedPool(w.n_embeds, w.model.hidden)
+    emb.write(ids_e, ctx.embed_read(ids_e))
+    oi, op, z = O.get_next_dist(w.model, w.head, emb, ids_e, w.top_k, w.temperature, round_intermediates=True)
+    check_topk(gi, gp, z / w.temperature, oi, op)
+    from paper_2510_24051_amd import TAP_LOGITS
+    zg = ctx.read_tap(TAP_LOGITS, len(ids_e))
+    mx = np.abs(zg - z).max()
+    print(f"    {what} logits max-abs {mx:.3e}; ids equal {np.mean(gi == oi) * 100:.2f}%", flush=True)
+    assert mx < 1e-3
+
+
+# ---------------------------------------------------------------- byte work
+def test_pool_roundtrips_are_bit_exact():
+    m = small_model()
+    w = W.build_workload("rt", m, [W.RequestSpec(3, 40), W.RequestSpec(1, 7)], n_kv_pages=16, seed=1)
+    ctx = make_ctx(w)
+    assert np.array_equal(ctx.embed_read(w.batch.in_embed_ids), w.embed_bits)
+    k, v = ctx.kv_read(0, w.prior.page_ids, w.prior.slots)
+    assert np.array_equal(k, w.prior.k_bits) and np.array_equal(v, w.prior.v_bits)
+    untouched = np.setdiff1d(np.arange(w.n_embeds), w.batch.in_embed_ids)
+    assert not ctx.embed_read(untouched).any()
+
+
+# ---------------------------------------------------------------- config 1
+def test_c1_tiny_layer_and_dist():
+    w = W.c1_tiny()
+    ctx, pb, y_bits, stored = compare_layer(w, what="c1")
+    compare_dist(ctx, w, "c1")
+    # explicit causal bitmaps give the same bits as inferred causal masks
+    wb = W.c1_tiny(bitmap=True)
+    ctx2 = make_ctx(wb)
+    _, _, y2 = gpu_forward(ctx2, wb)
+    assert np.array_equal(y2, y_bits)
+
+
+def test_c1_literal_unstored_rows_and_in_place():
+    w = W.c1_tiny()
+    w2 = copy.deepcopy(w)
+    b = w2.batch
+    t0 = b.tok_indptr[4]
+    b.out_embed_ids[t0:t0 + 31] = -1  # prefill keeps only its last row
+    ctx = make_ctx(w2)
+    before = ctx.embed_read(np.arange(w2.n_embeds))
+    _, stored, y_bits = gpu_forward(ctx, w2)
+    res, _, _ = run_oracle(w2, round_intermediates=True)
+    assert_close(dec(y_bits), res.y[stored], "c1 stored rows")
+    after = ctx.embed_read(np.arange(w2.n_embeds))
+    changed = np.nonzero((before != after).any(axis=1))[0]
+    assert set(changed.tolist()) <= set(b.out_embed_ids[stored].tolist())
+
+
+# ---------------------------------------------------------------- ragged shapes, masks, head dims, group sizes
+@pytest.mark.parametrize("head_dim,n_q,n_kv", [(64, 4, 2), (128, 8, 2), (128, 8, 1), (64, 2, 2)])
+def test_ragged_mixed_batch(head_dim, n_q, n_kv):
+    m = small_model(head_dim, n_q, n_kv)
+    sparse = random_mask(0.3)
+    reqs = [W.RequestSpec(1, 0), W.RequestSpec(1, 15), W.RequestSpec(1, 16), W.RequestSpec(2, 100),
+            W.RequestSpec(3, 33, mask=sparse), W.RequestSpec(9, 0), W.RequestSpec(31, 5, mask=W.causal_bitmap),
+            W.RequestSpec(33, 47), W.RequestSpec(70, 130, mask=sparse), W.RequestSpec(1, 700, mask=random_mask(0.02)),
+            W.RequestSpec(1, 257, in_place=True), W.RequestSpec(40, 0, mask=random_mask(0.9))]
+    w = W.build_workload("ragged", m, reqs, n_kv_pages=160, seed=100 + head_dim + n_q, std=0.05)
+    compare_layer(w, what=f"ragged D{head_dim} {n_q}/{n_kv}")
+
+
+def test_rows_without_visible_keys_output_the_residual_only():
+    m = small_model()
+
+    def none_visible(n_new, L, rng):
+        a = W.causal_bitmap(n_new, L)
+        a[0, :] = False
+        return a
+    reqs = [W.RequestSpec(1, 20, mask=none_visible), W.RequestSpec(40, 3, mask=none_visible)]
+    w = W.build_workload("blind", m, reqs, n_kv_pages=16, seed=5, std=0.05)
+    ctx, *_ = compare_layer(w, what="blind rows")
+    from paper_2510_24051_amd import TAP_ATTN
+    o = ctx.read_tap(TAP_ATTN, w.batch.n_tokens)
+    assert not o[0].any() and not o[1].any()
+
+
+def test_sparse_mask_skips_pages_and_matches():
+    m = small_model(128, 8, 2)
+    reqs = [W.RequestSpec(1, 1500, mask=W.sink_window_mask(4, 100)), W.RequestSpec(2, 900, mask=W.sink_window_mask(4, 64))]
+    w = W.build_workload("sinkwin", m, reqs, n_kv_pages=200, seed=6, std=0.05)
+    ctx, pb, *_ = compare_layer(w, what="sink+window")
+    work = pb.work()
+    assert work["visited_pages"] == (1 + 7) + (1 + 5)  # sink page + window pages only
+    assert work["kv_bytes"] == work["visited_pages"] * 2 * 16 * 128 * 2 * 2
+
+
+def test_split_call_equivalence_on_gpu():
+    m = small_model()
+    one = W.build_workload("split", m, [W.RequestSpec(40, 0)], n_kv_pages=8, seed=21, std=0.05)
+    ctx = make_ctx(one)
+    _, _, y_one = gpu_forward(ctx, one)
+    b = one.batch
+    ctx2 = make_ctx(one)
+    from helpers import clone_batch
+    first = clone_batch(b, n_tokens=39, tok_indptr=np.array([0, 39], np.int32), in_embed_ids=b.in_embed_ids[:39],
+                        out_embed_ids=np.full(39, -1, np.int32), positions=b.positions[:39],
+                        kv_len=np.array([39], np.int32))
+    ctx2.forward_host(0, first)
+    second = clone_batch(b, n_tokens=1, tok_indptr=np.array([0, 1], np.int32), in_embed_ids=b.in_embed_ids[39:],
+                         out_embed_ids=b.out_embed_ids[39:], positions=b.positions[39:],
+                         kv_len=np.array([40], np.int32))
+    ctx2.forward_host(0, second)
+    y_two = ctx2.embed_read(b.out_embed_ids[39:])
+    assert_close(dec(y_two), dec(y_one[39:]), "split call vs single call", 2e-2, 2e-3)
+    pages, slots = appended_positions(one)
+    k1, v1 = ctx.kv_read(0, pages, slots)
+    k2, v2 = ctx2.kv_read(0, pages, slots)
+    assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
+
+
+def test_batch_composition_invariance_on_gpu():
+    m = small_model()
+    reqs = [W.RequestSpec(1, 90), W.RequestSpec(35, 10), W.RequestSpec(2, 300)]
+    w = W.build_workload("comp", m, reqs, n_kv_pages=64, seed=33, std=0.05)
+    ctx = make_ctx(w)
+    _, _, y_all = gpu_forward(ctx, w)
+    b = w.batch
+    from helpers import clone_batch
+    for r in range(3):
+        a, e = b.tok_indptr[r], b.tok_indptr[r + 1]
+        pa, pe = b.page_indptr[r], b.page_indptr[r + 1]
+        solo = clone_batch(b, n_requests=1, n_tokens=e - a, tok_indptr=np.array([0, e - a], np.int32),
+                           in_embed_ids=b.in_embed_ids[a:e], out_embed_ids=b.out_embed_ids[a:e],
+                           positions=b.positions[a:e], page_indptr=np.array([0, pe - pa], np.int32),
+                           page_ids=b.page_ids[pa:pe], kv_len=b.kv_len[r:r + 1])
+        c2 = make_ctx(w)
+        c2.forward_host(0, solo)
+        y = c2.embed_read(b.out_embed_ids[a:e])
+        # GEMM tiling depends on the row count, so allow rounding-level differences only
+        assert_close(dec(y), dec(y_all[a:e]), f"request {r} alone vs in batch", 2e-2, 5e-4)
+
+
+# ---------------------------------------------------------------- distribution
+@pytest.mark.parametrize("k,temp", [(1, 1.0), (8, 0.7), (256, 1.0), (300, 2.0)])
+def test_get_next_dist_top_k(k, temp):
+    m = small_model(vocab=2048)
+    w = W.build_workload("dist", m, [W.RequestSpec(1, 5) for _ in range(7)], n_kv_pages=16, seed=40, std=0.05,
+                         top_k=k, temperature=temp)
+    ctx = make_ctx(w, max_top_k=512)
+    gpu_forward(ctx, w)
+    compare_dist(ctx, w, f"k={k} T={temp}")
+
+
+def test_top_k_ties_pick_lower_ids():
+    m = small_model(vocab=512)
+    w = W.build_workload("ties", m, [W.RequestSpec(1, 3)], n_kv_pages=4, seed=41, std=0.05, top_k=40)
+    w.head.w_lm[:] = 0  # all logits equal -> ids 0..k-1, uniform probabilities
+    ctx = make_ctx(w)
+    gpu_forward(ctx, w)
+    gi, gp = ctx.get_next_dist(w.batch.out_embed_ids[:1], 40, 1.0)
+    assert gi[0].tolist() == list(range(40))
+    np.testing.assert_allclose(gp[0], 1.0 / 512, rtol=1e-5)
+
+
+# ---------------------------------------------------------------- error paths (detected on the host)
+def test_error_codes():
+    from paper_2510_24051_amd import Pie, PieError
+    m = small_model()
+    w = W.build_workload("err", m, [W.RequestSpec(2, 10), W.RequestSpec(1, 4)], n_kv_pages=8, seed=50, std=0.05, top_k=4)
+    ctx = make_ctx(w)
+
+    def status_of(fn):
+        with pytest.raises(PieError) as e:
+            fn()
+        return e.value.status
+    b = copy.deepcopy(w.batch)
+    b.page_ids[0] = 99
+    assert status_of(lambda: ctx.batch_create(b)) == -2  # PIE_ERANGE
+    b = copy.deepcopy(w.batch)
+    b.in_embed_ids[0] = w.n_embeds
+    assert status_of(lambda: ctx.batch_create(b)) == -2
+    b = copy.deepcopy(w.batch)  # second request writes the slot of the first one's last token
+    b.page_ids[b.page_indptr[1]] = b.page_ids[0]
+    b.kv_len[1] = 12
+    assert status_of(lambda: ctx.batch_create(b, validate=True)) == -4  # PIE_ECONFLICT
+    big = W.build_workload("big", m, [W.RequestSpec(4, 0)], n_kv_pages=8, seed=51, std=0.05)
+    assert status_of(lambda: ctx.batch_create(big.batch)) == -3  # PIE_EBATCH: 4 tokens > 3
+    assert status_of(lambda: ctx.get_next_dist([0], 0)) == -2
+    assert status_of(lambda: ctx.get_next_dist([0], 4, temperature=0.0)) == -1
+    assert status_of(lambda: ctx.get_next_dist([w.n_embeds], 4)) == -2
+    assert status_of(lambda: ctx.embed_read([-1])) == -2
+    assert status_of(lambda: ctx.kv_read(0, [0], [16])) == -2
+    bad = copy.copy(m)
+    bad.page_size = 8
+    with pytest.raises(PieError) as e:
+        Pie(bad, 8, 8, 4, 4)
+    assert e.value.status == -7  # PIE_EUNSUPPORTED
+    # the context still works after the failed calls
+    compare_layer(w, ctx=ctx, what="after errors")
