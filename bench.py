@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch: `pie_forward` (one Llama-3-8B-shaped
+decoder layer over 64 decode requests with prior contexts uniform in [512, 4096] against a 40k-page pool)
+followed by `pie_get_next_dist` for the 64 output Embeds (vocab 128256, top-K 256).  Inputs are resident in
+HBM before the timed region; the batch has been deserialised (`pie_batch_create`) beforehand.
+
+Prints ONE JSON line: whole-step tokens/s, per-stage times, the roofline of the dominant forward kernel
+(paged decode attention, HBM-bound) measured with HIP events on the library's stream, and the CPU oracle
+timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--top-k", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2510_24051_amd import Pie
+
+    t_setup = time.time()
+    if args.workload == "c2":
+        w = W.c2_decode(top_k=args.top_k)
+        desc = "configs[1]: Llama-3-8B-shaped layer, 64 decode requests, prior ctx U[512,4096], 40k-page pool, page 16"
+    elif args.workload == "c3":
+        w = W.c3_mixed()
+        desc = "configs[2]: 8B-shaped layer, 8 prefill x 1024 (prior U[0,2048]) + 128 decode @2048"
+    elif args.workload == "c4":
+        w = W.c4_prefix_tree(with_head=True)
+        w.top_k = args.top_k
+        w.dist_rows = np.arange(w.batch.n_tokens, dtype=np.int32)
+        desc = "configs[3]: 8B-shaped layer, 256 branches sharing a 4096-token prefix, bitmap masks"
+    else:
+        w = W.c5_sparse_long()
+        desc = "configs[4]: 70B-shaped layer, 16 requests @32768, sink(4)+window(4096) bitmaps"
+    b = w.batch
+    T = int(b.n_tokens)
+    # distinct output Embeds so that every step does identical work on identical inputs
+    free_ids = np.setdiff1d(np.arange(w.n_embeds, dtype=np.int32), b.in_embed_ids)
+    b.out_embed_ids = free_ids[:T].astype(np.int32)
+    dist_ids = b.out_embed_ids[w.dist_rows]
+    n_dist = len(dist_ids)
+
+    ctx = Pie(w.model, w.n_kv_pages, w.n_embeds, max_batch_tokens=T, max_batch_requests=b.n_requests,
+              max_top_k=max(256, w.top_k), max_dist_rows=max(n_dist, 1))
+    ctx.load_layer(0, w.weights)
+    ctx.load_head(w.head)
+    ctx.embed_write(b.in_embed_ids, w.embed_bits)
+    ctx.kv_write(0, w.prior.page_ids, w.prior.slots, w.prior.k_bits, w.prior.v_bits)
+    pb = ctx.batch_create(b, validate=True)
+    work = pb.work()
+    out_ids = torch.empty((n_dist, w.top_k), dtype=torch.int32, device=ctx.device)
+    out_probs = torch.empty((n_dist, w.top_k), dtype=torch.float32, device=ctx.device)
+    torch.cuda.synchronize()
+    print(f"# setup {time.time() - t_setup:.1f}s: {desc}; T={T} R={b.n_requests} "
+          f"kv tokens={int(b.kv_len.sum())} visited pages={work['visited_pages']}", file=sys.stderr, flush=True)
+
+    def step():
+        ctx.forward(0, pb)
+        ctx.get_next_dist_async(dist_ids, w.top_k, w.temperature, out_ids, out_probs)
+
+    for _ in range(args.warmup):
+        step()
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    with torch.cuda.stream(ctx.stream):
+        ev0.record()
+        for _ in range(args.steps):
+            step()
+        ev1.record()
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    ms_per_step = max(wall_ms, ev_ms)
+
+    # forward only (the metric's "per layer" part), same method
+    ctx.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.forward(0, pb)
+    ctx.synchronize()
+    fwd_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-stage durations: HIP events recorded by the library on its own stream around every stage
+    ctx.set_stage_timing(True)
+    acc = {}
+    n_prof = min(args.steps, 20)
+    for _ in range(n_prof):
+        step()
+        for k, v in ctx.stage_times().items():
+            acc[k] = acc.get(k, 0.0) + v
+    ctx.set_stage_timing(False)
+    stages = {k: v / n_prof for k, v in acc.items() if v > 0}
+
+    m = w.model
+    kv_token_bytes = 2 * m.n_kv_heads * m.head_dim * 2
+    dec_tokens = sum(int(b.kv_len[r]) for r in range(b.n_requests) if (b.tok_indptr[r + 1] - b.tok_indptr[r]) * (m.n_q_heads // m.n_kv_heads) <= 32)
+    attn_bytes = work["kv_bytes_decode"] if b.mask_indptr is not None else dec_tokens * kv_token_bytes
+    attn_ms = stages.get("attn_decode", 0.0)
+    achieved = attn_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
+    roofline = {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes": attn_bytes, "avg_ms": round(attn_ms, 5)}
+
+    weight_bytes = 2 * (m.hidden * (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim + m.n_q_heads * m.head_dim * m.hidden
+                        + 3 * m.hidden * m.mlp_dim)
+    lm_bytes = 2 * m.vocab * m.hidden
+    gemm_ms = sum(stages.get(k, 0.0) for k in ("qkv", "oproj", "gateup", "down"))
+    extra = {
+        "layer_gemms": {"bound": "hbm", "algorithmic_bytes": weight_bytes, "ms": round(gemm_ms, 5),
+                        "achieved_GBs": round(weight_bytes / (gemm_ms * 1e-3) / 1e9, 1) if gemm_ms else None},
+        "lm_head": {"bound": "hbm", "algorithmic_bytes": lm_bytes, "ms": round(stages.get("lm_head", 0.0), 5),
+                    "achieved_GBs": round(lm_bytes / (stages["lm_head"] * 1e-3) / 1e9, 1) if stages.get("lm_head") else None},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import pie_oracle as O
+        from helpers import oracle_pools
+        kv, emb = oracle_pools(w)
+        tc = time.perf_counter()
+        O.forward(w.model, w.weights, kv, emb, b)
+        O.get_next_dist(w.model, w.head, emb, dist_ids, w.top_k, w.temperature)
+        cpu_s = time.perf_counter() - tc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = {"value": round(T / cpu_s, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"one whole step (forward over all {T} tokens + get_next_dist on {n_dist} rows), {cpu_s:.1f}s, float64 NumPy"}
+
+    line = {
+        "metric": "forward tokens/s per layer (8B shape) + decode-attn HBM GB/s % of peak",
+        "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": desc, "tokens_per_step": T, "requests": int(b.n_requests), "dist_rows": n_dist,
+                   "top_k": int(w.top_k), "step": "pie_forward (1 layer) + pie_get_next_dist"},
+        "forward_only": {"tokens_per_s": round(T / (fwd_ms * 1e-3), 1), "ms": round(fwd_ms, 5)},
+        "stages_ms": {k: round(v, 5) for k, v in stages.items()},
+        "roofline": roofline, "other_kernels": extra, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
