@@ -79,12 +79,12 @@ __device__ __forceinline__ void attn_step(AttnState<D>& st, const bf16x8 (&kf)[D
   mx = fmaxf(mx, __shfl_xor(mx, 32));
   const float m_new = fmaxf(st.m, mx);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-  const float alpha = exp2f(st.m - m_safe);  // 0 while nothing was visible before
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);  // 0 while nothing was visible before
   float lsum = 0.f;
   Pack16 pa, pb;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const float p = exp2f(s[v] - m_safe);  // masked keys: exp2(-inf) = 0
+    const float p = __builtin_amdgcn_exp2f(s[v] - m_safe);  // masked keys: exp2(-inf) = 0
     lsum += p;
     if (v < 8) pa.h[v] = f32_to_bf16(p);
     else pb.h[v - 8] = f32_to_bf16(p);
@@ -132,79 +132,204 @@ __device__ __forceinline__ void load_q(const bf16_t* __restrict__ qrow, bool val
 // ------------------------------------------------------------------------------------------------
 // decode: split-K partials
 // ------------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
-                                                          int n_items, int rows_cap, float* __restrict__ part_o,
-                                                          float* __restrict__ part_ml) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int item = blockIdx.x * 4 + wave;
-  const int hk = blockIdx.y;
-  if (item >= n_items) return;
-  const DecodeItem it = items[item];
-  const ReqInfo rq = a.reqs[it.r];
-  const int G = a.Hq / a.Hkv;
-  const int rows = rq.n_new * G;
-  const int qcol = lane & 31, g = lane >> 5;
-  const bool valid = qcol < rows;
-  const int i_tok = valid ? qcol / G : 0;
-  const int hg = valid ? qcol % G : 0;
-  bf16x8 qf[D / 16];
-  load_q<D>(a.q + (int64_t)(rq.tok0 + i_tok) * a.q_stride + (hk * G + hg) * D, valid, g, qf);
-  AttnState<D> st;
-  attn_init<D>(st);
-  for (int v = it.v0; v < it.v1; v += 2) {
-    const bool has_b = v + 1 < it.v1;
-    const int pl_a = a.visit_logical[v], pp_a = a.visit_phys[v];
-    const int pl_b = has_b ? a.visit_logical[v + 1] : pl_a;
-    const int pp_b = has_b ? a.visit_phys[v + 1] : pp_a;
-    bf16x8 kf[D / 16], va[D / 32], vb[D / 32];
-    load_kv<D>(a.kv, a.Hkv, hk, pp_a, pp_b, lane, kf, va, vb);
-    const uint32_t bits_a = key_bits(rq, a.mask_words, i_tok, pl_a, g, valid);
-    const uint32_t bits_b = has_b ? key_bits(rq, a.mask_words, i_tok, pl_b, g, valid) : 0u;
-    attn_step<D>(st, kf, qf, va, vb, bits_a, bits_b, a.scale_log2);
+// Visible-key bits from a preloaded mask word (bitmap requests) or from the causal rule.
+__device__ __forceinline__ uint32_t key_bits_w(int kv_len, int n_new, bool has_bitmap, uint32_t word, int i_tok, int pl,
+                                               int g, bool row_valid) {
+  if (!row_valid) return 0u;
+  const int j0 = pl * PAGE + g * 8;
+  int cnt = kv_len - j0;
+  cnt = cnt < 0 ? 0 : (cnt > 8 ? 8 : cnt);
+  uint32_t bits = (1u << cnt) - 1u;
+  if (has_bitmap) {
+    bits &= (word >> ((pl & 1) * 16 + g * 8)) & 0xFFu;
+  } else {
+    int lim = kv_len - n_new + i_tok - j0 + 1;
+    lim = lim < 0 ? 0 : (lim > 8 ? 8 : lim);
+    bits &= (1u << lim) - 1u;
   }
-  const float l_tot = st.l + __shfl_xor(st.l, 32);
-  if (!valid) return;
-  const int64_t prow = ((int64_t)item * a.Hkv + hk) * rows_cap + qcol;
-  if (g == 0) {
-    part_ml[prow * 2] = st.m;
-    part_ml[prow * 2 + 1] = l_tot;
-  }
-  float* po = part_o + prow * D;
-#pragma unroll
-  for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      f32x4 o4 = {st.o[b][q4 * 4], st.o[b][q4 * 4 + 1], st.o[b][q4 * 4 + 2], st.o[b][q4 * 4 + 3]};
-      *reinterpret_cast<f32x4*>(po + b * 32 + q4 * 8 + g * 4) = o4;
-    }
+  return bits;
 }
 
-// One workgroup per (decode-path request, kv head); thread d combines the request's chunks for every row.
+// Grid: one wave per equal share of the flattened (request, kv head, page pair) list; a wave walks the
+// segments of its share.  Per segment: query operands and page ids are fetched once, then K and V stream
+// through one register set each - K of the next pair is requested as soon as the QK^T MFMAs have consumed
+// this pair's K, V of the next pair (and its mask words) as soon as the PV MFMAs have consumed this pair's V;
+// the second wave on the SIMD covers the rest of the latency.
 template <int D>
-__global__ void attn_merge_kernel(AttnArgs a, const int32_t* __restrict__ dec_reqs, int rows_cap,
-                                  const float* __restrict__ part_o, const float* __restrict__ part_ml) {
-  const ReqInfo rq = a.reqs[dec_reqs[blockIdx.x]];
-  const int hk = blockIdx.y, d = threadIdx.x;
+__global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const DecodeSeg* __restrict__ segs,
+                                                             const int32_t* __restrict__ wave_seg, int n_waves,
+                                                             int rows_cap, float* __restrict__ part_o,
+                                                             float* __restrict__ part_ml) {
+  const int lane = threadIdx.x & 63;
+  const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (gw >= n_waves) return;
   const int G = a.Hq / a.Hkv;
-  const int rows = rq.n_new * G;
-  for (int row = 0; row < rows; ++row) {
-    float M = -INFINITY;
-    for (int c = 0; c < rq.n_items; ++c)
-      M = fmaxf(M, part_ml[(((int64_t)(rq.item0 + c) * a.Hkv + hk) * rows_cap + row) * 2]);
-    float num = 0.f, den = 0.f;
-    if (M != -INFINITY) {
-      for (int c = 0; c < rq.n_items; ++c) {
-        const int64_t prow = ((int64_t)(rq.item0 + c) * a.Hkv + hk) * rows_cap + row;
-        const float w = exp2f(part_ml[prow * 2] - M);
-        den += w * part_ml[prow * 2 + 1];
-        num += w * part_o[prow * D + d];
+  const int qcol = lane & 31, g = lane >> 5, m = lane & 31;
+  const int64_t blk = 2 * PAGE * D;
+  const int koff = g * 128 + (m & 15) * 8, voff = PAGE * D + g * 256 + m * 8;
+  const int seg_end = wave_seg[gw + 1];
+  for (int sg = wave_seg[gw]; sg < seg_end; ++sg) {
+    const DecodeSeg it = segs[sg];
+    const int hk = it.hk;
+    const int rows = it.n_new * G;
+    const bool valid = qcol < rows;
+    const int i_tok = valid ? qcol / G : 0;
+    const int hg = valid ? qcol % G : 0;
+    const bool has_bitmap = it.wpr > 0;
+    bf16x8 qf[D / 16];
+    load_q<D>(a.q + (int64_t)(it.tok0 + i_tok) * a.q_stride + (hk * G + hg) * D, valid, g, qf);
+    // page ids of the segment live across the lanes of two registers (<= 128 pages per segment)
+    const int n_pg = it.n_pg;
+    const int vphys_lo = lane < n_pg ? a.visit_phys[it.v0 + lane] : 0;
+    const int vphys_hi = lane + 64 < n_pg ? a.visit_phys[it.v0 + lane + 64] : 0;
+    const int vlog_lo = lane < n_pg ? a.visit_logical[it.v0 + lane] : 0;
+    const int vlog_hi = lane + 64 < n_pg ? a.visit_logical[it.v0 + lane + 64] : 0;
+    auto page_of = [&](int i, int& phys, int& logical) {  // i is wave-uniform
+      const int src = i & 63;
+      phys = __builtin_amdgcn_readlane(i < 64 ? vphys_lo : vphys_hi, src);
+      logical = __builtin_amdgcn_readlane(i < 64 ? vlog_lo : vlog_hi, src);
+    };
+    const uint32_t* mrow = a.mask_words + it.mask_off + (int64_t)i_tok * it.wpr;
+    AttnState<D> st;
+    attn_init<D>(st);
+    bf16x8 kf[D / 16], va[D / 32], vb[D / 32];
+    auto load_k = [&](int pp_a, int pp_b) {
+      const bf16_t* kb = a.kv + ((int64_t)(m < 16 ? pp_a : pp_b) * a.Hkv + hk) * blk + koff;
+#pragma unroll
+      for (int k = 0; k < D / 16; ++k) kf[k] = *reinterpret_cast<const bf16x8*>(kb + k * 256);
+    };
+    auto load_v = [&](int pp_a, int pp_b) {
+      const bf16_t* ba = a.kv + ((int64_t)pp_a * a.Hkv + hk) * blk + voff;
+      const bf16_t* bb = a.kv + ((int64_t)pp_b * a.Hkv + hk) * blk + voff;
+#pragma unroll
+      for (int b = 0; b < D / 32; ++b) {
+        va[b] = *reinterpret_cast<const bf16x8*>(ba + b * 512);
+        vb[b] = *reinterpret_cast<const bf16x8*>(bb + b * 512);
+      }
+    };
+    int pp_a = 0, pp_b = 0, pl_a = 0, pl_b = 0;
+    uint32_t mw_a = 0u, mw_b = 0u;  // mask words of the pair whose K/V are in the registers
+    bool has_b = false;
+    auto pick = [&](int i) {
+      page_of(i, pp_a, pl_a);
+      has_b = i + 1 < n_pg;
+      if (has_b) page_of(i + 1, pp_b, pl_b);
+      else { pp_b = pp_a; pl_b = pl_a; }
+    };
+    if (n_pg > 0) {
+      pick(0);
+      if (has_bitmap && valid) { mw_a = mrow[pl_a >> 1]; mw_b = mrow[pl_b >> 1]; }
+      load_k(pp_a, pp_b);
+      load_v(pp_a, pp_b);
+    }
+    for (int i = 0; i < n_pg; i += 2) {
+      const uint32_t bits_a = key_bits_w(it.kv_len, it.n_new, has_bitmap, mw_a, i_tok, pl_a, g, valid);
+      const uint32_t bits_b = has_b ? key_bits_w(it.kv_len, it.n_new, has_bitmap, mw_b, i_tok, pl_b, g, valid) : 0u;
+      f32x16 s;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+      for (int k = 0; k < D / 16; ++k) s = mfma32(kf[k], qf[k], s);
+      const bool more = i + 2 < n_pg;
+      if (more) {
+        pick(i + 2);
+        if (has_bitmap && valid) { mw_a = mrow[pl_a >> 1]; mw_b = mrow[pl_b >> 1]; }
+        load_k(pp_a, pp_b);
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const bool on = ((v < 8 ? (bits_a >> v) : (bits_b >> (v - 8))) & 1u) != 0u;
+        s[v] = on ? s[v] * a.scale_log2 : -INFINITY;
+        mx = fmaxf(mx, s[v]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(st.m, mx);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+      float lsum = 0.f;
+      Pack16 pa, pb;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(s[v] - m_safe);
+        lsum += p;
+        if (v < 8) pa.h[v] = f32_to_bf16(p);
+        else pb.h[v - 8] = f32_to_bf16(p);
+      }
+      st.l = st.l * alpha + lsum;
+      st.m = m_new;
+#pragma unroll
+      for (int b = 0; b < D / 32; ++b) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st.o[b][v] *= alpha;
+        st.o[b] = mfma32(va[b], pa.h, st.o[b]);
+        st.o[b] = mfma32(vb[b], pb.h, st.o[b]);
+      }
+      if (more) load_v(pp_a, pp_b);
+    }
+    const float l_tot = st.l + __shfl_xor(st.l, 32);
+    if (valid) {
+      const int64_t prow = (int64_t)sg * rows_cap + qcol;
+      if (g == 0) {
+        part_ml[prow * 2] = st.m;
+        part_ml[prow * 2 + 1] = l_tot;
+      }
+      float* po = part_o + prow * D;
+#pragma unroll
+      for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 o4 = {st.o[b][q4 * 4], st.o[b][q4 * 4 + 1], st.o[b][q4 * 4 + 2], st.o[b][q4 * 4 + 3]};
+          *reinterpret_cast<f32x4*>(po + b * 32 + q4 * 8 + g * 4) = o4;
+        }
+    }
+  }
+}
+
+// One wave per (decode-path request, kv head, query row): lanes first share the segments' (max, sum) pairs,
+// then each lane combines D/64 output elements over the segments with independent loads.
+template <int D>
+__global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, const int32_t* __restrict__ dec_reqs,
+                                                        const SegRange* __restrict__ ranges, int rows_cap,
+                                                        const float* __restrict__ part_o,
+                                                        const float* __restrict__ part_ml) {
+  const ReqInfo rq = a.reqs[dec_reqs[blockIdx.x]];
+  const int hk = blockIdx.y, row = blockIdx.z, lane = threadIdx.x;
+  const int G = a.Hq / a.Hkv;
+  if (row >= rq.n_new * G) return;
+  const SegRange rg = ranges[blockIdx.x * a.Hkv + hk];
+  constexpr int E = D / 64;
+  float num[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) num[e] = 0.f;
+  auto prow_of = [&](int c) { return (int64_t)(rg.first + c) * rows_cap + row; };
+  float M = -INFINITY;
+  for (int c = lane; c < rg.count; c += 64) M = fmaxf(M, part_ml[prow_of(c) * 2]);
+  M = wave_max(M);
+  float den = 0.f;
+  if (M != -INFINITY) {
+    for (int c0 = 0; c0 < rg.count; c0 += 64) {
+      const int c = c0 + lane;
+      float w = 0.f;
+      if (c < rg.count) {
+        w = __builtin_amdgcn_exp2f(part_ml[prow_of(c) * 2] - M);
+        den += w * part_ml[prow_of(c) * 2 + 1];
+      }
+      const int cnt = min(64, rg.count - c0);
+      for (int j = 0; j < cnt; ++j) {
+        const float wj = __shfl(w, j);
+        const float* po = part_o + prow_of(c0 + j) * D + lane * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] += wj * po[e];
       }
     }
-    const float o = den > 0.f ? num / den : 0.f;
-    const int i_tok = row / G, hg = row % G;
-    a.out[(int64_t)(rq.tok0 + i_tok) * a.Hq * D + (hk * G + hg) * D + d] = f32_to_bf16(o);
+    den = wave_sum(den);
   }
+  const float inv = den > 0.f ? 1.0f / den : 0.f;
+  const int i_tok = row / G, hg = row % G;
+  bf16_t* out = a.out + (int64_t)(rq.tok0 + i_tok) * a.Hq * D + (hk * G + hg) * D + lane * E;
+#pragma unroll
+  for (int e = 0; e < E; ++e) out[e] = f32_to_bf16(num[e] * inv);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -262,22 +387,22 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnArgs a, const Pre
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_attn_decode(const AttnArgs& a, const DecodeItem* items, int n_items, int rows_cap, float* part_o,
-                              float* part_ml, hipStream_t s) {
-  if (n_items <= 0) return hipSuccess;
-  dim3 grid((n_items + 3) / 4, a.Hkv), block(256);
-  if (a.D == 128) attn_decode_kernel<128><<<grid, block, 0, s>>>(a, items, n_items, rows_cap, part_o, part_ml);
-  else if (a.D == 64) attn_decode_kernel<64><<<grid, block, 0, s>>>(a, items, n_items, rows_cap, part_o, part_ml);
+hipError_t launch_attn_decode(const AttnArgs& a, const DecodeSeg* segs, const int32_t* wave_seg, int n_waves,
+                              int rows_cap, float* part_o, float* part_ml, hipStream_t s) {
+  if (n_waves <= 0) return hipSuccess;
+  dim3 grid((n_waves + 3) / 4), block(256);
+  if (a.D == 128) attn_decode_kernel<128><<<grid, block, 0, s>>>(a, segs, wave_seg, n_waves, rows_cap, part_o, part_ml);
+  else if (a.D == 64) attn_decode_kernel<64><<<grid, block, 0, s>>>(a, segs, wave_seg, n_waves, rows_cap, part_o, part_ml);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
-hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, int rows_cap,
-                             const float* part_o, const float* part_ml, hipStream_t s) {
+hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const SegRange* ranges,
+                             int rows_cap, const float* part_o, const float* part_ml, hipStream_t s) {
   if (n_dec_reqs <= 0) return hipSuccess;
-  dim3 grid(n_dec_reqs, a.Hkv), block(a.D);
-  if (a.D == 128) attn_merge_kernel<128><<<grid, block, 0, s>>>(a, dec_reqs, rows_cap, part_o, part_ml);
-  else if (a.D == 64) attn_merge_kernel<64><<<grid, block, 0, s>>>(a, dec_reqs, rows_cap, part_o, part_ml);
+  dim3 grid(n_dec_reqs, a.Hkv, rows_cap), block(64);
+  if (a.D == 128) attn_merge_kernel<128><<<grid, block, 0, s>>>(a, dec_reqs, ranges, rows_cap, part_o, part_ml);
+  else if (a.D == 64) attn_merge_kernel<64><<<grid, block, 0, s>>>(a, dec_reqs, ranges, rows_cap, part_o, part_ml);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -308,13 +308,15 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restric
 // ------------------------------------------------------------------------------------------------
 template <int MB, int MODE>
 static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
-                             size_t ws_elems, hipStream_t s) {
+                             size_t ws_elems, int n_cus, hipStream_t s) {
   constexpr int NBW = (MODE == EPI_SWIGLU) ? 2 : 1;
   const int wg_n = (W.NB + 4 * NBW - 1) / (4 * NBW);
   const int total_iters = (W.K + SK_BK - 1) / SK_BK;
-  int splits = 1;
-  const int target_wgs = 512;
-  if (wg_n < target_wgs) splits = (target_wgs + wg_n - 1) / wg_n;
+  // Split K so that one round of workgroups fills the chip without spilling into a second, mostly empty round:
+  // the kernel keeps `occ` workgroups per CU resident (register-limited).
+  const int occ = (MB == 1 && MODE != EPI_SWIGLU) ? 3 : ((MB <= 2 && !(MB == 2 && MODE == EPI_SWIGLU)) ? 2 : 1);
+  const int slots = n_cus * occ;
+  int splits = slots / wg_n;
   if (splits > total_iters / 2) splits = total_iters / 2;
   if (splits < 1) splits = 1;
   const int NP = W.NB * 32;
@@ -344,12 +346,12 @@ static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight
 
 template <int MODE>
 static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
-                           size_t ws_elems, hipStream_t s) {
+                           size_t ws_elems, int n_cus, hipStream_t s) {
   if (M <= 0) return hipSuccess;
-  if (M <= 32) return run_skinny<1, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
-  if (M <= 64) return run_skinny<2, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
-  if (M <= 128) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
-  if (M <= 256 && MODE != EPI_SWIGLU) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, s);
+  if (M <= 32) return run_skinny<1, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 64) return run_skinny<2, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 128) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 256 && MODE != EPI_SWIGLU) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   auto kern = gemm_large_kernel<MODE>;
   size_t smem = (size_t)4 * LG_BM * LG_BK * sizeof(bf16_t);
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -360,13 +362,13 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
 }
 
 hipError_t launch_gemm(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* splitk_ws,
-                       size_t splitk_elems, hipStream_t s) {
+                       size_t splitk_elems, int n_cus, hipStream_t s) {
   switch (epi.mode) {
-    case EPI_STORE_BF16: return run_mode<EPI_STORE_BF16>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
-    case EPI_RESID_EMBED: return run_mode<EPI_RESID_EMBED>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
-    case EPI_SWIGLU: return run_mode<EPI_SWIGLU>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
-    case EPI_RESID_OUT: return run_mode<EPI_RESID_OUT>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
-    case EPI_STORE_F32: return run_mode<EPI_STORE_F32>(A, lda, M, W, epi, splitk_ws, splitk_elems, s);
+    case EPI_STORE_BF16: return run_mode<EPI_STORE_BF16>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
+    case EPI_RESID_EMBED: return run_mode<EPI_RESID_EMBED>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
+    case EPI_SWIGLU: return run_mode<EPI_SWIGLU>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
+    case EPI_RESID_OUT: return run_mode<EPI_RESID_OUT>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
+    case EPI_STORE_F32: return run_mode<EPI_STORE_F32>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
   }
   return hipErrorInvalidValue;
 }

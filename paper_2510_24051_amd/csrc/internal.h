@@ -48,11 +48,18 @@ struct ReqInfo {       // one per request, device + host
   int32_t n_visit;     // pages with at least one visible key, logical order
   int32_t wpr;         // mask words per row (0: inferred causal)
   int64_t mask_off;    // word offset of the request's first row
-  int32_t item0;       // first decode work item (decode path) or -1
-  int32_t n_items;     // decode work items (split-K chunks)
+  int32_t dec_index;   // index among the decode-path requests, or -1
+  int32_t pad;
 };
 
-struct DecodeItem { int32_t r, v0, v1, pad; };   // visit-list range [v0, v1) of request r (absolute indices)
+struct DecodeSeg {     // a run of page pairs of one (decode-path request, kv head), processed by one wave
+  int32_t tok0, n_new, kv_len;
+  int32_t v0, n_pg;    // visit-list entries [v0, v0 + n_pg), n_pg <= 128
+  int32_t wpr;
+  int64_t mask_off;
+  int32_t hk, pad;
+};
+struct SegRange { int32_t first, count; };  // segments of one (decode-path request, kv head), in key order
 struct PrefillItem { int32_t r, qb; };           // query block qb (32 tokens) of request r
 
 struct pie_batch {
@@ -62,12 +69,14 @@ struct pie_batch {
   int32_t *visit_phys = nullptr, *visit_logical = nullptr;
   uint32_t* mask_words = nullptr;
   ReqInfo* reqs = nullptr;
-  DecodeItem* ditems = nullptr;
+  DecodeSeg* dsegs = nullptr;
+  int32_t* wave_seg = nullptr;   // [n_dwaves + 1] segments of each wave
+  SegRange* seg_ranges = nullptr;  // [n_dec_reqs * Hkv]
   PrefillItem* pitems = nullptr;
   int32_t* dec_reqs = nullptr;  // request indices on the decode path
-  int32_t n_ditems = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
-  float* part_o = nullptr;   // [n_ditems * Hkv * rows_cap, D]
-  float* part_ml = nullptr;  // [n_ditems * Hkv * rows_cap, 2]
+  int32_t n_dsegs = 0, n_dwaves = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
+  float* part_o = nullptr;   // [n_dsegs * rows_cap, D]
+  float* part_ml = nullptr;  // [n_dsegs * rows_cap, 2]
   int64_t work[4] = {0, 0, 0, 0};
 };
 
@@ -76,6 +85,7 @@ struct pie_ctx {
   pie_pool_desc p;
   hipStream_t stream = nullptr;
   int device = 0;
+  int wave_slots = 2048;  // waves the chip keeps resident for the decode-attention kernel
   bf16_t* embeds = nullptr;
   bf16_t* kv = nullptr;
   size_t kv_layer_elems = 0;
@@ -86,7 +96,8 @@ struct pie_ctx {
   double* inv_freq = nullptr;
   // workspace
   bf16_t *xn = nullptr, *qkv = nullptr, *attn = nullptr, *act = nullptr, *en = nullptr;
-  float *h = nullptr, *splitk = nullptr, *logits = nullptr;
+  float *h = nullptr, *splitk = nullptr, *logits = nullptr, *topk_stats = nullptr;
+  unsigned long long* topk_cand = nullptr;
   size_t splitk_elems = 0;
   int32_t* ids_dev = nullptr;  // staging for id lists of the small resource calls
   size_t ids_cap = 0;
@@ -130,7 +141,7 @@ struct EpiArgs {
 };
 // C[M, N] = A[M, K] (bf16 row-major, leading dimension lda) x W^T with the epilogue above.
 hipError_t launch_gemm(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* splitk_ws,
-                       size_t splitk_elems, hipStream_t s);
+                       size_t splitk_elems, int n_cus, hipStream_t s);
 
 struct AttnArgs {
   const bf16_t* q;   // [T, q_stride] rotated queries
@@ -144,11 +155,13 @@ struct AttnArgs {
   const int32_t* visit_logical;
   const uint32_t* mask_words;
 };
-hipError_t launch_attn_decode(const AttnArgs& a, const DecodeItem* items, int n_items, int rows_cap, float* part_o,
-                              float* part_ml, hipStream_t s);
-hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, int rows_cap,
-                             const float* part_o, const float* part_ml, hipStream_t s);
+hipError_t launch_attn_decode(const AttnArgs& a, const DecodeSeg* segs, const int32_t* wave_seg, int n_waves,
+                              int rows_cap, float* part_o, float* part_ml, hipStream_t s);
+hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const SegRange* ranges,
+                             int rows_cap, const float* part_o, const float* part_ml, hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s);
 
+int topk_chunks(int V, int k);  // chunks per row used by launch_topk (<= 16), 0 if unsupported
+// cand_ws: [n, chunks, k] 64-bit candidates; stats_ws: [n, chunks, 2] floats
 hipError_t launch_topk(const float* logits, int n, int V, int k, float inv_temp, int32_t* out_ids, float* out_probs,
-                       hipStream_t s);
+                       unsigned long long* cand_ws, float* stats_ws, hipStream_t s);

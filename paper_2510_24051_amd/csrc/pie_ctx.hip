@@ -53,6 +53,8 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   if (m->hidden <= 0 || m->hidden % 32 || m->mlp_dim <= 0 || m->mlp_dim % 32 || m->vocab < 0 || m->vocab % 32 ||
       m->hidden > 8192)
     return fail(nullptr, PIE_EUNSUPPORTED, "hidden (<= 8192), mlp_dim and vocab must be multiples of 32");
+  if (m->vocab > 0 && topk_chunks(m->vocab, 1) == 0)
+    return fail(nullptr, PIE_EUNSUPPORTED, "vocab %d: the top-k kernels handle up to 131072 entries", m->vocab);
   if (m->n_layers <= 0 || !(m->rms_eps > 0.f) || !(m->rope_theta > 0.f))
     return fail(nullptr, PIE_EINVAL, "n_layers, rms_eps and rope_theta must be positive");
   if (p->n_kv_pages <= 0 || p->n_embeds <= 0 || p->max_batch_tokens <= 0 || p->max_batch_requests <= 0 ||
@@ -67,6 +69,11 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   for (int i = 0; i < PIE_N_STAGES; ++i) c->ev_used[i] = false;
   for (int i = 0; i < 2 * PIE_N_STAGES; ++i) c->ev[i] = nullptr;
   hipError_t e = hipGetDevice(&c->device);
+  {
+    int cus = 0;
+    if (e == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
+      c->wave_slots = cus * 8;  // the decode kernel runs two waves per SIMD
+  }
   const int H = m->hidden, QD = m->n_q_heads * m->head_dim, KD = m->n_kv_heads * m->head_dim, I = m->mlp_dim;
   const size_t T = (size_t)p->max_batch_tokens;
   c->layers.resize(m->n_layers);
@@ -89,6 +96,8 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   if (m->vocab > 0 && p->max_dist_rows > 0) {
     chk(dev_alloc(&c->logits, (size_t)p->max_dist_rows * m->vocab, false, c->stream));
     chk(dev_alloc(&c->en, (size_t)p->max_dist_rows * H, false, c->stream));
+    chk(dev_alloc(&c->topk_cand, (size_t)p->max_dist_rows * 16 * std::max(p->max_top_k, 1), false, c->stream));
+    chk(dev_alloc(&c->topk_stats, (size_t)p->max_dist_rows * 16 * 2, false, c->stream));
   }
   c->ids_cap = std::max<size_t>(4096, 2 * T);
   chk(dev_alloc(&c->ids_dev, c->ids_cap, false, c->stream));
@@ -124,7 +133,7 @@ extern "C" pie_status pie_destroy(pie_ctx* c) {
   }
   free_packed(c->wlm);
   void* bufs[] = {c->embeds, c->kv, c->xn, c->qkv, c->attn, c->h, c->act, c->splitk, c->logits, c->en,
-                  c->ids_dev, c->inv_freq, c->g_final};
+                  c->ids_dev, c->inv_freq, c->g_final, c->topk_cand, c->topk_stats};
   for (void* b : bufs) if (b) (void)hipFree(b);
   for (int i = 0; i < 2 * PIE_N_STAGES; ++i) if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
   delete c;
@@ -304,7 +313,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
     ReqInfo& q = reqs[r];
     q.tok0 = t0; q.n_new = n_new; q.kv_len = L;
     q.visit0 = (int32_t)visit_phys.size();
-    q.wpr = 0; q.mask_off = 0; q.item0 = -1; q.n_items = 0;
+    q.wpr = 0; q.mask_off = 0; q.dec_index = -1; q.pad = 0;
     for (int i = 0; i < n_new; ++i) {
       const int t = t0 + i, j = L - n_new + i;
       if (b->in_embed_ids[t] < 0 || b->in_embed_ids[t] >= c->p.n_embeds)
@@ -341,6 +350,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
     const bool decode_path = n_new * G <= 32;
     int64_t visited_pages = 0;
     if (decode_path) {
+      q.dec_index = (int32_t)dec_reqs.size();
       dec_reqs.push_back(r);
       rows_cap = std::max(rows_cap, n_new * G);
       visited_pages = q.n_visit;
@@ -363,30 +373,40 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
       if (!seen.insert((int64_t)tok_page[t] * PAGE + tok_slot[t]).second)
         return fail(c, PIE_ECONFLICT, "token %d writes (page %d, slot %d) that another token of the batch writes", t, tok_page[t], tok_slot[t]);
   }
-  // split the decode-path visit lists into chunks of page pairs: aim for a few thousand waves
-  std::vector<DecodeItem> ditems;
+  // Decode path: the page pairs of all (request, kv head) combinations form one flat list that is cut into
+  // equal shares, one per wave, for as many waves as the chip keeps resident.  A share may cover the end of
+  // one (request, head) and the start of the next; each such run is a segment with its own partial result.
+  std::vector<DecodeSeg> dsegs;
+  std::vector<int32_t> wave_seg(1, 0);
+  std::vector<SegRange> seg_ranges(dec_reqs.size() * Hkv, SegRange{0, 0});
   {
     int64_t total_pairs = 0;
-    for (int r : dec_reqs) total_pairs += (reqs[r].n_visit + 1) / 2;
-    total_pairs *= Hkv;
-    int64_t ch = total_pairs / 4096;
-    ch = std::max<int64_t>(2, std::min<int64_t>(64, ch));
-    for (int r : dec_reqs) {
-      ReqInfo& q = reqs[r];
-      q.item0 = (int32_t)ditems.size();
-      const int pages_per_item = (int)ch * 2;
-      int n_it = std::max(1, (q.n_visit + pages_per_item - 1) / pages_per_item);
-      // even split so the last chunk is not a sliver
-      int per = ((q.n_visit + n_it - 1) / n_it + 1) / 2 * 2;
-      if (per < 2) per = 2;
-      int made = 0;
-      for (int v = 0; v < q.n_visit || made == 0; v += per) {
-        ditems.push_back(DecodeItem{r, q.visit0 + v, q.visit0 + std::min(q.n_visit, v + per), 0});
-        ++made;
-        if (q.n_visit == 0) break;
+    for (int r : dec_reqs) total_pairs += (int64_t)((reqs[r].n_visit + 1) / 2) * Hkv;
+    int64_t per_wave = (total_pairs + c->wave_slots - 1) / c->wave_slots;
+    per_wave = std::max<int64_t>(per_wave, 2);
+    int64_t filled = 0;
+    for (size_t di = 0; di < dec_reqs.size(); ++di) {
+      const ReqInfo& q = reqs[dec_reqs[di]];
+      const int P = (q.n_visit + 1) / 2;
+      for (int hk = 0; hk < Hkv; ++hk) {
+        SegRange& rg = seg_ranges[di * Hkv + hk];
+        rg.first = (int32_t)dsegs.size();
+        int p = 0;
+        while (p < P) {
+          int take = (int)std::min<int64_t>(std::min<int64_t>(per_wave - filled, P - p), 64);
+          dsegs.push_back(DecodeSeg{q.tok0, q.n_new, q.kv_len, q.visit0 + 2 * p, std::min(q.n_visit - 2 * p, 2 * take),
+                                    q.wpr, q.mask_off, hk, 0});
+          p += take;
+          filled += take;
+          if (filled == per_wave) {
+            wave_seg.push_back((int32_t)dsegs.size());
+            filled = 0;
+          }
+        }
+        rg.count = (int32_t)dsegs.size() - rg.first;
       }
-      q.n_items = made;
     }
+    if (wave_seg.back() != (int32_t)dsegs.size()) wave_seg.push_back((int32_t)dsegs.size());
   }
   // heavy query blocks first
   std::stable_sort(pitems.begin(), pitems.end(), [&](const PrefillItem& x, const PrefillItem& y) {
@@ -399,7 +419,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
 
   pie_batch* pb = new pie_batch();
   pb->R = R; pb->T = T;
-  pb->n_ditems = (int32_t)ditems.size();
+  pb->n_dsegs = (int32_t)dsegs.size();
+  pb->n_dwaves = (int32_t)wave_seg.size() - 1;
   pb->n_pitems = (int32_t)pitems.size();
   pb->n_dec_reqs = (int32_t)dec_reqs.size();
   pb->rows_cap = std::max(rows_cap, 1);
@@ -413,10 +434,12 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   const size_t n_mask = b->mask_indptr ? (size_t)b->mask_indptr[R] : 0;
   const size_t o_mw = blob.add(n_mask ? b->mask_words : nullptr, n_mask * 4, 4);
   const size_t o_rq = blob.add(reqs.data(), reqs.size() * sizeof(ReqInfo));
-  const size_t o_di = blob.add(ditems.data(), ditems.size() * sizeof(DecodeItem), 16);
+  const size_t o_di = blob.add(dsegs.data(), dsegs.size() * sizeof(DecodeSeg), 16);
+  const size_t o_ws = blob.add(wave_seg.data(), wave_seg.size() * 4, 4);
+  const size_t o_sr = blob.add(seg_ranges.data(), seg_ranges.size() * sizeof(SegRange), 8);
   const size_t o_pi = blob.add(pitems.data(), pitems.size() * sizeof(PrefillItem), 8);
   const size_t o_dr = blob.add(dec_reqs.data(), dec_reqs.size() * 4, 4);
-  const size_t part_rows = (size_t)pb->n_ditems * Hkv * pb->rows_cap;
+  const size_t part_rows = (size_t)pb->n_dsegs * pb->rows_cap;
   const size_t o_po = blob.add(nullptr, 0, 0);  // metadata ends here; the partial buffers are device-only
   const size_t o_pm = (o_po + part_rows * D * 4 + 255) / 256 * 256;
   const size_t total_bytes = o_pm + part_rows * 2 * 4 + 256;
@@ -438,7 +461,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   pb->tok_page = (int32_t*)(d + o_tp); pb->tok_slot = (int32_t*)(d + o_ts);
   pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl);
   pb->mask_words = (uint32_t*)(d + o_mw); pb->reqs = (ReqInfo*)(d + o_rq);
-  pb->ditems = (DecodeItem*)(d + o_di); pb->pitems = (PrefillItem*)(d + o_pi); pb->dec_reqs = (int32_t*)(d + o_dr);
+  pb->dsegs = (DecodeSeg*)(d + o_di); pb->wave_seg = (int32_t*)(d + o_ws); pb->seg_ranges = (SegRange*)(d + o_sr);
+  pb->pitems = (PrefillItem*)(d + o_pi); pb->dec_reqs = (int32_t*)(d + o_dr);
   pb->part_o = (float*)(d + o_po); pb->part_ml = (float*)(d + o_pm);
   *out = pb;
   return PIE_OK;
@@ -493,7 +517,7 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
 
   tm.begin(PIE_STAGE_QKV);
   e = EpiArgs{EPI_STORE_BF16, c->qkv, QKV, nullptr, nullptr, nullptr, 0};
-  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wqkv, e, c->splitk, c->splitk_elems, s));
+  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wqkv, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_QKV);
 
   tm.begin(PIE_STAGE_ROPE_APPEND);
@@ -504,12 +528,12 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
   a.q = c->qkv; a.q_stride = QKV; a.kv = kv_layer; a.out = c->attn; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
   a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
   a.reqs = b->reqs; a.visit_phys = b->visit_phys; a.visit_logical = b->visit_logical; a.mask_words = b->mask_words;
-  if (b->n_ditems > 0) {
+  if (b->n_dec_reqs > 0) {
     tm.begin(PIE_STAGE_ATTN_DECODE);
-    HIP_TRY(c, launch_attn_decode(a, b->ditems, b->n_ditems, b->rows_cap, b->part_o, b->part_ml, s));
+    HIP_TRY(c, launch_attn_decode(a, b->dsegs, b->wave_seg, b->n_dwaves, b->rows_cap, b->part_o, b->part_ml, s));
     tm.end(PIE_STAGE_ATTN_DECODE);
     tm.begin(PIE_STAGE_ATTN_MERGE);
-    HIP_TRY(c, launch_attn_merge(a, b->dec_reqs, b->n_dec_reqs, b->rows_cap, b->part_o, b->part_ml, s));
+    HIP_TRY(c, launch_attn_merge(a, b->dec_reqs, b->n_dec_reqs, b->seg_ranges, b->rows_cap, b->part_o, b->part_ml, s));
     tm.end(PIE_STAGE_ATTN_MERGE);
   }
   if (b->n_pitems > 0) {
@@ -520,7 +544,7 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
 
   tm.begin(PIE_STAGE_OPROJ);
   e = EpiArgs{EPI_RESID_EMBED, c->h, H, c->embeds, b->in_ids, nullptr, H};
-  HIP_TRY(c, launch_gemm(c->attn, Hq * D, T, L.wo, e, c->splitk, c->splitk_elems, s));
+  HIP_TRY(c, launch_gemm(c->attn, Hq * D, T, L.wo, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_OPROJ);
 
   tm.begin(PIE_STAGE_NORM2);
@@ -529,12 +553,12 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
 
   tm.begin(PIE_STAGE_GATEUP);
   e = EpiArgs{EPI_SWIGLU, c->act, I, nullptr, nullptr, nullptr, 0};
-  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wgu, e, c->splitk, c->splitk_elems, s));
+  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wgu, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_GATEUP);
 
   tm.begin(PIE_STAGE_DOWN);
   e = EpiArgs{EPI_RESID_OUT, nullptr, 0, c->embeds, b->out_ids, c->h, H};
-  HIP_TRY(c, launch_gemm(c->act, I, T, L.wdown, e, c->splitk, c->splitk_elems, s));
+  HIP_TRY(c, launch_gemm(c->act, I, T, L.wdown, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_DOWN);
   c->last_T = T;
   return PIE_OK;
@@ -579,10 +603,10 @@ extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, in
   tm.end(PIE_STAGE_HEAD_NORM);
   tm.begin(PIE_STAGE_LM_HEAD);
   EpiArgs e{EPI_STORE_F32, c->logits, V, nullptr, nullptr, nullptr, 0};
-  HIP_TRY(c, launch_gemm(c->en, H, n, c->wlm, e, c->splitk, c->splitk_elems, s));
+  HIP_TRY(c, launch_gemm(c->en, H, n, c->wlm, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_LM_HEAD);
   tm.begin(PIE_STAGE_TOPK);
-  HIP_TRY(c, launch_topk(c->logits, n, V, top_k, 1.0f / temperature, out_ids, out_probs, s));
+  HIP_TRY(c, launch_topk(c->logits, n, V, top_k, 1.0f / temperature, out_ids, out_probs, c->topk_cand, c->topk_stats, s));
   tm.end(PIE_STAGE_TOPK);
   c->last_dist_n = n;
   return PIE_OK;
