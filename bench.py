@@ -120,7 +120,7 @@ def main():
 
     m = w.model
     kv_token_bytes = 2 * m.n_kv_heads * m.head_dim * 2
-    dec_tokens = sum(int(b.kv_len[r]) for r in range(b.n_requests) if (b.tok_indptr[r + 1] - b.tok_indptr[r]) * (m.n_q_heads // m.n_kv_heads) <= 32)
+    dec_tokens = sum(int(b.kv_len[r]) for r in range(b.n_requests) if (b.tok_indptr[r + 1] - b.tok_indptr[r]) * (m.n_q_heads // m.n_kv_heads) <= 16)
     attn_bytes = work["kv_bytes_decode"] if b.mask_indptr is not None else dec_tokens * kv_token_bytes
     attn_ms = stages.get("attn_decode", 0.0)
     achieved = attn_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0

@@ -13,6 +13,8 @@
 //                  unnormalised partial (running max, sum, O) that attn_merge combines.
 //   attn_prefill : one workgroup per (request, 32-token query block, kv head), one wave per query head of
 //                  the group; causal requests stop at the block's last visible page.
+#include <type_traits>
+
 #include "internal.h"
 
 template <int D>
@@ -132,41 +134,58 @@ __device__ __forceinline__ void load_q(const bf16_t* __restrict__ qrow, bool val
 // ------------------------------------------------------------------------------------------------
 // decode: split-K partials
 // ------------------------------------------------------------------------------------------------
-// Visible-key bits from a preloaded mask word (bitmap requests) or from the causal rule.
-__device__ __forceinline__ uint32_t key_bits_w(int kv_len, int n_new, bool has_bitmap, uint32_t word, int i_tok, int pl,
-                                               int g, bool row_valid) {
+// 16x16x32 MFMA: A is 16x32 (lane l: row l % 16, contraction elements (l / 16) * 8 .. + 8), B is 32x16 (lane l:
+// column l % 16, same contraction elements), C/D 16x16 (lane l: column l % 16, register i is row (l / 16) * 4 + i).
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Visible-key bits of the 4 keys j0 .. j0+3 of a page (j0 = logical index of the first), from a preloaded
+// mask word (bitmap requests) or from the causal rule.
+__device__ __forceinline__ uint32_t key_bits4(int kv_len, int n_new, bool has_bitmap, uint32_t word, int i_tok, int pl,
+                                              int quad, bool row_valid) {
   if (!row_valid) return 0u;
-  const int j0 = pl * PAGE + g * 8;
+  const int j0 = pl * PAGE + quad * 4;
   int cnt = kv_len - j0;
-  cnt = cnt < 0 ? 0 : (cnt > 8 ? 8 : cnt);
+  cnt = cnt < 0 ? 0 : (cnt > 4 ? 4 : cnt);
   uint32_t bits = (1u << cnt) - 1u;
   if (has_bitmap) {
-    bits &= (word >> ((pl & 1) * 16 + g * 8)) & 0xFFu;
+    bits &= (word >> ((pl & 1) * 16 + quad * 4)) & 0xFu;
   } else {
     int lim = kv_len - n_new + i_tok - j0 + 1;
-    lim = lim < 0 ? 0 : (lim > 8 ? 8 : lim);
+    lim = lim < 0 ? 0 : (lim > 4 ? 4 : lim);
     bits &= (1u << lim) - 1u;
   }
   return bits;
 }
 
+// Decode attention (requests with n_new * group <= 16 query rows), HBM-bound.
 // Grid: one wave per equal share of the flattened (request, kv head, page pair) list; a wave walks the
-// segments of its share.  Per segment: query operands and page ids are fetched once, then K and V stream
-// through one register set each - K of the next pair is requested as soon as the QK^T MFMAs have consumed
-// this pair's K, V of the next pair (and its mask words) as soon as the PV MFMAs have consumed this pair's V;
-// the second wave on the SIMD covers the rest of the latency.
+// segments of its share and writes one unnormalised partial (running max, sum, O) per segment.
+// Per page pair and kv head, on 16x16x32 MFMAs (16 query columns, so accumulators are half the size of the
+// 32-wide prefill tile and two waves per SIMD fit with K and V double-buffered in registers):
+//     S^T[16 keys, 16 q]  = K_page[16, D] Q^T[D, 16]          per page, D/32 MFMAs; a K operand is one
+//                                                              contiguous 1 KiB load per (page, 32 dims)
+//     O^T[D, 16 q]       += V^T[D, 32 keys] P^T[32, 16]       D/16 MFMAs over both pages at once
+// MFMA row r of a K operand is key swap23(r), so lane group g4 = lane / 16 ends up with keys
+// 4*sigma(g4) .. +3 of each page (sigma swaps the two bits of g4); P^T is then the lane's own S registers.
+// The whole next pair (16 KiB per wave) and its mask words are requested before this pair is computed.
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const DecodeSeg* __restrict__ segs,
                                                              const int32_t* __restrict__ wave_seg, int n_waves,
                                                              int rows_cap, float* __restrict__ part_o,
                                                              float* __restrict__ part_ml) {
+  constexpr int KS = D / 32;  // K operands per page
+  constexpr int DB = D / 16;  // 16-row blocks of O^T
   const int lane = threadIdx.x & 63;
   const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (gw >= n_waves) return;
   const int G = a.Hq / a.Hkv;
-  const int qcol = lane & 31, g = lane >> 5, m = lane & 31;
+  const int qcol = lane & 15, g4 = lane >> 4;
+  const int quad = ((g4 & 1) << 1) | (g4 >> 1);  // sigma(g4): this lane group's key quad within a page
   const int64_t blk = 2 * PAGE * D;
-  const int koff = g * 128 + (m & 15) * 8, voff = PAGE * D + g * 256 + m * 8;
+  const int koff = lane * 8;                                                    // + s32 * 512 elements
+  const int voff = PAGE * D + (quad >> 1) * 256 + qcol * 8 + (quad & 1) * 4;    // + (d / 32) * 512 + ((d / 16) & 1) * 128
   const int seg_end = wave_seg[gw + 1];
   for (int sg = wave_seg[gw]; sg < seg_end; ++sg) {
     const DecodeSeg it = segs[sg];
@@ -176,8 +195,17 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
     const int i_tok = valid ? qcol / G : 0;
     const int hg = valid ? qcol % G : 0;
     const bool has_bitmap = it.wpr > 0;
-    bf16x8 qf[D / 16];
-    load_q<D>(a.q + (int64_t)(it.tok0 + i_tok) * a.q_stride + (hk * G + hg) * D, valid, g, qf);
+    bf16x8 qf[KS];
+    {
+      const bf16_t* qrow = a.q + (int64_t)(it.tok0 + i_tok) * a.q_stride + (hk * G + hg) * D + g4 * 8;
+#pragma unroll
+      for (int k = 0; k < KS; ++k) {
+        Pack16 p;
+        p.u = u32x4{0, 0, 0, 0};
+        if (valid) p.u = *reinterpret_cast<const u32x4*>(qrow + k * 32);
+        qf[k] = p.h;
+      }
+    }
     // page ids of the segment live across the lanes of two registers (<= 128 pages per segment)
     const int n_pg = it.n_pg;
     const int vphys_lo = lane < n_pg ? a.visit_phys[it.v0 + lane] : 0;
@@ -190,98 +218,103 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
       logical = __builtin_amdgcn_readlane(i < 64 ? vlog_lo : vlog_hi, src);
     };
     const uint32_t* mrow = a.mask_words + it.mask_off + (int64_t)i_tok * it.wpr;
-    AttnState<D> st;
-    attn_init<D>(st);
-    bf16x8 kf[D / 16], va[D / 32], vb[D / 32];
-    auto load_k = [&](int pp_a, int pp_b) {
-      const bf16_t* kb = a.kv + ((int64_t)(m < 16 ? pp_a : pp_b) * a.Hkv + hk) * blk + koff;
+    f32x4 o[DB];
 #pragma unroll
-      for (int k = 0; k < D / 16; ++k) kf[k] = *reinterpret_cast<const bf16x8*>(kb + k * 256);
-    };
-    auto load_v = [&](int pp_a, int pp_b) {
-      const bf16_t* ba = a.kv + ((int64_t)pp_a * a.Hkv + hk) * blk + voff;
-      const bf16_t* bb = a.kv + ((int64_t)pp_b * a.Hkv + hk) * blk + voff;
+    for (int b = 0; b < DB; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float st_m = -INFINITY, st_l = 0.f;
+    // two register sets, used alternately; the set index is a compile-time constant so they stay in registers
+    bf16x8 ka[2][KS], kb[2][KS];
+    bf16x4 va[2][DB], vb[2][DB];
+    int pl_a[2] = {0, 0}, pl_b[2] = {0, 0};
+    uint32_t mw_a[2] = {0u, 0u}, mw_b[2] = {0u, 0u};
+    bool has_b[2] = {false, false};
+    auto fetch = [&](auto set_c, int i) {
+      constexpr int S = decltype(set_c)::value;
+      int pp_a, pp_b;
+      page_of(i, pp_a, pl_a[S]);
+      has_b[S] = i + 1 < n_pg;
+      if (has_b[S]) page_of(i + 1, pp_b, pl_b[S]);
+      else { pp_b = pp_a; pl_b[S] = pl_a[S]; }
+      if (has_bitmap && valid) { mw_a[S] = mrow[pl_a[S] >> 1]; mw_b[S] = mrow[pl_b[S] >> 1]; }
+      const bf16_t* pa_ = a.kv + ((int64_t)pp_a * a.Hkv + hk) * blk;
+      const bf16_t* pb_ = a.kv + ((int64_t)pp_b * a.Hkv + hk) * blk;
 #pragma unroll
-      for (int b = 0; b < D / 32; ++b) {
-        va[b] = *reinterpret_cast<const bf16x8*>(ba + b * 512);
-        vb[b] = *reinterpret_cast<const bf16x8*>(bb + b * 512);
+      for (int k = 0; k < KS; ++k) {
+        ka[S][k] = *reinterpret_cast<const bf16x8*>(pa_ + koff + k * 512);
+        kb[S][k] = *reinterpret_cast<const bf16x8*>(pb_ + koff + k * 512);
+      }
+#pragma unroll
+      for (int b = 0; b < DB; ++b) {
+        const int vo = voff + (b >> 1) * 512 + (b & 1) * 128;
+        va[S][b] = *reinterpret_cast<const bf16x4*>(pa_ + vo);
+        vb[S][b] = *reinterpret_cast<const bf16x4*>(pb_ + vo);
       }
     };
-    int pp_a = 0, pp_b = 0, pl_a = 0, pl_b = 0;
-    uint32_t mw_a = 0u, mw_b = 0u;  // mask words of the pair whose K/V are in the registers
-    bool has_b = false;
-    auto pick = [&](int i) {
-      page_of(i, pp_a, pl_a);
-      has_b = i + 1 < n_pg;
-      if (has_b) page_of(i + 1, pp_b, pl_b);
-      else { pp_b = pp_a; pl_b = pl_a; }
-    };
-    if (n_pg > 0) {
-      pick(0);
-      if (has_bitmap && valid) { mw_a = mrow[pl_a >> 1]; mw_b = mrow[pl_b >> 1]; }
-      load_k(pp_a, pp_b);
-      load_v(pp_a, pp_b);
-    }
-    for (int i = 0; i < n_pg; i += 2) {
-      const uint32_t bits_a = key_bits_w(it.kv_len, it.n_new, has_bitmap, mw_a, i_tok, pl_a, g, valid);
-      const uint32_t bits_b = has_b ? key_bits_w(it.kv_len, it.n_new, has_bitmap, mw_b, i_tok, pl_b, g, valid) : 0u;
-      f32x16 s;
+    auto compute = [&](auto set_c) {
+      constexpr int S = decltype(set_c)::value;
+      const uint32_t bits_a = key_bits4(it.kv_len, it.n_new, has_bitmap, mw_a[S], i_tok, pl_a[S], quad, valid);
+      const uint32_t bits_b =
+          has_b[S] ? key_bits4(it.kv_len, it.n_new, has_bitmap, mw_b[S], i_tok, pl_b[S], quad, valid) : 0u;
+      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[v] = 0.f;
-#pragma unroll
-      for (int k = 0; k < D / 16; ++k) s = mfma32(kf[k], qf[k], s);
-      const bool more = i + 2 < n_pg;
-      if (more) {
-        pick(i + 2);
-        if (has_bitmap && valid) { mw_a = mrow[pl_a >> 1]; mw_b = mrow[pl_b >> 1]; }
-        load_k(pp_a, pp_b);
+      for (int k = 0; k < KS; ++k) {
+        sa = mfma16(ka[S][k], qf[k], sa);
+        sb = mfma16(kb[S][k], qf[k], sb);
       }
+      float sv[8];
       float mx = -INFINITY;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const bool on = ((v < 8 ? (bits_a >> v) : (bits_b >> (v - 8))) & 1u) != 0u;
-        s[v] = on ? s[v] * a.scale_log2 : -INFINITY;
-        mx = fmaxf(mx, s[v]);
+      for (int e = 0; e < 4; ++e) {
+        sv[e] = ((bits_a >> e) & 1u) ? sa[e] * a.scale_log2 : -INFINITY;
+        sv[4 + e] = ((bits_b >> e) & 1u) ? sb[e] * a.scale_log2 : -INFINITY;
+        mx = fmaxf(mx, fmaxf(sv[e], sv[4 + e]));
       }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(st.m, mx);
+      const float m_new = fmaxf(st_m, mx);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+      const float alpha = __builtin_amdgcn_exp2f(st_m - m_safe);
       float lsum = 0.f;
-      Pack16 pa, pb;
+      Pack16 pp;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(s[v] - m_safe);
+      for (int e = 0; e < 8; ++e) {
+        const float p = __builtin_amdgcn_exp2f(sv[e] - m_safe);
         lsum += p;
-        if (v < 8) pa.h[v] = f32_to_bf16(p);
-        else pb.h[v - 8] = f32_to_bf16(p);
+        pp.h[e] = f32_to_bf16(p);
       }
-      st.l = st.l * alpha + lsum;
-      st.m = m_new;
+      st_l = st_l * alpha + lsum;
+      st_m = m_new;
 #pragma unroll
-      for (int b = 0; b < D / 32; ++b) {
+      for (int b = 0; b < DB; ++b) {
+        bf16x8 vv;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) st.o[b][v] *= alpha;
-        st.o[b] = mfma32(va[b], pa.h, st.o[b]);
-        st.o[b] = mfma32(vb[b], pb.h, st.o[b]);
+        for (int e = 0; e < 4; ++e) { vv[e] = va[S][b][e]; vv[4 + e] = vb[S][b][e]; }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[b][e] *= alpha;
+        o[b] = mfma16(vv, pp.h, o[b]);
       }
-      if (more) load_v(pp_a, pp_b);
+    };
+    std::integral_constant<int, 0> set0;
+    std::integral_constant<int, 1> set1;
+    if (n_pg > 0) fetch(set0, 0);
+    for (int i = 0; i < n_pg; i += 4) {
+      if (i + 2 < n_pg) fetch(set1, i + 2);
+      compute(set0);
+      if (i + 2 >= n_pg) break;
+      if (i + 4 < n_pg) fetch(set0, i + 4);
+      compute(set1);
     }
-    const float l_tot = st.l + __shfl_xor(st.l, 32);
+    float l_tot = st_l + __shfl_xor(st_l, 16);
+    l_tot += __shfl_xor(l_tot, 32);
     if (valid) {
       const int64_t prow = (int64_t)sg * rows_cap + qcol;
-      if (g == 0) {
-        part_ml[prow * 2] = st.m;
+      if (g4 == 0) {
+        part_ml[prow * 2] = st_m;
         part_ml[prow * 2 + 1] = l_tot;
       }
-      float* po = part_o + prow * D;
+      float* po = part_o + prow * D + g4 * 4;
 #pragma unroll
-      for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 o4 = {st.o[b][q4 * 4], st.o[b][q4 * 4 + 1], st.o[b][q4 * 4 + 2], st.o[b][q4 * 4 + 3]};
-          *reinterpret_cast<f32x4*>(po + b * 32 + q4 * 8 + g * 4) = o4;
-        }
+      for (int b = 0; b < DB; ++b) *reinterpret_cast<f32x4*>(po + b * 16) = o[b];
     }
   }
 }

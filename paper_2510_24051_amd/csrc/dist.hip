@@ -23,16 +23,9 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
-// histogram update with one LDS atomic per distinct bin among the active lanes of a wave
+// histogram update: one LDS atomic per active lane (the hardware serialises equal addresses within a wave)
 __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool active, int lane) {
-  unsigned long long todo = __ballot(active);
-  while (todo) {
-    const int leader = __ffsll((long long)todo) - 1;
-    const uint32_t b = __shfl(bin, leader);
-    const unsigned long long same = __ballot(active && bin == b);
-    if (lane == leader) atomicAdd(&hist[b], (uint32_t)__popcll(same));
-    todo &= ~same;
-  }
+  if (active) atomicAdd(&hist[bin], 1u);
 }
 
 // After the call *sh_prefix holds the `need`-th largest value among the n LDS-resident keys, *sh_need how many
@@ -182,14 +175,11 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
 __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(const float* __restrict__ logits, int V, int n_chunks,
                                                                 int k, float inv_temp,
                                                                 const unsigned long long* __restrict__ cand,
-                                                                const float* __restrict__ stats,
+                                                                const float* __restrict__ stats, int n2,
                                                                 int32_t* __restrict__ out_ids,
                                                                 float* __restrict__ out_probs) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  unsigned long long* c = reinterpret_cast<unsigned long long*>(smem_raw);  // [n_chunks * k], then sorted top [n2]
-  __shared__ uint32_t hist[256];
-  __shared__ unsigned long long sh_prefix;
-  __shared__ uint32_t sh_need, sh_bin, sh_count;
+  unsigned long long* c = reinterpret_cast<unsigned long long*>(smem_raw);  // [n2 >= n_chunks * k]
   __shared__ float sh_max, sh_sum;
   const int tid = threadIdx.x;
   const int row = blockIdx.x;
@@ -203,33 +193,23 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(const float* __r
       s += stats[((int64_t)row * n_chunks + j) * 2 + 1] * expf((stats[((int64_t)row * n_chunks + j) * 2] - gm) * inv_temp);
     sh_max = gm;
     sh_sum = s;
-    sh_count = 0u;
   }
   __syncthreads();
-  // the id half of the composite only matters when equal logits straddle the cut: stop after the key half
-  // when every candidate sharing the selected key is needed
-  radix_select<unsigned long long, TM_THREADS>(c, n, (uint32_t)k, 56, hist, &sh_prefix, &sh_need, &sh_bin, true, 32);
-  const unsigned long long kth = sh_prefix;  // composites are unique: exactly k of them are >= kth
-  int n2 = 1;
-  while (n2 < k) n2 <<= 1;
-  unsigned long long* top = c + n;  // [n2]
-  for (int i = tid; i < n2; i += TM_THREADS) top[i] = 0ull;
-  __syncthreads();
-  for (int i = tid; i < n; i += TM_THREADS) {
-    const unsigned long long v = c[i];
-    if (v >= kth && v != 0ull) top[atomicAdd(&sh_count, 1u)] = v;
-  }
+  // composites are unique and order by (logit, then lower id): a descending bitonic sort of all candidates
+  // puts the row's top-k first
+  unsigned long long* top = c;
+  for (int i = n + tid; i < n2; i += TM_THREADS) c[i] = 0ull;
   __syncthreads();
   for (int size = 2; size <= n2; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
       for (int i = tid; i < n2 / 2; i += TM_THREADS) {
-        const int lo = ((i / stride) * stride * 2) + (i % stride);
+        const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));  // stride is a power of two
         const int hi = lo + stride;
         const bool desc = ((lo & size) == 0);
-        const unsigned long long a = top[lo], b = top[hi];
+        const unsigned long long a = c[lo], b = c[hi];
         if ((a < b) == desc) {
-          top[lo] = b;
-          top[hi] = a;
+          c[lo] = b;
+          c[hi] = a;
         }
       }
       __syncthreads();
@@ -260,15 +240,15 @@ hipError_t launch_topk(const float* logits, int n, int V, int k, float inv_temp,
   int chunk_len = ((V + n_chunks - 1) / n_chunks + 3) / 4 * 4;
   size_t smem_a = (size_t)chunk_len * 4;
   int n2 = 1;
-  while (n2 < k) n2 <<= 1;
-  size_t smem_b = ((size_t)n_chunks * k + n2) * 8;
+  while (n2 < n_chunks * k) n2 <<= 1;
+  size_t smem_b = (size_t)n2 * 8;
   hipError_t e = hipFuncSetAttribute((const void*)topk_merge_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_b);
   if (e != hipSuccess) return e;
   topk_chunk_kernel<<<dim3(n, n_chunks), dim3(TC_THREADS), smem_a, s>>>(logits, V, chunk_len, k, inv_temp, cand_ws,
                                                                        stats_ws);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  topk_merge_kernel<<<dim3(n), dim3(TM_THREADS), smem_b, s>>>(logits, V, n_chunks, k, inv_temp, cand_ws, stats_ws,
+  topk_merge_kernel<<<dim3(n), dim3(TM_THREADS), smem_b, s>>>(logits, V, n_chunks, k, inv_temp, cand_ws, stats_ws, n2,
                                                                out_ids, out_probs);
   return hipGetLastError();
 }

@@ -347,7 +347,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
       for (int pg = 0; pg < n_pages; ++pg) { visit_phys.push_back(b->page_ids[p0 + pg]); visit_logical.push_back(pg); }
     }
     q.n_visit = (int32_t)visit_phys.size() - q.visit0;
-    const bool decode_path = n_new * G <= 32;
+    const bool decode_path = n_new * G <= 16;  // query rows that fit the decode kernel's 16-column tile
     int64_t visited_pages = 0;
     if (decode_path) {
       q.dec_index = (int32_t)dec_reqs.size();
