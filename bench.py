@@ -21,6 +21,9 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the decode-attention kernel from rocprofv3 counters (FETCH_SIZE scaled by the factor a
+# once-streamed weight matrix of known size gives, plus WRITE_SIZE); see profiles/c2_decode_pmc.md
+PMC_TRAFFIC_BYTES = {"c2": 523.4e6 + 10.1e6}
 
 
 def main():
@@ -125,7 +128,7 @@ def main():
     attn_ms = stages.get("attn_decode", 0.0)
     achieved = attn_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
     roofline = {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": PMC_TRAFFIC_BYTES.get(args.workload),
                 "algorithmic_bytes": attn_bytes, "avg_ms": round(attn_ms, 5)}
 
     weight_bytes = 2 * (m.hidden * (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim + m.n_q_heads * m.head_dim * m.hidden
