@@ -12,7 +12,8 @@
 //                  is cut into chunks (split-K); one wave per (chunk, kv head) streams its pages and writes an
 //                  unnormalised partial (running max, sum, O) that attn_merge combines.
 //   attn_prefill : one workgroup per (request, 32-token query block, kv head), one wave per query head of
-//                  the group; causal requests stop at the block's last visible page.
+//                  the group; K/V page blocks shared through a four-stage LDS ring filled by direct-to-LDS
+//                  loads; causal requests stop at the block's last visible page.
 #include <type_traits>
 
 #include "internal.h"
@@ -61,6 +62,9 @@ __device__ __forceinline__ uint32_t key_bits(const ReqInfo& rq, const uint32_t* 
 }
 
 // One page pair.  kf: K operands (rows 0-15 page a, 16-31 page b); va/vb: V^T operands of each page.
+// The softmax is kept lean: masking is skipped when the whole wave sees every key of the pair, the score
+// scale is folded into the exponent's fused multiply-add, and the accumulators are rescaled only when some
+// lane's running maximum actually moved.
 template <int D>
 __device__ __forceinline__ void attn_step(AttnState<D>& st, const bf16x8 (&kf)[D / 16], const bf16x8 (&qf)[D / 16],
                                           const bf16x8 (&va)[D / 32], const bf16x8 (&vb)[D / 32], uint32_t bits_a,
@@ -71,34 +75,97 @@ __device__ __forceinline__ void attn_step(AttnState<D>& st, const bf16x8 (&kf)[D
 #pragma unroll
   for (int k = 0; k < D / 16; ++k) s = mfma32(kf[k], qf[k], s);
   // register v < 8: key g*8 + v of page a; v >= 8: key g*8 + v - 8 of page b
-  float mx = -INFINITY;
+  const uint32_t bits = bits_a | (bits_b << 8);
+  if (__builtin_amdgcn_ballot_w64(bits != 0xFFFFu) != 0ull) {
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const bool on = ((v < 8 ? (bits_a >> v) : (bits_b >> (v - 8))) & 1u) != 0u;
-    s[v] = on ? s[v] * scale_log2 : -INFINITY;
-    mx = fmaxf(mx, s[v]);
+    for (int v = 0; v < 16; ++v) s[v] = ((bits >> v) & 1u) ? s[v] : -INFINITY;
   }
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
+  mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;  // scale > 0; -inf stays -inf
   const float m_new = fmaxf(st.m, mx);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);  // 0 while nothing was visible before
+  if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0ull) {
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);  // 0 while nothing was visible before
+    st.l *= alpha;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) st.o[b][v] *= alpha;
+    st.m = m_new;
+  }
   float lsum = 0.f;
   Pack16 pa, pb;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const float p = __builtin_amdgcn_exp2f(s[v] - m_safe);  // masked keys: exp2(-inf) = 0
+    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], scale_log2, -m_safe));  // masked keys: exp2(-inf) = 0
     lsum += p;
     if (v < 8) pa.h[v] = f32_to_bf16(p);
     else pb.h[v - 8] = f32_to_bf16(p);
   }
-  st.l = st.l * alpha + lsum;
-  st.m = m_new;
+  st.l += lsum;
 #pragma unroll
   for (int b = 0; b < D / 32; ++b) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) st.o[b][v] *= alpha;
     st.o[b] = mfma32(va[b], pa.h, st.o[b]);
     st.o[b] = mfma32(vb[b], pb.h, st.o[b]);
+  }
+}
+
+// The three phases of attn_step as separate functions, for kernels that overlap the QK^T MFMAs of the next
+// pair with the softmax arithmetic of the current one.
+template <int D>
+__device__ __forceinline__ f32x16 attn_qk(const bf16x8 (&kf)[D / 16], const bf16x8 (&qf)[D / 16]) {
+  f32x16 s;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+  for (int k = 0; k < D / 16; ++k) s = mfma32(kf[k], qf[k], s);
+  return s;
+}
+
+template <int D>
+__device__ __forceinline__ void attn_softmax(AttnState<D>& st, f32x16 s, uint32_t bits_a, uint32_t bits_b,
+                                             float scale_log2, bf16x8& pa_out, bf16x8& pb_out) {
+  const uint32_t bits = bits_a | (bits_b << 8);
+  if (__builtin_amdgcn_ballot_w64(bits != 0xFFFFu) != 0ull) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = ((bits >> v) & 1u) ? s[v] : -INFINITY;
+  }
+  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
+  mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+  const float m_new = fmaxf(st.m, mx);
+  const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+  if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0ull) {
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+    st.l *= alpha;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) st.o[b][v] *= alpha;
+    st.m = m_new;
+  }
+  float lsum = 0.f;
+  Pack16 pa, pb;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], scale_log2, -m_safe));
+    lsum += p;
+    if (v < 8) pa.h[v] = f32_to_bf16(p);
+    else pb.h[v - 8] = f32_to_bf16(p);
+  }
+  st.l += lsum;
+  pa_out = pa.h;
+  pb_out = pb.h;
+}
+
+template <int D>
+__device__ __forceinline__ void attn_pv(AttnState<D>& st, const bf16x8 (&va)[D / 32], const bf16x8 (&vb)[D / 32],
+                                        bf16x8 pa, bf16x8 pb) {
+#pragma unroll
+  for (int b = 0; b < D / 32; ++b) {
+    st.o[b] = mfma32(va[b], pa, st.o[b]);
+    st.o[b] = mfma32(vb[b], pb, st.o[b]);
   }
 }
 
@@ -368,8 +435,176 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, const int32_
 // ------------------------------------------------------------------------------------------------
 // prefill
 // ------------------------------------------------------------------------------------------------
+// Prefill attention: one workgroup per (request, 32-token query block, kv head), one wave per query head of
+// the group (G waves).  The K/V blocks of a page pair (16 KiB at D = 128) are shared by the group's waves through
+// LDS: they are copied global -> LDS with direct-to-LDS loads (each wave issues its share, 1 KiB per
+// instruction; the page block is already in operand order) into a ring of four stages, so the copies of the
+// next three pairs are in flight while a pair is computed.  Every step issues exactly one copy batch (past the
+// end it re-reads the last pair into a stage nobody consumes), which keeps the wait-counter arithmetic
+// uniform: a pair has landed when at most two younger batches are outstanding.  Page ids sit across the lanes
+// of two registers (refilled every 64 pairs); mask words are fetched with the copy, a stage ahead of their use.
+template <int D, int G>
+__global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
+  constexpr int BLK = 2 * PAGE * D;            // elements of one (page, head) block: K part then V part
+  constexpr int PIECES = BLK * 2 / 1024;       // 1 KiB copy instructions per page block
+  constexpr int IPW = 2 * PIECES / G;          // copy instructions per wave per pair
+  static_assert(IPW * G == 2 * PIECES && 2 * IPW <= 63, "group size must divide the copy instructions");
+  __shared__ __align__(16) bf16_t st0[2 * BLK], st1[2 * BLK], st2[2 * BLK], st3[2 * BLK];
+  const int lane = threadIdx.x & 63, hg = threadIdx.x >> 6;
+  const PrefillItem it = items[blockIdx.x];
+  const int hk = blockIdx.y;
+  const ReqInfo rq = a.reqs[it.r];
+  const int qcol = lane & 31, g = lane >> 5, m = lane & 31;
+  const int i_tok = it.qb * 32 + qcol;
+  const bool valid = i_tok < rq.n_new;
+  const int i_ld = valid ? i_tok : rq.n_new - 1;
+  const bool has_bitmap = rq.wpr > 0;
+  bf16x8 qf[D / 16];
+  load_q<D>(a.q + (int64_t)(rq.tok0 + i_ld) * a.q_stride + (hk * G + hg) * D, valid, g, qf);
+  AttnState<D> st;
+  attn_init<D>(st);
+  int v_end = rq.n_visit;
+  if (!has_bitmap) {  // inferred causal: the visit list is pages 0.. in order; stop at the block's last visible key
+    int i_last = it.qb * 32 + 31;
+    i_last = i_last < rq.n_new ? i_last : rq.n_new - 1;
+    const int pages = (rq.kv_len - rq.n_new + i_last) / PAGE + 1;
+    v_end = pages < v_end ? pages : v_end;
+  }
+  const int n_pairs = (v_end + 1) / 2;
+  if (n_pairs > 0) {
+    int win0 = 0, vphys_lo = 0, vphys_hi = 0, vlog_lo = 0, vlog_hi = 0;
+    auto load_window = [&](int w0) {
+      win0 = w0;
+      const int base = rq.visit0 + w0;
+      vphys_lo = w0 + lane < v_end ? a.visit_phys[base + lane] : 0;
+      vphys_hi = w0 + lane + 64 < v_end ? a.visit_phys[base + lane + 64] : 0;
+      vlog_lo = w0 + lane < v_end ? a.visit_logical[base + lane] : 0;
+      vlog_hi = w0 + lane + 64 < v_end ? a.visit_logical[base + lane + 64] : 0;
+    };
+    auto page_of = [&](int v, int& phys, int& logical) {  // v is workgroup-uniform, inside the window
+      const int i = v - win0, src = i & 63;
+      phys = __builtin_amdgcn_readlane(i < 64 ? vphys_lo : vphys_hi, src);
+      logical = __builtin_amdgcn_readlane(i < 64 ? vlog_lo : vlog_hi, src);
+    };
+    const bf16_t* kvh = a.kv + (int64_t)hk * BLK + lane * 8;
+    const int64_t page_stride = (int64_t)a.Hkv * BLK;
+    const uint32_t* mrow = a.mask_words + rq.mask_off + (int64_t)i_ld * rq.wpr;
+    struct Meta { int pl_a, pl_b; bool has_b; uint32_t mw_a, mw_b; };
+    Meta m0{}, m1{}, m2{}, m3{};
+    auto start_pair = [&](bf16_t* stage, int pair, Meta& md) {
+      const int pc = pair < n_pairs ? pair : n_pairs - 1;
+      const int v = pc * 2;
+      if (v - win0 >= 128) load_window(v);
+      int pp_a, pp_b;
+      page_of(v, pp_a, md.pl_a);
+      md.has_b = v + 1 < v_end;
+      if (md.has_b) page_of(v + 1, pp_b, md.pl_b);
+      else { pp_b = pp_a; md.pl_b = md.pl_a; }
+      if (has_bitmap && valid) { md.mw_a = mrow[md.pl_a >> 1]; md.mw_b = mrow[md.pl_b >> 1]; }
+      const bf16_t* sa = kvh + (int64_t)pp_a * page_stride;
+      const bf16_t* sb = kvh + (int64_t)pp_b * page_stride;
+#pragma unroll
+      for (int q = 0; q < IPW; ++q) {
+        const int j = hg * IPW + q;  // workgroup-wide copy index: page j / PIECES, piece j % PIECES
+        const bf16_t* src = (j >= PIECES ? sb : sa) + (j % PIECES) * 512;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(stage + j * 512), 16, 0, 0);
+      }
+    };
+    const int koff = (m < 16 ? 0 : BLK) + g * 128 + (m & 15) * 8;
+    const int voff = PAGE * D + g * 256 + m * 8;
+    auto bits_of = [&](uint32_t word, int pl) -> uint32_t {
+      if (!valid) return 0u;
+      const int j0 = pl * PAGE + g * 8;
+      int cnt = rq.kv_len - j0;
+      cnt = cnt < 0 ? 0 : (cnt > 8 ? 8 : cnt);
+      uint32_t bits = (1u << cnt) - 1u;
+      if (has_bitmap) {
+        bits &= (word >> ((pl & 1) * 16 + g * 8)) & 0xFFu;
+      } else {
+        int lim = rq.kv_len - rq.n_new + i_ld - j0 + 1;
+        lim = lim < 0 ? 0 : (lim > 8 ? 8 : lim);
+        bits &= (1u << lim) - 1u;
+      }
+      return bits;
+    };
+    // QK^T of a pair (K part of its stage) and the rest of the step (softmax, then PV with the V part)
+    auto scores = [&](const bf16_t* stage) {
+      bf16x8 kf[D / 16];
+#pragma unroll
+      for (int k = 0; k < D / 16; ++k) kf[k] = *reinterpret_cast<const bf16x8*>(stage + koff + k * 256);
+      return attn_qk<D>(kf, qf);
+    };
+    auto finish = [&](const bf16_t* stage, const Meta& md, const f32x16& sc) {
+      const uint32_t bits_a = bits_of(md.mw_a, md.pl_a);
+      const uint32_t bits_b = md.has_b ? bits_of(md.mw_b, md.pl_b) : 0u;
+      bf16x8 pa, pb;
+      attn_softmax<D>(st, sc, bits_a, bits_b, a.scale_log2, pa, pb);
+      bf16x8 va[D / 32], vb[D / 32];
+#pragma unroll
+      for (int bb = 0; bb < D / 32; ++bb) {
+        va[bb] = *reinterpret_cast<const bf16x8*>(stage + voff + bb * 512);
+        vb[bb] = *reinterpret_cast<const bf16x8*>(stage + BLK + voff + bb * 512);
+      }
+      attn_pv<D>(st, va, vb, pa, pb);
+    };
+#define PIE_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+    // Step i: the scores of pair i+1 are issued to the matrix cores first, so they run under the softmax
+    // arithmetic of pair i.  A stage is read in two consecutive steps (K, then V), the ring has four stages,
+    // two pairs are in flight.
+    load_window(0);
+    start_pair(st0, 0, m0);
+    start_pair(st1, 1, m1);
+    start_pair(st2, 2, m2);
+    PIE_WAIT_VM(2 * IPW);
+    __syncthreads();
+    f32x16 s_cur = scores(st0), s_next = s_cur;
+    for (int p = 0; p < n_pairs; p += 4) {
+      PIE_WAIT_VM(IPW);
+      __syncthreads();
+      start_pair(st3, p + 3, m3);
+      s_next = scores(st1);
+      finish(st0, m0, s_cur);
+      if (p + 1 >= n_pairs) break;
+      PIE_WAIT_VM(IPW);
+      __syncthreads();
+      start_pair(st0, p + 4, m0);
+      s_cur = scores(st2);
+      finish(st1, m1, s_next);
+      if (p + 2 >= n_pairs) break;
+      PIE_WAIT_VM(IPW);
+      __syncthreads();
+      start_pair(st1, p + 5, m1);
+      s_next = scores(st3);
+      finish(st2, m2, s_cur);
+      if (p + 3 >= n_pairs) break;
+      PIE_WAIT_VM(IPW);
+      __syncthreads();
+      start_pair(st2, p + 6, m2);
+      s_cur = scores(st0);
+      finish(st3, m3, s_next);
+    }
+    PIE_WAIT_VM(0);
+#undef PIE_WAIT_VM
+  }
+  const float l_tot = st.l + __shfl_xor(st.l, 32);
+  if (!valid) return;
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  bf16_t* orow = a.out + (int64_t)(rq.tok0 + i_tok) * a.Hq * D + (hk * G + hg) * D;
+#pragma unroll
+  for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      bf16x4 o4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o4[e] = f32_to_bf16(st.o[b][q4 * 4 + e] * inv);
+      *reinterpret_cast<bf16x4*>(orow + b * 32 + q4 * 8 + g * 4) = o4;
+    }
+}
+
+// Variant without LDS: every wave loads its own K/V operands from global memory (the group's waves meet in L1).
 template <int D>
-__global__ __launch_bounds__(512) void attn_prefill_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
+__global__ __launch_bounds__(512) void attn_prefill_direct_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
   const int lane = threadIdx.x & 63, hg = threadIdx.x >> 6;  // one wave per query head of the group
   const PrefillItem it = items[blockIdx.x];
   const int hk = blockIdx.y;
@@ -440,12 +675,21 @@ hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_d
   return hipGetLastError();
 }
 
-hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s) {
-  if (n_items <= 0) return hipSuccess;
+template <int D>
+static hipError_t launch_prefill_d(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   dim3 grid(n_items, a.Hkv), block(64 * G);
-  if (a.D == 128) attn_prefill_kernel<128><<<grid, block, 0, s>>>(a, items);
-  else if (a.D == 64) attn_prefill_kernel<64><<<grid, block, 0, s>>>(a, items);
-  else return hipErrorInvalidValue;
+  if (G == 1) attn_prefill_kernel<D, 1><<<grid, block, 0, s>>>(a, items);
+  else if (G == 2) attn_prefill_kernel<D, 2><<<grid, block, 0, s>>>(a, items);
+  else if (G == 4) attn_prefill_kernel<D, 4><<<grid, block, 0, s>>>(a, items);
+  else if (G == 8) attn_prefill_kernel<D, 8><<<grid, block, 0, s>>>(a, items);
+  else attn_prefill_direct_kernel<D><<<grid, block, 0, s>>>(a, items);  // other group sizes: no LDS sharing
   return hipGetLastError();
+}
+
+hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s) {
+  if (n_items <= 0) return hipSuccess;
+  if (a.D == 128) return launch_prefill_d<128>(a, items, n_items, s);
+  if (a.D == 64) return launch_prefill_d<64>(a, items, n_items, s);
+  return hipErrorInvalidValue;
 }

@@ -16,31 +16,54 @@
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
+// Loads are batched ahead of the stores (ids, then residual values, then all stores) so that a tile costs
+// three dependent memory round trips instead of one per element.
 template <int MODE>
 __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, const f32x16& acc2, int m0, int n0,
                                          int M, int N, int lane) {
   const int n = n0 + (lane & 31);
   const int g = lane >> 5;
   if (n >= N) return;
+  int rows[16];
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int m = m0 + (v >> 2) * 8 + g * 4 + (v & 3);
-    if (m >= M) continue;
-    const float x = acc[v];
-    if (MODE == EPI_STORE_BF16) {
-      reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + n] = f32_to_bf16(x);
-    } else if (MODE == EPI_STORE_F32) {
-      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + n] = x;
-    } else if (MODE == EPI_RESID_EMBED) {
-      float r = bf16_to_f32(e.embeds[(int64_t)e.ids[m] * e.H + n]);
-      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + n] = r + x;
-    } else if (MODE == EPI_RESID_OUT) {
-      int id = e.ids[m];
-      if (id >= 0) e.embeds[(int64_t)id * e.H + n] = f32_to_bf16(e.resid[(int64_t)m * e.H + n] + x);
-    } else if (MODE == EPI_SWIGLU) {  // acc = gate block, acc2 = up block; n0 is the gate block's packed column
-      const int nc = (n0 >> 1) + (lane & 31);
-      reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + nc] = f32_to_bf16(silu_f(x) * acc2[v]);
-    }
+  for (int v = 0; v < 16; ++v) rows[v] = m0 + (v >> 2) * 8 + g * 4 + (v & 3);
+  if (MODE == EPI_STORE_BF16) {
+    bf16_t* out = reinterpret_cast<bf16_t*>(e.out);
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = f32_to_bf16(acc[v]);
+  } else if (MODE == EPI_STORE_F32) {
+    float* out = reinterpret_cast<float*>(e.out);
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = acc[v];
+  } else if (MODE == EPI_SWIGLU) {  // acc = gate block, acc2 = up block; n0 is the gate block's packed column
+    bf16_t* out = reinterpret_cast<bf16_t*>(e.out);
+    const int nc = (n0 >> 1) + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + nc] = f32_to_bf16(silu_f(acc[v]) * acc2[v]);
+  } else if (MODE == EPI_RESID_EMBED) {
+    int id[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) id[v] = rows[v] < M ? e.ids[rows[v]] : 0;
+    float r[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) r[v] = bf16_to_f32(e.embeds[(int64_t)id[v] * e.H + n]);
+    float* out = reinterpret_cast<float*>(e.out);
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = r[v] + acc[v];
+  } else if (MODE == EPI_RESID_OUT) {
+    int id[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) id[v] = rows[v] < M ? e.ids[rows[v]] : -1;
+    float r[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) r[v] = id[v] >= 0 ? e.resid[(int64_t)rows[v] * e.H + n] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (id[v] >= 0) e.embeds[(int64_t)id[v] * e.H + n] = f32_to_bf16(r[v] + acc[v]);
   }
 }
 
@@ -304,6 +327,129 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restric
 }
 
 // ------------------------------------------------------------------------------------------------
+// gemm_large, asynchronous-copy version (K a multiple of 128)
+//
+// Same 256x256x64 tile and 8 waves of 128x64 as above, but both operand tiles are copied global -> LDS by
+// direct-to-LDS loads (no VGPR staging, no LDS store instructions): each wave instruction moves 1 KiB, the
+// activation rows land pre-swizzled (16-byte chunk c of row r at position c ^ ((r >> 1) & 7), conflict-free for
+// the 64-bank LDS when 16 consecutive rows read the same chunk), the weight tiles land in operand order.  Two
+// LDS stages as separate arrays so that the compiler's wait counters keep the copy of tile t+1 in flight while
+// tile t is computed; the surplus copy of the last round re-reads the last tile.  Workgroup ids are remapped so
+// that each XCD (id % 8) works on a contiguous range of a grouped tile order (8 row tiles per group) and its L2
+// sees a few activation and weight panels at a time.
+// ------------------------------------------------------------------------------------------------
+#define LDS_DMA16(gptr, lptr)                                                                       \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),           \
+                                   (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
+
+template <int MODE>
+__global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __restrict__ A, int lda, int M,
+                                                               const bf16_t* __restrict__ Wp, int N, int NB, int K,
+                                                               EpiArgs epi, int tiles_m, int tiles_n) {
+  __shared__ __align__(16) bf16_t As0[LG_BM * LG_BK], As1[LG_BM * LG_BK], Bs0[LG_BN * LG_BK], Bs1[LG_BN * LG_BK];
+  constexpr int GROUP_M = 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int KB = K / 16, KT = K / LG_BK;  // KT is even
+  int pid = blockIdx.x;
+  const int ntiles = tiles_m * tiles_n;
+  if (ntiles % 8 == 0) pid = (pid & 7) * (ntiles / 8) + (pid >> 3);
+  int tm, tn;
+  {
+    const int width = GROUP_M * tiles_n;
+    const int first_m = (pid / width) * GROUP_M;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    tm = first_m + (pid % width) % gsz;
+    tn = (pid % width) / gsz;
+  }
+  const int m0 = tm * LG_BM, nb0 = tn * (LG_BN / 32);
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // copy instruction j = wave * 4 + jj of an operand covers LDS bytes [j KiB, (j + 1) KiB)
+  //   A: rows j*8 .. j*8+7, lane -> row j*8 + lane/8, stored chunk lane%8
+  //   W: block j/4, k-step j%4 (1 KiB contiguous in the tiled weight)
+  const bf16_t* ap[4];
+  const bf16_t* bp[4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const int j = wave * 4 + jj;
+    const int r = j * 8 + (lane >> 3);
+    const int kc = (lane & 7) ^ ((r >> 1) & 7);
+    int gr = m0 + r;
+    gr = gr < M ? gr : M - 1;  // rows past M re-read a valid row; their results are never stored
+    ap[jj] = A + (int64_t)gr * lda + kc * 8;
+    int nb = nb0 + (j >> 2);
+    nb = nb < NB ? nb : NB - 1;
+    bp[jj] = Wp + packed_tile_offset(nb, j & 3, KB) + lane * 8;
+  }
+  auto issue = [&](bf16_t* As, bf16_t* Bs, int kt) {
+    const int k = kt < KT ? kt : KT - 1;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) LDS_DMA16(ap[jj] + (int64_t)k * LG_BK, As + (wave * 4 + jj) * 512);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) LDS_DMA16(bp[jj] + (int64_t)k * 2048, Bs + (wave * 4 + jj) * 512);
+  };
+  auto load_frags = [&](const bf16_t* As, const bf16_t* Bs, int s, bf16x8 (&af)[4], bf16x8 (&bfr)[2]) {
+    const int kc = s * 2 + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = wm * 128 + i * 32 + (lane & 31);
+      af[i] = *reinterpret_cast<const bf16x8*>(As + r * LG_BK + ((kc ^ ((r >> 1) & 7)) << 3));
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + ((wn * 2 + j) * 4 + s) * 512 + lane * 8);
+  };
+  auto compute = [&](const bf16_t* As, const bf16_t* Bs) {
+    bf16x8 af[2][4], bfr[2][2];
+    load_frags(As, Bs, 0, af[0], bfr[0]);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (s + 1 < 4) load_frags(As, Bs, s + 1, af[(s + 1) & 1], bfr[(s + 1) & 1]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(af[s & 1][i], bfr[s & 1][j], acc[i][j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  issue(As0, Bs0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  for (int kt = 0; kt < KT; kt += 2) {
+    issue(As1, Bs1, kt + 1);
+    compute(As0, Bs0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    issue(As0, Bs0, kt + 2);
+    compute(As1, Bs1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int mt = m0 + wm * 128 + i * 32;
+    if (MODE == EPI_SWIGLU) {
+      int nb = nb0 + wn * 2;
+      if (nb < NB) epi_tile<MODE>(epi, acc[i][0], acc[i][1], mt, nb * 32, M, NB * 32, lane);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        int nb = nb0 + wn * 2 + j;
+        if (nb < NB) epi_tile<MODE>(epi, acc[i][j], acc[i][j], mt, nb * 32, M, N, lane);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // dispatch
 // ------------------------------------------------------------------------------------------------
 template <int MB, int MODE>
@@ -352,6 +498,12 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   if (M <= 64) return run_skinny<2, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   if (M <= 128) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   if (M <= 256 && MODE != EPI_SWIGLU) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (W.K % 128 == 0) {
+    const int tiles_m = (M + LG_BM - 1) / LG_BM, tiles_n = (W.NB + 7) / 8;
+    gemm_large_async_kernel<MODE><<<dim3(tiles_m * tiles_n), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, epi,
+                                                                                tiles_m, tiles_n);
+    return hipGetLastError();
+  }
   auto kern = gemm_large_kernel<MODE>;
   size_t smem = (size_t)4 * LG_BM * LG_BK * sizeof(bf16_t);
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
