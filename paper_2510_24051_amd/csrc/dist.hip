@@ -1,19 +1,25 @@
 // Next-token distribution: softmax over the whole vocabulary and exact top-k.
 //
 // Two kernels so that a handful of rows still fills the chip:
-//   topk_chunk : grid (rows, chunks).  A workgroup stages one chunk of a row's logits in LDS as
-//                order-preserving 32-bit keys, reduces the chunk max and sum of exponentials with
-//                wavefront reductions, finds the chunk's k-th largest key by radix select (8 bits per
-//                pass, LDS histograms, one atomic per distinct bin per wave) and writes the chunk's
-//                top-k candidates as 64-bit (key, ~id) composites.
-//   topk_merge : grid (rows).  Combines the chunk maxima/sums into the row's softmax normaliser,
-//                radix-selects the k largest composites among chunks*k candidates (composites are
-//                unique, so ties on the logit resolve to the lower id), sorts them with a bitonic network
-//                and writes ids and probabilities of the full distribution.
+//   topk_chunk : grid (rows, chunks).  A workgroup takes one chunk (<= 8192 logits) of a row, keeps its
+//                order-preserving 32-bit keys in registers, reduces the chunk max and sum of exponentials with
+//                wavefront reductions, finds the chunk's k-th largest key by radix select and writes the
+//                chunk's top-k candidates as 64-bit (key, ~id) composites.
+//   topk_merge : grid (rows).  Combines the chunk maxima/sums into the row's softmax normaliser, radix-selects
+//                the k largest composites among chunks*k candidates (composites are unique, so ties on the
+//                logit resolve to the lower id), sorts those k with a bitonic network and writes ids and
+//                probabilities of the full distribution.
+//
+// Radix select, 8 bits per pass.  Logits share a handful of sign/exponent values, so a histogram of the top
+// byte would hammer a few LDS addresses with atomics; instead the top byte is found by walking the byte values
+// downward from the maximum's and counting matches in registers (a few steps for any realistic distribution).
+// The lower bytes only concern the few keys that share the selected top byte: LDS histogram with atomics.
 #include "internal.h"
 
 #define TC_THREADS 512
+#define TC_PER 16  // keys per thread: chunks hold at most TC_THREADS * TC_PER = 8192 logits
 #define TM_THREADS 1024
+#define TM_PER 16  // composites per thread: at most 16384 candidates per row
 
 __device__ __forceinline__ uint32_t order_key(float z) {
   uint32_t u = __float_as_uint(z);
@@ -23,41 +29,58 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
-// histogram update: one LDS atomic per active lane (the hardware serialises equal addresses within a wave)
-__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool active, int lane) {
-  if (active) atomicAdd(&hist[bin], 1u);
+// Sum of one unsigned per thread over the workgroup (all threads get the result).  red: [THREADS / 64] words.
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();  // previous use of red is over
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  uint32_t t = 0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) t += red[w];
+  return t;
 }
 
-// After the call *sh_prefix holds the `need`-th largest value among the n LDS-resident keys, *sh_need how many
-// keys equal to it belong to the top set and *sh_bin_count how many keys equal it in total.  With
-// stop_when_unique the passes below `stop_shift` are skipped once every key sharing the prefix found so far
-// is needed anyway (then *sh_prefix holds only the decided high bits and is a lower bound of the selected set).
-template <typename KeyT, int THREADS>
-__device__ __forceinline__ void radix_select(const KeyT* keys, int n, uint32_t need, int top_shift, uint32_t* hist,
-                                             KeyT* sh_prefix, uint32_t* sh_need, uint32_t* sh_bin_count,
-                                             bool stop_when_unique = false, int stop_shift = 0) {
+// k-th largest of the workgroup's keys (PER per thread in registers, key 0 = padding below every real key).
+// On return: *out_kth the selected value, *out_need how many keys equal to it belong to the top set, *out_eq
+// how many keys equal it in total.  hist: 256 words, red: THREADS / 64 words of LDS.
+// `top_byte_max`: top byte of the largest key.  With stop_at_shift > 0 the search stops before the passes below
+// that shift when every key sharing the bits decided so far is needed anyway (then the low bits of *out_kth
+// are 0 and it is a lower bound of exactly the selected set).
+template <typename KeyT, int PER, int THREADS>
+__device__ __forceinline__ void select_kth(const KeyT (&keys)[PER], uint32_t need, int top_byte_max, int stop_at_shift,
+                                           uint32_t* hist, uint32_t* red, KeyT* sh_prefix, uint32_t* sh_need,
+                                           uint32_t* sh_eq, KeyT* out_kth, uint32_t* out_need, uint32_t* out_eq) {
+  constexpr int TOP = sizeof(KeyT) * 8 - 8;
   const int tid = threadIdx.x, lane = tid & 63;
-  if (tid == 0) {
-    *sh_prefix = 0;
-    *sh_need = need;
+  // top byte: walk downward from the maximum's
+  int b = top_byte_max;
+  uint32_t cnt = 0;
+  for (;; --b) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) c += ((int)(keys[i] >> TOP) == b && keys[i] != 0) ? 1u : 0u;
+    cnt = block_sum<THREADS>(c, red);
+    if (cnt >= need || b == 0) break;
+    need -= cnt;
   }
-  __syncthreads();
-  for (int shift = top_shift; shift >= 0; shift -= 8) {
+  KeyT prefix = (KeyT)b << TOP;
+  uint32_t eq = cnt;  // keys matching the decided bits
+  for (int shift = TOP - 8; shift >= 0; shift -= 8) {
+    if (stop_at_shift > 0 && shift < stop_at_shift && eq == need) break;
+    __syncthreads();
     if (tid < 256) hist[tid] = 0u;
     __syncthreads();
-    const KeyT prefix = *sh_prefix;
-    const KeyT hi_mask = (shift == top_shift) ? (KeyT)0 : (~(KeyT)0 << (shift + 8));
-    for (int i0 = 0; i0 < n; i0 += THREADS) {
-      const int i = i0 + tid;
-      KeyT key = i < n ? keys[i] : (KeyT)0;
-      const bool act = i < n && (key & hi_mask) == prefix;
-      hist_add(hist, (uint32_t)((key >> shift) & 0xFF), act, lane);
-    }
+    const KeyT hi_mask = ~(KeyT)0 << (shift + 8);
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      if ((keys[i] & hi_mask) == prefix && keys[i] != 0) atomicAdd(&hist[(uint32_t)(keys[i] >> shift) & 0xFFu], 1u);
     __syncthreads();
     if (tid < 64) {
-      // first wave: lane L owns bins 255-4L .. 252-4L (descending); a wave scan gives the number of keys in
-      // higher bins, and the one lane whose range crosses `need` picks the bin
-      const uint32_t nd = *sh_need;
+      // lane L owns bins 255-4L .. 252-4L (descending); a wave scan gives the number of keys in higher bins
       const int b0 = 255 - 4 * lane;
       const uint32_t h0 = hist[b0], h1 = hist[b0 - 1], h2 = hist[b0 - 2], h3 = hist[b0 - 3];
       const uint32_t tot = h0 + h1 + h2 + h3;
@@ -68,31 +91,35 @@ __device__ __forceinline__ void radix_select(const KeyT* keys, int n, uint32_t n
         if (lane >= o) incl += t;
       }
       const uint32_t excl = incl - tot;
-      if (excl < nd && nd <= incl) {
-        uint32_t acc = excl;
-        int b = b0;
-        if (acc + h0 < nd) { acc += h0; b = b0 - 1;
-          if (acc + h1 < nd) { acc += h1; b = b0 - 2;
-            if (acc + h2 < nd) { acc += h2; b = b0 - 3; } } }
-        *sh_need = nd - acc;
-        *sh_prefix = prefix | ((KeyT)b << shift);
-        *sh_bin_count = (b == b0) ? h0 : (b == b0 - 1) ? h1 : (b == b0 - 2) ? h2 : h3;
+      if (excl < need && need <= incl) {
+        uint32_t acc = excl, hb = h0;
+        int bb = b0;
+        if (acc + h0 < need) { acc += h0; bb = b0 - 1; hb = h1;
+          if (acc + h1 < need) { acc += h1; bb = b0 - 2; hb = h2;
+            if (acc + h2 < need) { acc += h2; bb = b0 - 3; hb = h3; } } }
+        *sh_need = need - acc;
+        *sh_eq = hb;
+        *sh_prefix = prefix | ((KeyT)bb << shift);
       }
     }
     __syncthreads();
-    if (stop_when_unique && *sh_bin_count == *sh_need && shift <= stop_shift) break;  // uniform: shared values
+    need = *sh_need;
+    eq = *sh_eq;
+    prefix = *sh_prefix;
   }
+  *out_kth = prefix;
+  *out_need = need;
+  *out_eq = eq;
 }
 
 __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __restrict__ logits, int V, int chunk_len,
                                                                 int k, float inv_temp,
                                                                 unsigned long long* __restrict__ cand,
                                                                 float* __restrict__ stats) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint32_t* keys = reinterpret_cast<uint32_t*>(smem_raw);  // [chunk_len]
-  __shared__ float red[TC_THREADS / 64];
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t sh_prefix, sh_need, sh_bin, sh_count, sh_count_eq, sh_wave_off[TC_THREADS / 64 + 1];
+  __shared__ uint32_t red[TC_THREADS / 64];
+  __shared__ float fred[TC_THREADS / 64];
+  __shared__ uint32_t sh_prefix, sh_need, sh_eq, sh_count, sh_count_eq, sh_wave_off[TC_THREADS / 64 + 1];
   __shared__ float sh_max;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = blockIdx.x, chunk = blockIdx.y, n_chunks = gridDim.y;
@@ -100,91 +127,124 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
   const int n = min(chunk_len, V - start);
   const float* z = logits + (int64_t)row * V + start;
 
+  // thread t holds logits t*4 + j*(4*THREADS) + e (e < 4, j < PER/4): 16-byte loads, ids recoverable from (j, e)
+  uint32_t keys[TC_PER];
   float mx = -INFINITY;
-  for (int i = tid * 4; i < n; i += TC_THREADS * 4) {  // start and V are multiples of 4
-    f32x4 v = *reinterpret_cast<const f32x4*>(z + i);
+#pragma unroll
+  for (int j = 0; j < TC_PER / 4; ++j) {
+    const int i = tid * 4 + j * 4 * TC_THREADS;  // start, n and V are multiples of 4
+    f32x4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    const bool in = i < n;
+    if (in) v = *reinterpret_cast<const f32x4*>(z + i);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      keys[i + e] = order_key(v[e]);
+      keys[j * 4 + e] = in ? order_key(v[e]) : 0u;
       mx = fmaxf(mx, v[e]);
     }
   }
   mx = wave_max(mx);
-  if (lane == 0) red[wave] = mx;
+  if (lane == 0) fred[wave] = mx;
   __syncthreads();
   if (tid == 0) {
-    float m = red[0];
-    for (int w = 1; w < TC_THREADS / 64; ++w) m = fmaxf(m, red[w]);
+    float m = fred[0];
+    for (int w = 1; w < TC_THREADS / 64; ++w) m = fmaxf(m, fred[w]);
     sh_max = m;
+    sh_count = 0u;
+    sh_count_eq = 0u;
   }
   __syncthreads();
   const float cmax = sh_max;
   float sum = 0.f;
-  for (int i = tid; i < n; i += TC_THREADS) sum += expf((key_to_float(keys[i]) - cmax) * inv_temp);
+#pragma unroll
+  for (int i = 0; i < TC_PER; ++i)
+    if (keys[i] != 0u) sum += expf((key_to_float(keys[i]) - cmax) * inv_temp);
   sum = wave_sum(sum);
   __syncthreads();
-  if (lane == 0) red[wave] = sum;
+  if (lane == 0) fred[wave] = sum;
   __syncthreads();
   if (tid == 0) {
     float t = 0.f;
-    for (int w = 0; w < TC_THREADS / 64; ++w) t += red[w];
+    for (int w = 0; w < TC_THREADS / 64; ++w) t += fred[w];
     stats[((int64_t)row * n_chunks + chunk) * 2] = cmax;
     stats[((int64_t)row * n_chunks + chunk) * 2 + 1] = t;
-    sh_count = 0u;
-    sh_count_eq = 0u;
   }
   const int kc = min(k, n);  // candidates this chunk contributes
-  radix_select<uint32_t, TC_THREADS>(keys, n, (uint32_t)kc, 24, hist, &sh_prefix, &sh_need, &sh_bin);
-  const uint32_t kth = sh_prefix, need_eq = sh_need;
-  const bool split_tie = sh_bin != need_eq;  // some but not all keys equal to kth are taken: lowest ids win
+  uint32_t kth, need_eq, eq_total;
+  select_kth<uint32_t, TC_PER, TC_THREADS>(keys, (uint32_t)kc, (int)(order_key(cmax) >> 24), 0, hist, red, &sh_prefix,
+                                           &sh_need, &sh_eq, &kth, &need_eq, &eq_total);
   unsigned long long* out = cand + ((int64_t)row * n_chunks + chunk) * k;
-  // keys above kth: any order, slots [need_eq, kc); keys equal to kth: lowest ids first, slots [0, need_eq)
-  uint32_t eq_seen = 0u;
-  for (int base = 0; base < n; base += TC_THREADS) {
-    const int i = base + tid;
-    uint32_t key = 0u;
-    bool gt = false, eq = false;
-    if (i < n) {
-      key = keys[i];
-      gt = key > kth;
-      eq = key == kth;
+  // keys above kth: any order, slots [need_eq, kc); keys equal to kth: slots [0, need_eq), lowest ids first when
+  // only some of them are taken
+  const bool split_tie = eq_total != need_eq;
+  auto comp_of = [&](int i) {
+    const int id = start + tid * 4 + (i >> 2) * 4 * TC_THREADS + (i & 3);
+    return ((unsigned long long)keys[i] << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)id);
+  };
+#pragma unroll
+  for (int i = 0; i < TC_PER; ++i) {
+    if (keys[i] > kth) {
+      const uint32_t pos = need_eq + atomicAdd(&sh_count, 1u);
+      if (pos < (uint32_t)kc) out[pos] = comp_of(i);  // kc - need_eq keys by construction
+    } else if (!split_tie && keys[i] == kth && keys[i] != 0u) {
+      const uint32_t pos = atomicAdd(&sh_count_eq, 1u);
+      if (pos < need_eq) out[pos] = comp_of(i);
     }
-    const unsigned long long comp = ((unsigned long long)key << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)(start + i));
-    if (gt) out[need_eq + atomicAdd(&sh_count, 1u)] = comp;
-    if (!split_tie) {
-      if (eq) out[atomicAdd(&sh_count_eq, 1u)] = comp;
-    } else if (eq_seen < need_eq) {  // uniform across the workgroup
-      const unsigned long long bal = __ballot(eq);
-      const uint32_t before = (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-      if (lane == 0) sh_wave_off[wave + 1] = (uint32_t)__popcll(bal);
+  }
+  if (split_tie) {
+    // ids ascend with (j, thread, e): walk j outermost; within a j the workgroup's ids are tid*4 + e
+    uint32_t eq_seen = 0u;
+    for (int j = 0; j < TC_PER / 4 && eq_seen < need_eq; ++j) {  // eq_seen is uniform across the workgroup
+      uint32_t mine = 0u;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) mine += (keys[j * 4 + e] == kth && keys[j * 4 + e] != 0u) ? 1u : 0u;
+      uint32_t incl = mine;  // inclusive prefix over the wave, then wave offsets through LDS
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+      }
+      __syncthreads();
+      if (lane == 63) sh_wave_off[wave + 1] = incl;
       __syncthreads();
       if (tid == 0) {
         sh_wave_off[0] = 0u;
         for (int w = 0; w < TC_THREADS / 64; ++w) sh_wave_off[w + 1] += sh_wave_off[w];
       }
       __syncthreads();
-      const uint32_t pos = eq_seen + sh_wave_off[wave] + before;
-      if (eq && pos < need_eq) out[pos] = comp;
+      uint32_t pos = eq_seen + sh_wave_off[wave] + incl - mine;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (keys[j * 4 + e] == kth && keys[j * 4 + e] != 0u) {
+          if (pos < need_eq) out[pos] = comp_of(j * 4 + e);
+          ++pos;
+        }
       eq_seen += sh_wave_off[TC_THREADS / 64];
-      __syncthreads();
     }
   }
   for (int i = kc + tid; i < k; i += TC_THREADS) out[i] = 0ull;  // short chunk: pad (a zero never wins)
 }
 
-__global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(const float* __restrict__ logits, int V, int n_chunks,
-                                                                int k, float inv_temp,
+__global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, int k, float inv_temp,
                                                                 const unsigned long long* __restrict__ cand,
                                                                 const float* __restrict__ stats, int n2,
                                                                 int32_t* __restrict__ out_ids,
                                                                 float* __restrict__ out_probs) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  unsigned long long* c = reinterpret_cast<unsigned long long*>(smem_raw);  // [n2 >= n_chunks * k]
+  unsigned long long* top = reinterpret_cast<unsigned long long*>(smem_raw);  // [n2 >= k]
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t red[TM_THREADS / 64];
+  __shared__ unsigned long long sh_prefix;
+  __shared__ uint32_t sh_need, sh_eq, sh_count;
   __shared__ float sh_max, sh_sum;
   const int tid = threadIdx.x;
   const int row = blockIdx.x;
   const int n = n_chunks * k;
-  for (int i = tid; i < n; i += TM_THREADS) c[i] = cand[(int64_t)row * n + i];
+  unsigned long long c[TM_PER];
+#pragma unroll
+  for (int i = 0; i < TM_PER; ++i) {
+    const int idx = tid + i * TM_THREADS;
+    c[i] = idx < n ? cand[(int64_t)row * n + idx] : 0ull;
+  }
   if (tid == 0) {
     float gm = -INFINITY;
     for (int j = 0; j < n_chunks; ++j) gm = fmaxf(gm, stats[((int64_t)row * n_chunks + j) * 2]);
@@ -193,12 +253,24 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(const float* __r
       s += stats[((int64_t)row * n_chunks + j) * 2 + 1] * expf((stats[((int64_t)row * n_chunks + j) * 2] - gm) * inv_temp);
     sh_max = gm;
     sh_sum = s;
+    sh_count = 0u;
   }
+  for (int i = tid; i < n2; i += TM_THREADS) top[i] = 0ull;
   __syncthreads();
-  // composites are unique and order by (logit, then lower id): a descending bitonic sort of all candidates
-  // puts the row's top-k first
-  unsigned long long* top = c;
-  for (int i = n + tid; i < n2; i += TM_THREADS) c[i] = 0ull;
+  const int top_byte = (int)(order_key(sh_max) >> 24);  // the row maximum is among the candidates
+  unsigned long long kth;
+  uint32_t need_eq, eq_total;
+  // the id half of a composite only matters when equal logits straddle the cut: stop after the key half when
+  // every candidate sharing the selected key is needed
+  select_kth<unsigned long long, TM_PER, TM_THREADS>(c, (uint32_t)k, top_byte, 32, hist, red, &sh_prefix, &sh_need,
+                                                     &sh_eq, &kth, &need_eq, &eq_total);
+  // composites are unique: exactly k of them are >= kth
+#pragma unroll
+  for (int i = 0; i < TM_PER; ++i)
+    if (c[i] >= kth && c[i] != 0ull) {
+      const uint32_t pos = atomicAdd(&sh_count, 1u);
+      if (pos < (uint32_t)n2) top[pos] = c[i];  // exactly k by construction; never write past the buffer
+    }
   __syncthreads();
   for (int size = 2; size <= n2; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
@@ -206,10 +278,10 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(const float* __r
         const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));  // stride is a power of two
         const int hi = lo + stride;
         const bool desc = ((lo & size) == 0);
-        const unsigned long long a = c[lo], b = c[hi];
+        const unsigned long long a = top[lo], b = top[hi];
         if ((a < b) == desc) {
-          c[lo] = b;
-          c[hi] = a;
+          top[lo] = b;
+          top[hi] = a;
         }
       }
       __syncthreads();
@@ -224,7 +296,7 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(const float* __r
   }
 }
 
-// chunks per row for a vocabulary of V entries and top-k k; 0 when the combination is not supported
+// chunks per row for a vocabulary of V entries; 0 when the combination is not supported
 int topk_chunks(int V, int k) {
   int n_chunks = (V + 8191) / 8192;
   if (n_chunks < 1) n_chunks = 1;
@@ -238,17 +310,14 @@ hipError_t launch_topk(const float* logits, int n, int V, int k, float inv_temp,
   const int n_chunks = topk_chunks(V, k);
   if (n_chunks == 0 || k > 1024 || k > V || k <= 0 || (V & 3)) return hipErrorInvalidValue;
   int chunk_len = ((V + n_chunks - 1) / n_chunks + 3) / 4 * 4;
-  size_t smem_a = (size_t)chunk_len * 4;
+  if (chunk_len > TC_THREADS * TC_PER || n_chunks * k > TM_THREADS * TM_PER) return hipErrorInvalidValue;
   int n2 = 1;
-  while (n2 < n_chunks * k) n2 <<= 1;
+  while (n2 < k) n2 <<= 1;
   size_t smem_b = (size_t)n2 * 8;
-  hipError_t e = hipFuncSetAttribute((const void*)topk_merge_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_b);
+  topk_chunk_kernel<<<dim3(n, n_chunks), dim3(TC_THREADS), 0, s>>>(logits, V, chunk_len, k, inv_temp, cand_ws, stats_ws);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  topk_chunk_kernel<<<dim3(n, n_chunks), dim3(TC_THREADS), smem_a, s>>>(logits, V, chunk_len, k, inv_temp, cand_ws,
-                                                                       stats_ws);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  topk_merge_kernel<<<dim3(n), dim3(TM_THREADS), smem_b, s>>>(logits, V, n_chunks, k, inv_temp, cand_ws, stats_ws, n2,
-                                                               out_ids, out_probs);
+  topk_merge_kernel<<<dim3(n), dim3(TM_THREADS), smem_b, s>>>(n_chunks, k, inv_temp, cand_ws, stats_ws, n2, out_ids,
+                                                               out_probs);
   return hipGetLastError();
 }

@@ -72,7 +72,7 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
 // ------------------------------------------------------------------------------------------------
 #define SK_BK 128  // contraction elements per main-loop iteration (8 MFMA steps)
 
-template <int MB, int MODE, bool PARTIAL>
+template <int MB, int MODE, bool PARTIAL, int NBW>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                           const bf16_t* __restrict__ Wp, int N, int NB, int K,
                                                           int iters_per_split, EpiArgs epi, float* __restrict__ part) {
@@ -85,8 +85,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
   const int total_iters = (K + SK_BK - 1) / SK_BK;
   const int it0 = blockIdx.y * iters_per_split;
   const int it1 = min(total_iters, it0 + iters_per_split);
-  // SWIGLU waves own a gate/up block pair; other modes one block per wave
-  constexpr int NBW = (MODE == EPI_SWIGLU) ? 2 : 1;
+  // a wave owns NBW adjacent 32-column blocks (SWIGLU: a gate/up pair)
   int nb0 = (blockIdx.x * 4 + wave) * NBW;
   const bool wave_active = nb0 < NB;
   if (!wave_active) nb0 = 0;  // keep loads in bounds; results are dropped
@@ -130,7 +129,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
       for (int s = 0; s < 8; ++s) {
         int kb = it * 8 + s;
         kb = kb < KB ? kb : KB - 1;  // tail steps read a valid tile; their A operand is zero
-        breg[slot][j][s] = *reinterpret_cast<const bf16x8*>(Wp + packed_tile_offset(nb0 + j, kb, KB) + lane * 8);
+        const int nbj = nb0 + j < NB ? nb0 + j : NB - 1;  // a missing second block re-reads a valid one
+        breg[slot][j][s] = *reinterpret_cast<const bf16x8*>(Wp + packed_tile_offset(nbj, kb, KB) + lane * 8);
       }
   };
 
@@ -180,13 +180,18 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           int m = i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          if (m < M) P[(int64_t)m * (NB * 32) + (nb0 + j) * 32 + (lane & 31)] = acc[j][i][v];
+          if (m < M && nb0 + j < NB) P[(int64_t)m * (NB * 32) + (nb0 + j) * 32 + (lane & 31)] = acc[j][i][v];
         }
   } else {
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
-      if (MODE == EPI_SWIGLU) epi_tile<MODE>(epi, acc[0][i], acc[NBW - 1][i], i * 32, nb0 * 32, M, NB * 32, lane);
-      else epi_tile<MODE>(epi, acc[0][i], acc[0][i], i * 32, nb0 * 32, M, N, lane);
+      if (MODE == EPI_SWIGLU) {
+        epi_tile<MODE>(epi, acc[0][i], acc[NBW - 1][i], i * 32, nb0 * 32, M, NB * 32, lane);
+      } else {
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+          if (nb0 + j < NB) epi_tile<MODE>(epi, acc[j][i], acc[j][i], i * 32, (nb0 + j) * 32, M, N, lane);
+      }
     }
   }
 }
@@ -452,15 +457,14 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
 // ------------------------------------------------------------------------------------------------
 // dispatch
 // ------------------------------------------------------------------------------------------------
-template <int MB, int MODE>
-static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
-                             size_t ws_elems, int n_cus, hipStream_t s) {
-  constexpr int NBW = (MODE == EPI_SWIGLU) ? 2 : 1;
+template <int MB, int MODE, int NBW>
+static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
+                               size_t ws_elems, int n_cus, hipStream_t s) {
   const int wg_n = (W.NB + 4 * NBW - 1) / (4 * NBW);
   const int total_iters = (W.K + SK_BK - 1) / SK_BK;
   // Split K so that one round of workgroups fills the chip without spilling into a second, mostly empty round:
   // the kernel keeps `occ` workgroups per CU resident (register-limited).
-  const int occ = (MB == 1 && MODE != EPI_SWIGLU) ? 3 : ((MB <= 2 && !(MB == 2 && MODE == EPI_SWIGLU)) ? 2 : 1);
+  const int occ = (MB == 1 && NBW == 1) ? 3 : ((MB * NBW <= 2) ? 2 : 1);
   const int slots = n_cus * occ;
   int splits = slots / wg_n;
   if (splits > total_iters / 2) splits = total_iters / 2;
@@ -472,13 +476,13 @@ static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight
   size_t smem = (size_t)2 * MB * 32 * SK_BK * sizeof(bf16_t);
   dim3 grid(wg_n, splits), block(256);
   if (splits == 1) {
-    auto kern = gemm_skinny_kernel<MB, MODE, false>;
+    auto kern = gemm_skinny_kernel<MB, MODE, false, NBW>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, nullptr);
     return hipGetLastError();
   }
-  auto kern = gemm_skinny_kernel<MB, MODE, true>;
+  auto kern = gemm_skinny_kernel<MB, MODE, true, NBW>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, ws);
@@ -488,6 +492,17 @@ static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight
   int64_t total = (int64_t)M * cols;
   splitk_epilogue_kernel<MODE><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(ws, splits, M, W.N, NP, epi);
   return hipGetLastError();
+}
+
+template <int MB, int MODE>
+static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
+                             size_t ws_elems, int n_cus, hipStream_t s) {
+  if (MODE == EPI_SWIGLU) return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  // wide outputs (LM head): two blocks per wave, so that all workgroups are resident at once (one round) and
+  // every activation operand read from LDS feeds two MFMAs
+  if (MB <= 2 && (W.NB + 3) / 4 > n_cus * (MB == 1 ? 3 : 2))
+    return run_skinny_n<MB, MODE, (MB <= 2 ? 2 : 1)>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
 }
 
 template <int MODE>
