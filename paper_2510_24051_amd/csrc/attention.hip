@@ -227,8 +227,9 @@ __device__ __forceinline__ uint32_t key_bits4(int kv_len, int n_new, bool has_bi
 }
 
 // Decode attention (requests with n_new * group <= 16 query rows), HBM-bound.
-// Grid: one wave per equal share of the flattened (request, kv head, page pair) list; a wave walks the
-// segments of its share and writes one unnormalised partial (running max, sum, O) per segment.
+// Grid: one wave per equal share of the flattened (request, kv head, page pair) list.  A share may cover the
+// end of one (request, head) and the start of the next; each such run is a segment, and the wave writes one
+// unnormalised partial (running max, sum, O) per segment.
 // Per page pair and kv head, on 16x16x32 MFMAs (16 query columns, so accumulators are half the size of the
 // 32-wide prefill tile and two waves per SIMD fit with K and V double-buffered in registers):
 //     S^T[16 keys, 16 q]  = K_page[16, D] Q^T[D, 16]          per page, D/32 MFMAs; a K operand is one
@@ -236,145 +237,91 @@ __device__ __forceinline__ uint32_t key_bits4(int kv_len, int n_new, bool has_bi
 //     O^T[D, 16 q]       += V^T[D, 32 keys] P^T[32, 16]       D/16 MFMAs over both pages at once
 // MFMA row r of a K operand is key swap23(r), so lane group g4 = lane / 16 ends up with keys
 // 4*sigma(g4) .. +3 of each page (sigma swaps the two bits of g4); P^T is then the lane's own S registers.
-// The whole next pair (16 KiB per wave) and its mask words are requested before this pair is computed.
+// The wave's whole page list (block index = page * Hkv + kv head, and logical page number) sits at an address
+// that depends on the wave index alone and is held across the lanes of two registers, so the first K/V request
+// goes out after a single dependent load, and the K/V stream runs on across segment boundaries: the next pair
+// (16 KiB per wave) is always requested before the current one is computed.  Segment descriptors, queries and
+// (for bitmap requests) the mask words of pairs requested before a boundary are loaded at the boundary.
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const DecodeSeg* __restrict__ segs,
-                                                             const int32_t* __restrict__ wave_seg, int n_waves,
+__global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const DecodeWave* __restrict__ waves,
+                                                             const int2* __restrict__ wave_pg, int slots,
+                                                             const DecodeSeg* __restrict__ segs, int n_waves,
                                                              int rows_cap, float* __restrict__ part_o,
                                                              float* __restrict__ part_ml) {
   constexpr int KS = D / 32;  // K operands per page
   constexpr int DB = D / 16;  // 16-row blocks of O^T
   const int lane = threadIdx.x & 63;
-  const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
   if (gw >= n_waves) return;
   const int G = a.Hq / a.Hkv;
   const int qcol = lane & 15, g4 = lane >> 4;
   const int quad = ((g4 & 1) << 1) | (g4 >> 1);  // sigma(g4): this lane group's key quad within a page
-  const int64_t blk = 2 * PAGE * D;
+  constexpr int64_t blk = 2 * PAGE * D;
   const int koff = lane * 8;                                                    // + s32 * 512 elements
   const int voff = PAGE * D + (quad >> 1) * 256 + qcol * 8 + (quad & 1) * 4;    // + (d / 32) * 512 + ((d / 16) & 1) * 128
-  const int seg_end = wave_seg[gw + 1];
-  for (int sg = wave_seg[gw]; sg < seg_end; ++sg) {
-    const DecodeSeg it = segs[sg];
-    const int hk = it.hk;
-    const int rows = it.n_new * G;
-    const bool valid = qcol < rows;
-    const int i_tok = valid ? qcol / G : 0;
-    const int hg = valid ? qcol % G : 0;
-    const bool has_bitmap = it.wpr > 0;
-    bf16x8 qf[KS];
-    {
-      const bf16_t* qrow = a.q + (int64_t)(it.tok0 + i_tok) * a.q_stride + (hk * G + hg) * D + g4 * 8;
+  // the wave's page list: slot 2j and 2j+1 are pair j (second block index -1: the pair has one page)
+  const int2* wp = wave_pg + (int64_t)gw * slots;
+  int2 id_lo = wp[min(lane, slots - 1)];        // clamped loads: lanes past the list are never consulted
+  int2 id_hi = wp[min(lane + 64, slots - 1)];
+  const DecodeWave wv = waves[gw];
+  const int n_pairs = __builtin_amdgcn_readfirstlane(wv.n_pairs);
+  int cur_sg = __builtin_amdgcn_readfirstlane(wv.seg0) - 1;
+  int seg_end = 0;  // wave-local index of the first pair after the current segment
+
+  // per-segment state
+  int s_kv_len = 0, s_n_new = 1;
+  bool valid = false, has_bitmap = false;
+  int i_tok = 0;
+  const uint32_t* mrow = a.mask_words;
+  bf16x8 qf[KS];
 #pragma unroll
-      for (int k = 0; k < KS; ++k) {
-        Pack16 p;
-        p.u = u32x4{0, 0, 0, 0};
-        if (valid) p.u = *reinterpret_cast<const u32x4*>(qrow + k * 32);
-        qf[k] = p.h;
-      }
+  for (int k = 0; k < KS; ++k) { Pack16 p; p.u = u32x4{0, 0, 0, 0}; qf[k] = p.h; }
+  f32x4 o[DB];
+#pragma unroll
+  for (int b = 0; b < DB; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float st_m = -INFINITY, st_l = 0.f;
+
+  // two register sets, used alternately; the set index is a compile-time constant so they stay in registers
+  bf16x8 ka[2][KS], kb[2][KS];
+  bf16x4 va[2][DB], vb[2][DB];
+  int pl_a[2] = {0, 0}, pl_b[2] = {0, 0};
+  uint32_t mw_a[2] = {0u, 0u}, mw_b[2] = {0u, 0u};
+  bool has_b[2] = {false, false};
+
+  auto load_mask = [&](auto set_c) {
+    constexpr int S = decltype(set_c)::value;
+    if (has_bitmap && valid) { mw_a[S] = mrow[pl_a[S] >> 1]; mw_b[S] = mrow[pl_b[S] >> 1]; }
+  };
+  auto fetch = [&](auto set_c, int j) {  // j is wave-uniform
+    constexpr int S = decltype(set_c)::value;
+    const int src = (2 * j) & 63;
+    const bool low = 2 * j < 64;
+    const int pp_a = __builtin_amdgcn_readlane(low ? id_lo.x : id_hi.x, src);
+    pl_a[S] = __builtin_amdgcn_readlane(low ? id_lo.y : id_hi.y, src);
+    int pp_b = __builtin_amdgcn_readlane(low ? id_lo.x : id_hi.x, src + 1);
+    pl_b[S] = __builtin_amdgcn_readlane(low ? id_lo.y : id_hi.y, src + 1);
+    has_b[S] = pp_b >= 0;
+    if (!has_b[S]) { pp_b = pp_a; pl_b[S] = pl_a[S]; }
+    if (j < seg_end) load_mask(set_c);  // the pair belongs to the current segment: its mask row is known
+    const bf16_t* pa_ = a.kv + (int64_t)pp_a * blk;
+    const bf16_t* pb_ = a.kv + (int64_t)pp_b * blk;
+#pragma unroll
+    for (int k = 0; k < KS; ++k) {
+      ka[S][k] = *reinterpret_cast<const bf16x8*>(pa_ + koff + k * 512);
+      kb[S][k] = *reinterpret_cast<const bf16x8*>(pb_ + koff + k * 512);
     }
-    // page ids of the segment live across the lanes of two registers (<= 128 pages per segment)
-    const int n_pg = it.n_pg;
-    const int vphys_lo = lane < n_pg ? a.visit_phys[it.v0 + lane] : 0;
-    const int vphys_hi = lane + 64 < n_pg ? a.visit_phys[it.v0 + lane + 64] : 0;
-    const int vlog_lo = lane < n_pg ? a.visit_logical[it.v0 + lane] : 0;
-    const int vlog_hi = lane + 64 < n_pg ? a.visit_logical[it.v0 + lane + 64] : 0;
-    auto page_of = [&](int i, int& phys, int& logical) {  // i is wave-uniform
-      const int src = i & 63;
-      phys = __builtin_amdgcn_readlane(i < 64 ? vphys_lo : vphys_hi, src);
-      logical = __builtin_amdgcn_readlane(i < 64 ? vlog_lo : vlog_hi, src);
-    };
-    const uint32_t* mrow = a.mask_words + it.mask_off + (int64_t)i_tok * it.wpr;
-    f32x4 o[DB];
 #pragma unroll
-    for (int b = 0; b < DB; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float st_m = -INFINITY, st_l = 0.f;
-    // two register sets, used alternately; the set index is a compile-time constant so they stay in registers
-    bf16x8 ka[2][KS], kb[2][KS];
-    bf16x4 va[2][DB], vb[2][DB];
-    int pl_a[2] = {0, 0}, pl_b[2] = {0, 0};
-    uint32_t mw_a[2] = {0u, 0u}, mw_b[2] = {0u, 0u};
-    bool has_b[2] = {false, false};
-    auto fetch = [&](auto set_c, int i) {
-      constexpr int S = decltype(set_c)::value;
-      int pp_a, pp_b;
-      page_of(i, pp_a, pl_a[S]);
-      has_b[S] = i + 1 < n_pg;
-      if (has_b[S]) page_of(i + 1, pp_b, pl_b[S]);
-      else { pp_b = pp_a; pl_b[S] = pl_a[S]; }
-      if (has_bitmap && valid) { mw_a[S] = mrow[pl_a[S] >> 1]; mw_b[S] = mrow[pl_b[S] >> 1]; }
-      const bf16_t* pa_ = a.kv + ((int64_t)pp_a * a.Hkv + hk) * blk;
-      const bf16_t* pb_ = a.kv + ((int64_t)pp_b * a.Hkv + hk) * blk;
-#pragma unroll
-      for (int k = 0; k < KS; ++k) {
-        ka[S][k] = *reinterpret_cast<const bf16x8*>(pa_ + koff + k * 512);
-        kb[S][k] = *reinterpret_cast<const bf16x8*>(pb_ + koff + k * 512);
-      }
-#pragma unroll
-      for (int b = 0; b < DB; ++b) {
-        const int vo = voff + (b >> 1) * 512 + (b & 1) * 128;
-        va[S][b] = *reinterpret_cast<const bf16x4*>(pa_ + vo);
-        vb[S][b] = *reinterpret_cast<const bf16x4*>(pb_ + vo);
-      }
-    };
-    auto compute = [&](auto set_c) {
-      constexpr int S = decltype(set_c)::value;
-      const uint32_t bits_a = key_bits4(it.kv_len, it.n_new, has_bitmap, mw_a[S], i_tok, pl_a[S], quad, valid);
-      const uint32_t bits_b =
-          has_b[S] ? key_bits4(it.kv_len, it.n_new, has_bitmap, mw_b[S], i_tok, pl_b[S], quad, valid) : 0u;
-      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int k = 0; k < KS; ++k) {
-        sa = mfma16(ka[S][k], qf[k], sa);
-        sb = mfma16(kb[S][k], qf[k], sb);
-      }
-      float sv[8];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        sv[e] = ((bits_a >> e) & 1u) ? sa[e] * a.scale_log2 : -INFINITY;
-        sv[4 + e] = ((bits_b >> e) & 1u) ? sb[e] * a.scale_log2 : -INFINITY;
-        mx = fmaxf(mx, fmaxf(sv[e], sv[4 + e]));
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(st_m, mx);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(st_m - m_safe);
-      float lsum = 0.f;
-      Pack16 pp;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float p = __builtin_amdgcn_exp2f(sv[e] - m_safe);
-        lsum += p;
-        pp.h[e] = f32_to_bf16(p);
-      }
-      st_l = st_l * alpha + lsum;
-      st_m = m_new;
-#pragma unroll
-      for (int b = 0; b < DB; ++b) {
-        bf16x8 vv;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { vv[e] = va[S][b][e]; vv[4 + e] = vb[S][b][e]; }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[b][e] *= alpha;
-        o[b] = mfma16(vv, pp.h, o[b]);
-      }
-    };
-    std::integral_constant<int, 0> set0;
-    std::integral_constant<int, 1> set1;
-    if (n_pg > 0) fetch(set0, 0);
-    for (int i = 0; i < n_pg; i += 4) {
-      if (i + 2 < n_pg) fetch(set1, i + 2);
-      compute(set0);
-      if (i + 2 >= n_pg) break;
-      if (i + 4 < n_pg) fetch(set0, i + 4);
-      compute(set1);
+    for (int b = 0; b < DB; ++b) {
+      const int vo = voff + (b >> 1) * 512 + (b & 1) * 128;
+      va[S][b] = *reinterpret_cast<const bf16x4*>(pa_ + vo);
+      vb[S][b] = *reinterpret_cast<const bf16x4*>(pb_ + vo);
     }
+  };
+  auto end_segment = [&]() {
     float l_tot = st_l + __shfl_xor(st_l, 16);
     l_tot += __shfl_xor(l_tot, 32);
     if (valid) {
-      const int64_t prow = (int64_t)sg * rows_cap + qcol;
+      const int64_t prow = (int64_t)cur_sg * rows_cap + qcol;
       if (g4 == 0) {
         part_ml[prow * 2] = st_m;
         part_ml[prow * 2 + 1] = l_tot;
@@ -383,7 +330,94 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
 #pragma unroll
       for (int b = 0; b < DB; ++b) *reinterpret_cast<f32x4*>(po + b * 16) = o[b];
     }
+  };
+  auto begin_segment = [&](int j) {
+    ++cur_sg;
+    const DecodeSeg it = segs[cur_sg];
+    const int rows = it.n_new * G;
+    valid = qcol < rows;
+    i_tok = valid ? qcol / G : 0;
+    const int hg = valid ? qcol % G : 0;
+    has_bitmap = it.wpr > 0;
+    s_kv_len = it.kv_len; s_n_new = it.n_new;
+    mrow = a.mask_words + it.mask_off + (int64_t)i_tok * it.wpr;
+    const bf16_t* qrow = a.q + (int64_t)(it.tok0 + i_tok) * a.q_stride + (it.hk * G + hg) * D + g4 * 8;
+#pragma unroll
+    for (int k = 0; k < KS; ++k) {
+      Pack16 p;
+      p.u = u32x4{0, 0, 0, 0};
+      if (valid) p.u = *reinterpret_cast<const u32x4*>(qrow + k * 32);
+      qf[k] = p.h;
+    }
+#pragma unroll
+    for (int b = 0; b < DB; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st_m = -INFINITY;
+    st_l = 0.f;
+    seg_end = j + it.n_pairs;
+  };
+  auto compute = [&](auto set_c, auto other_c, int j) {
+    constexpr int S = decltype(set_c)::value;
+    if (j == seg_end) {  // wave-uniform: pair j opens the next segment
+      if (j > 0) end_segment();
+      begin_segment(j);
+      // mask words of the pairs that were requested before the boundary
+      load_mask(set_c);
+      if (j + 1 < seg_end && j + 1 < n_pairs) load_mask(other_c);
+    }
+    const uint32_t bits_a = key_bits4(s_kv_len, s_n_new, has_bitmap, mw_a[S], i_tok, pl_a[S], quad, valid);
+    const uint32_t bits_b =
+        has_b[S] ? key_bits4(s_kv_len, s_n_new, has_bitmap, mw_b[S], i_tok, pl_b[S], quad, valid) : 0u;
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < KS; ++k) {
+      sa = mfma16(ka[S][k], qf[k], sa);
+      sb = mfma16(kb[S][k], qf[k], sb);
+    }
+    float sv[8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      sv[e] = ((bits_a >> e) & 1u) ? sa[e] * a.scale_log2 : -INFINITY;
+      sv[4 + e] = ((bits_b >> e) & 1u) ? sb[e] * a.scale_log2 : -INFINITY;
+      mx = fmaxf(mx, fmaxf(sv[e], sv[4 + e]));
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(st_m, mx);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st_m - m_safe);
+    float lsum = 0.f;
+    Pack16 pp;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float p = __builtin_amdgcn_exp2f(sv[e] - m_safe);
+      lsum += p;
+      pp.h[e] = f32_to_bf16(p);
+    }
+    st_l = st_l * alpha + lsum;
+    st_m = m_new;
+#pragma unroll
+    for (int b = 0; b < DB; ++b) {
+      bf16x8 vv;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { vv[e] = va[S][b][e]; vv[4 + e] = vb[S][b][e]; }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[b][e] *= alpha;
+      o[b] = mfma16(vv, pp.h, o[b]);
+    }
+  };
+  if (n_pairs <= 0) return;
+  std::integral_constant<int, 0> set0;
+  std::integral_constant<int, 1> set1;
+  fetch(set0, 0);
+  for (int j = 0; j < n_pairs; j += 2) {
+    if (j + 1 < n_pairs) fetch(set1, j + 1);
+    compute(set0, set1, j);
+    if (j + 1 >= n_pairs) break;
+    if (j + 2 < n_pairs) fetch(set0, j + 2);
+    compute(set1, set0, j + 1);
   }
+  end_segment();
 }
 
 // One wave per (decode-path request, kv head, query row): lanes first share the segments' (max, sum) pairs,
@@ -655,12 +689,16 @@ __global__ __launch_bounds__(512) void attn_prefill_direct_kernel(AttnArgs a, co
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_attn_decode(const AttnArgs& a, const DecodeSeg* segs, const int32_t* wave_seg, int n_waves,
-                              int rows_cap, float* part_o, float* part_ml, hipStream_t s) {
+hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const int2* wave_pg, int slots,
+                              const DecodeSeg* segs, int n_waves, int rows_cap, float* part_o, float* part_ml,
+                              hipStream_t s) {
   if (n_waves <= 0) return hipSuccess;
+  if (slots < 2 || slots > 128 || (slots & 1)) return hipErrorInvalidValue;  // the page list must fit two registers
   dim3 grid((n_waves + 3) / 4), block(256);
-  if (a.D == 128) attn_decode_kernel<128><<<grid, block, 0, s>>>(a, segs, wave_seg, n_waves, rows_cap, part_o, part_ml);
-  else if (a.D == 64) attn_decode_kernel<64><<<grid, block, 0, s>>>(a, segs, wave_seg, n_waves, rows_cap, part_o, part_ml);
+  if (a.D == 128)
+    attn_decode_kernel<128><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, n_waves, rows_cap, part_o, part_ml);
+  else if (a.D == 64)
+    attn_decode_kernel<64><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, n_waves, rows_cap, part_o, part_ml);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

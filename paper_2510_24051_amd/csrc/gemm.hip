@@ -497,12 +497,15 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
 template <int MB, int MODE>
 static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
                              size_t ws_elems, int n_cus, hipStream_t s) {
-  if (MODE == EPI_SWIGLU) return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
-  // wide outputs (LM head): two blocks per wave, so that all workgroups are resident at once (one round) and
-  // every activation operand read from LDS feeds two MFMAs
-  if (MB <= 2 && (W.NB + 3) / 4 > n_cus * (MB == 1 ? 3 : 2))
-    return run_skinny_n<MB, MODE, (MB <= 2 ? 2 : 1)>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
-  return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if constexpr (MODE == EPI_SWIGLU) {
+    return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  } else {
+    // wide outputs (LM head): two blocks per wave halve the workgroup count and the activation reads from LDS
+    if constexpr (MB <= 2)
+      if ((W.NB + 3) / 4 > n_cus * (MB == 1 ? 3 : 2))
+        return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+    return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  }
 }
 
 template <int MODE>

@@ -52,13 +52,14 @@ struct ReqInfo {       // one per request, device + host
   int32_t pad;
 };
 
-struct DecodeSeg {     // a run of page pairs of one (decode-path request, kv head), processed by one wave
+struct DecodeSeg {     // a run of page pairs of one (decode-path request, kv head) inside one wave's share
   int32_t tok0, n_new, kv_len;
-  int32_t v0, n_pg;    // visit-list entries [v0, v0 + n_pg), n_pg <= 128
+  int32_t n_pairs;     // page pairs of the run (the last pair of a (request, head) may hold one page)
   int32_t wpr;
+  int32_t hk;
   int64_t mask_off;
-  int32_t hk, pad;
 };
+struct DecodeWave { int32_t seg0, n_seg, n_pairs, pad; };  // a wave's share: segments [seg0, seg0 + n_seg)
 struct SegRange { int32_t first, count; };  // segments of one (decode-path request, kv head), in key order
 struct PrefillItem { int32_t r, qb; };           // query block qb (32 tokens) of request r
 
@@ -70,11 +71,12 @@ struct pie_batch {
   uint32_t* mask_words = nullptr;
   ReqInfo* reqs = nullptr;
   DecodeSeg* dsegs = nullptr;
-  int32_t* wave_seg = nullptr;   // [n_dwaves + 1] segments of each wave
+  DecodeWave* dwaves = nullptr;  // [n_dwaves]
+  int2* wave_pg = nullptr;       // [n_dwaves, dslots] (page * Hkv + kv head, logical page) of every pair slot
   SegRange* seg_ranges = nullptr;  // [n_dec_reqs * Hkv]
   PrefillItem* pitems = nullptr;
   int32_t* dec_reqs = nullptr;  // request indices on the decode path
-  int32_t n_dsegs = 0, n_dwaves = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
+  int32_t n_dsegs = 0, n_dwaves = 0, dslots = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
   float* part_o = nullptr;   // [n_dsegs * rows_cap, D]
   float* part_ml = nullptr;  // [n_dsegs * rows_cap, 2]
   int64_t work[4] = {0, 0, 0, 0};
@@ -155,8 +157,9 @@ struct AttnArgs {
   const int32_t* visit_logical;
   const uint32_t* mask_words;
 };
-hipError_t launch_attn_decode(const AttnArgs& a, const DecodeSeg* segs, const int32_t* wave_seg, int n_waves,
-                              int rows_cap, float* part_o, float* part_ml, hipStream_t s);
+hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const int2* wave_pg, int slots,
+                              const DecodeSeg* segs, int n_waves, int rows_cap, float* part_o, float* part_ml,
+                              hipStream_t s);
 hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const SegRange* ranges,
                              int rows_cap, const float* part_o, const float* part_ml, hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s);

@@ -60,6 +60,8 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   if (p->n_kv_pages <= 0 || p->n_embeds <= 0 || p->max_batch_tokens <= 0 || p->max_batch_requests <= 0 ||
       p->max_top_k < 0 || p->max_dist_rows < 0 || p->max_top_k > 1024)
     return fail(nullptr, PIE_EINVAL, "pool sizes must be positive (max_top_k <= 1024)");
+  if ((int64_t)p->n_kv_pages * m->n_kv_heads > INT32_MAX)
+    return fail(nullptr, PIE_EUNSUPPORTED, "n_kv_pages * n_kv_heads must fit 31 bits (page-head block indices are int32)");
 
   pie_ctx* c = new pie_ctx();
   c->m = *m;
@@ -374,17 +376,31 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
         return fail(c, PIE_ECONFLICT, "token %d writes (page %d, slot %d) that another token of the batch writes", t, tok_page[t], tok_slot[t]);
   }
   // Decode path: the page pairs of all (request, kv head) combinations form one flat list that is cut into
-  // equal shares, one per wave, for as many waves as the chip keeps resident.  A share may cover the end of
-  // one (request, head) and the start of the next; each such run is a segment with its own partial result.
+  // equal shares, one per wave, for as many waves as the chip keeps resident (more when a share would exceed
+  // the 64 pairs whose page ids a wave holds in registers).  A share may cover the end of one (request, head)
+  // and the start of the next; each such run is a segment with its own partial result.  Every wave gets its
+  // page list (block index = page * Hkv + kv head, logical page) at a fixed stride, two slots per pair.
   std::vector<DecodeSeg> dsegs;
-  std::vector<int32_t> wave_seg(1, 0);
+  std::vector<DecodeWave> dwaves;
+  std::vector<int2> wave_pg;
   std::vector<SegRange> seg_ranges(dec_reqs.size() * Hkv, SegRange{0, 0});
+  int dslots = 2;
   {
     int64_t total_pairs = 0;
     for (int r : dec_reqs) total_pairs += (int64_t)((reqs[r].n_visit + 1) / 2) * Hkv;
     int64_t per_wave = (total_pairs + c->wave_slots - 1) / c->wave_slots;
-    per_wave = std::max<int64_t>(per_wave, 2);
-    int64_t filled = 0;
+    per_wave = std::min<int64_t>(std::max<int64_t>(per_wave, 2), 64);
+    dslots = (int)(2 * per_wave);
+    wave_pg.reserve((size_t)((total_pairs + per_wave - 1) / per_wave + 1) * dslots);
+    int filled = 0;
+    DecodeWave cur{0, 0, 0, 0};
+    auto close_wave = [&]() {
+      cur.n_pairs = filled;
+      dwaves.push_back(cur);
+      wave_pg.resize(dwaves.size() * (size_t)dslots, make_int2(-1, 0));
+      cur = DecodeWave{(int32_t)dsegs.size(), 0, 0, 0};
+      filled = 0;
+    };
     for (size_t di = 0; di < dec_reqs.size(); ++di) {
       const ReqInfo& q = reqs[dec_reqs[di]];
       const int P = (q.n_visit + 1) / 2;
@@ -393,20 +409,37 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
         rg.first = (int32_t)dsegs.size();
         int p = 0;
         while (p < P) {
-          int take = (int)std::min<int64_t>(std::min<int64_t>(per_wave - filled, P - p), 64);
-          dsegs.push_back(DecodeSeg{q.tok0, q.n_new, q.kv_len, q.visit0 + 2 * p, std::min(q.n_visit - 2 * p, 2 * take),
-                                    q.wpr, q.mask_off, hk, 0});
+          const int take = (int)std::min<int64_t>(per_wave - filled, P - p);
+          dsegs.push_back(DecodeSeg{q.tok0, q.n_new, q.kv_len, take, q.wpr, hk, q.mask_off});
+          ++cur.n_seg;
+          for (int pr = p; pr < p + take; ++pr)
+            for (int e = 0; e < 2; ++e) {
+              const int v = 2 * pr + e;
+              wave_pg.push_back(v < q.n_visit ? make_int2(visit_phys[q.visit0 + v] * Hkv + hk, visit_logical[q.visit0 + v])
+                                              : make_int2(-1, 0));
+            }
           p += take;
           filled += take;
-          if (filled == per_wave) {
-            wave_seg.push_back((int32_t)dsegs.size());
-            filled = 0;
-          }
+          if (filled == per_wave) close_wave();
         }
         rg.count = (int32_t)dsegs.size() - rg.first;
       }
     }
-    if (wave_seg.back() != (int32_t)dsegs.size()) wave_seg.push_back((int32_t)dsegs.size());
+    if (filled > 0) close_wave();
+    // the kernel trusts this plan: check what it assumes before anything is launched from it
+    const int64_t n_blocks = (int64_t)c->p.n_kv_pages * Hkv;
+    for (size_t w = 0; w < dwaves.size(); ++w) {
+      const DecodeWave& dw = dwaves[w];
+      int pairs = 0;
+      for (int sg = dw.seg0; sg < dw.seg0 + dw.n_seg; ++sg) pairs += dsegs[sg].n_pairs;
+      bool ok = dw.n_seg > 0 && dw.seg0 >= 0 && dw.seg0 + dw.n_seg <= (int)dsegs.size() && pairs == dw.n_pairs &&
+                dw.n_pairs > 0 && 2 * dw.n_pairs <= dslots;
+      for (int j = 0; ok && j < 2 * dw.n_pairs; ++j) {
+        const int2 e = wave_pg[w * dslots + j];
+        ok = (e.x >= 0 || (j & 1)) && e.x < n_blocks && e.y >= 0;
+      }
+      if (!ok) return fail(c, PIE_EINVAL, "internal: inconsistent decode plan for wave %zu", w);
+    }
   }
   // heavy query blocks first
   std::stable_sort(pitems.begin(), pitems.end(), [&](const PrefillItem& x, const PrefillItem& y) {
@@ -420,7 +453,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   pie_batch* pb = new pie_batch();
   pb->R = R; pb->T = T;
   pb->n_dsegs = (int32_t)dsegs.size();
-  pb->n_dwaves = (int32_t)wave_seg.size() - 1;
+  pb->n_dwaves = (int32_t)dwaves.size();
+  pb->dslots = dslots;
   pb->n_pitems = (int32_t)pitems.size();
   pb->n_dec_reqs = (int32_t)dec_reqs.size();
   pb->rows_cap = std::max(rows_cap, 1);
@@ -435,7 +469,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   const size_t o_mw = blob.add(n_mask ? b->mask_words : nullptr, n_mask * 4, 4);
   const size_t o_rq = blob.add(reqs.data(), reqs.size() * sizeof(ReqInfo));
   const size_t o_di = blob.add(dsegs.data(), dsegs.size() * sizeof(DecodeSeg), 16);
-  const size_t o_ws = blob.add(wave_seg.data(), wave_seg.size() * 4, 4);
+  const size_t o_ws = blob.add(dwaves.data(), dwaves.size() * sizeof(DecodeWave), 16);
+  const size_t o_wp = blob.add(wave_pg.data(), wave_pg.size() * sizeof(int2), 16);
   const size_t o_sr = blob.add(seg_ranges.data(), seg_ranges.size() * sizeof(SegRange), 8);
   const size_t o_pi = blob.add(pitems.data(), pitems.size() * sizeof(PrefillItem), 8);
   const size_t o_dr = blob.add(dec_reqs.data(), dec_reqs.size() * 4, 4);
@@ -461,7 +496,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   pb->tok_page = (int32_t*)(d + o_tp); pb->tok_slot = (int32_t*)(d + o_ts);
   pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl);
   pb->mask_words = (uint32_t*)(d + o_mw); pb->reqs = (ReqInfo*)(d + o_rq);
-  pb->dsegs = (DecodeSeg*)(d + o_di); pb->wave_seg = (int32_t*)(d + o_ws); pb->seg_ranges = (SegRange*)(d + o_sr);
+  pb->dsegs = (DecodeSeg*)(d + o_di); pb->dwaves = (DecodeWave*)(d + o_ws); pb->wave_pg = (int2*)(d + o_wp); pb->seg_ranges = (SegRange*)(d + o_sr);
   pb->pitems = (PrefillItem*)(d + o_pi); pb->dec_reqs = (int32_t*)(d + o_dr);
   pb->part_o = (float*)(d + o_po); pb->part_ml = (float*)(d + o_pm);
   *out = pb;
@@ -530,7 +565,7 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
   a.reqs = b->reqs; a.visit_phys = b->visit_phys; a.visit_logical = b->visit_logical; a.mask_words = b->mask_words;
   if (b->n_dec_reqs > 0) {
     tm.begin(PIE_STAGE_ATTN_DECODE);
-    HIP_TRY(c, launch_attn_decode(a, b->dsegs, b->wave_seg, b->n_dwaves, b->rows_cap, b->part_o, b->part_ml, s));
+    HIP_TRY(c, launch_attn_decode(a, b->dwaves, b->wave_pg, b->dslots, b->dsegs, b->n_dwaves, b->rows_cap, b->part_o, b->part_ml, s));
     tm.end(PIE_STAGE_ATTN_DECODE);
     tm.begin(PIE_STAGE_ATTN_MERGE);
     HIP_TRY(c, launch_attn_merge(a, b->dec_reqs, b->n_dec_reqs, b->seg_ranges, b->rows_cap, b->part_o, b->part_ml, s));
