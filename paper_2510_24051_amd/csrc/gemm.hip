@@ -508,6 +508,16 @@ static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight
   }
 }
 
+// The epilogue arguments of rows m0.. of the same product.
+template <int MODE>
+static EpiArgs offset_rows(EpiArgs e, int m0) {
+  if (MODE == EPI_STORE_BF16 || MODE == EPI_SWIGLU) e.out = reinterpret_cast<bf16_t*>(e.out) + (int64_t)m0 * e.ldo;
+  if (MODE == EPI_STORE_F32 || MODE == EPI_RESID_EMBED) e.out = reinterpret_cast<float*>(e.out) + (int64_t)m0 * e.ldo;
+  if (MODE == EPI_RESID_EMBED || MODE == EPI_RESID_OUT) e.ids += m0;
+  if (MODE == EPI_RESID_OUT) e.resid += (int64_t)m0 * e.H;
+  return e;
+}
+
 template <int MODE>
 static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
                            size_t ws_elems, int n_cus, hipStream_t s) {
@@ -517,7 +527,20 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   if (M <= 128) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   if (M <= 256 && MODE != EPI_SWIGLU) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   if (W.K % 128 == 0) {
-    const int tiles_m = (M + LG_BM - 1) / LG_BM, tiles_n = (W.NB + 7) / 8;
+    const int tiles_n = (W.NB + 7) / 8;
+    // A ragged last row block that would open one more round of tiles (a round = one tile per CU) costs a whole
+    // round for a fraction of a tile's work: those rows go through the weight-streaming kernel instead.
+    const int full = M / LG_BM, ragged = M % LG_BM;
+    auto rounds = [&](int tm) { return (tm * tiles_n + n_cus - 1) / n_cus; };
+    if (ragged > 0 && full > 0 && (ragged <= 128 || MODE != EPI_SWIGLU) && rounds(full + 1) > rounds(full)) {
+      const int M0 = full * LG_BM;
+      gemm_large_async_kernel<MODE><<<dim3(full * tiles_n), dim3(512), 0, s>>>(A, lda, M0, W.data, W.N, W.NB, W.K, epi,
+                                                                              full, tiles_n);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      return run_mode<MODE>(A + (int64_t)M0 * lda, lda, ragged, W, offset_rows<MODE>(epi, M0), ws, ws_elems, n_cus, s);
+    }
+    const int tiles_m = (M + LG_BM - 1) / LG_BM;
     gemm_large_async_kernel<MODE><<<dim3(tiles_m * tiles_n), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, epi,
                                                                                 tiles_m, tiles_n);
     return hipGetLastError();
