@@ -1,6 +1,7 @@
 """CPU oracle for the batched `forward` handler (one Llama-class decoder layer over a
-heterogeneous batch of commands against KvPage page tables with per-token masks and KV append)
-and for the `get_next_dist` handler (vocab softmax truncated to top-K).
+heterogeneous batch of commands against KvPage page tables with per-token masks and KV append,
+and the same call through every layer of the model), for the `embed_txt` handler (token ids and
+positions into Embeds) and for the `get_next_dist` handler (vocab softmax truncated to top-K).
 
 THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, dense NumPy implementation written from the
 paper's statement of the two calls (Programming Model and API: Resources; Forward API; Sample
@@ -27,6 +28,10 @@ Parity pins (tests/test_oracle_*.py, all CPU):
   norm / SiLU / GEMM  closed forms, torch CPU rms_norm / silu, zero Wo and Wdown -> y == x
   whole layer         torch CPU expression of a textbook Llama layer on one contiguous request
   softmax / top-k     torch.softmax + torch.topk, k=V sums to 1, shift invariance
+  embed_txt           one-hot matrix product, positions recorded with the Embed
+  full depth          torch CPU expression of a textbook L-layer Llama on one contiguous request;
+                      zero Wo and Wdown in every layer -> output == input; prefill of n tokens ==
+                      n-1 tokens writing pages + 1 token reading them, through all layers
 Parity unpinned (convention-internal, the paper is silent): rotate-half pairing, K stored after
 the rotary step, final norm inside get_next_dist, tie order of equal probabilities.
 """
@@ -81,6 +86,7 @@ class EmbedPool:
 
     def __init__(self, n_embeds: int, hidden: int):
         self.bits = np.zeros((n_embeds, hidden), dtype=np.uint16)
+        self.pos = np.full(n_embeds, -1, dtype=np.int64)  # sequence position recorded by embed_txt, -1 = none
 
     def write(self, ids, bits):
         self.bits[np.asarray(ids, dtype=np.int64)] = np.asarray(bits, dtype=np.uint16)
@@ -199,7 +205,8 @@ def _maybe_round(x: np.ndarray, on: bool) -> np.ndarray:
 
 
 def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional[Sequence[int]] = None,
-            round_intermediates: bool = False, write_embeds: bool = True) -> ForwardResult:
+            round_intermediates: bool = False, write_embeds: bool = True,
+            x_in: Optional[np.ndarray] = None) -> ForwardResult:
     """One decoder layer over a batch of `forward` commands (Forward API; Table 1 `forward`).
 
     `model`   : hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, page_size, rms_eps, rope_theta
@@ -210,6 +217,10 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
                 word offsets; empty range = infer causal), mask_words.
     `rows`    : restrict the per-token outputs to these token indices (the K/V append is always done
                 for every token, since any later token may attend to it).
+    `x_in`    : float64 [T, H] layer input that replaces the Embed read (used by `forward_model` for
+                the layers after the first, whose input is the previous layer's output).
+    `batch.positions` may be None: the positions are then those recorded with the input Embeds by
+    `embed_txt` (Forward API: the call works on the sequence positions associated with its resources).
 
     Order of effects inside one call: every input Embed is read first; every K/V append lands
     before any attention read; output Embeds are written last.  New token i of a request sits
@@ -223,7 +234,11 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
     page_indptr = np.asarray(batch.page_indptr, dtype=np.int64)
     page_ids = np.asarray(batch.page_ids, dtype=np.int64)
     kv_len = np.asarray(batch.kv_len, dtype=np.int64)
-    positions = np.asarray(batch.positions, dtype=np.int64)
+    if batch.positions is None:
+        positions = emb.pos[np.asarray(batch.in_embed_ids, dtype=np.int64)]
+        assert (positions >= 0).all(), "an input Embed carries no position"
+    else:
+        positions = np.asarray(batch.positions, dtype=np.int64)
     assert tok_indptr[0] == 0 and tok_indptr[R] == T
 
     rnd = round_intermediates
@@ -231,7 +246,11 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
     g1, g2 = bf16_decode(weights.g1), bf16_decode(weights.g2)
 
     # 1-3: read input Embeds, first norm, K/V projections for every token
-    x_all = bf16_decode(emb.bits[np.asarray(batch.in_embed_ids, dtype=np.int64)])  # [T, H]
+    if x_in is None:
+        x_all = bf16_decode(emb.bits[np.asarray(batch.in_embed_ids, dtype=np.int64)])  # [T, H]
+    else:
+        x_all = np.asarray(x_in, dtype=np.float64)
+        assert x_all.shape == (T, H)
     xn_all = _maybe_round(rmsnorm(x_all, g1, model.rms_eps), rnd)
     k_all = _maybe_round(xn_all @ Wk.T, rnd).reshape(T, Hkv, D)
     v_all = _maybe_round(xn_all @ Wv.T, rnd).reshape(T, Hkv, D)
@@ -297,6 +316,44 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
         keep = out_ids >= 0
         emb.bits[out_ids[keep]] = bf16_encode(y[keep])
     return ForwardResult(rows=rows, y=y, q=q_out, o=o_out, h=h, k_new=k_new, v_new=v_new)
+
+
+# --------------------------------------------------------------------------------------------
+# embed_txt handler and the forward pass through every layer
+# --------------------------------------------------------------------------------------------
+
+
+def embed_txt(table_bits: np.ndarray, token_ids, positions, emb: EmbedPool, embed_ids) -> None:
+    """Embed API `embed_txt(tok, pos, embs)` (Table 1, InputText): Embed `embed_ids[i]` receives row
+    `token_ids[i]` of the embedding table `[vocab, hidden]` (bf16 bits, copied unchanged) and the
+    sequence position `positions[i]`, which later `forward` calls use for the rotary step."""
+    tok = np.asarray(token_ids, dtype=np.int64)
+    ids = np.asarray(embed_ids, dtype=np.int64)
+    pos = np.asarray(positions, dtype=np.int64)
+    assert tok.shape == ids.shape == pos.shape
+    assert (tok >= 0).all() and (tok < table_bits.shape[0]).all()
+    emb.bits[ids] = np.asarray(table_bits, dtype=np.uint16)[tok]
+    emb.pos[ids] = pos
+
+
+def forward_model(model, layers, kvs, emb: EmbedPool, batch, *, rows: Optional[Sequence[int]] = None,
+                  round_intermediates: bool = False):
+    """The `forward` call through the whole model (Forward API: the core Transformer forward pass):
+    layer l reads and appends to its own KvPage pool `kvs[l]` with the same page table, its input is
+    the output of layer l-1 (kept wide: only Embeds, KvPages and weights are bf16 storage), the
+    first layer reads the input Embeds and the last one writes the output Embeds.  `rows` restricts
+    the last layer's per-token outputs; every earlier layer is computed for all tokens.
+    Returns the list of per-layer results."""
+    assert len(layers) == len(kvs) and len(layers) >= 1
+    results = []
+    x = None
+    for l, (w, kv) in enumerate(zip(layers, kvs)):
+        last = l == len(layers) - 1
+        res = forward(model, w, kv, emb, batch, rows=rows if last else None,
+                      round_intermediates=round_intermediates, write_embeds=last, x_in=x)
+        results.append(res)
+        x = res.y
+    return results
 
 
 # --------------------------------------------------------------------------------------------

@@ -45,3 +45,15 @@ def check_topk(ids_gpu, probs_gpu, z_oracle, ids_oracle, probs_oracle, logit_tie
         ref = p_full[ids_gpu[r].astype(np.int64)]
         np.testing.assert_allclose(probs_gpu[r], ref, rtol=rel, atol=1e-9)
         assert len(set(ids_gpu[r].tolist())) == k, "duplicate ids in top-k"
+
+
+def deep_oracle_pools(dw):
+    """Per-layer oracle KvPools holding each layer's prior KV, and an empty EmbedPool (inputs come from embed_txt)."""
+    m = dw.base.model
+    kvs = []
+    for pr in dw.priors:
+        kv = O.KvPool(dw.base.n_kv_pages, m.page_size, m.n_kv_heads, m.head_dim)
+        if len(pr.page_ids):
+            kv.write(pr.page_ids, pr.slots, pr.k_bits, pr.v_bits)
+        kvs.append(kv)
+    return kvs, O.EmbedPool(dw.base.n_embeds, m.hidden)

@@ -91,6 +91,15 @@ class RequestSpec:
 
 
 @dataclass
+class DeepWorkload:  # the same batch through every layer of a model, inputs produced by embed_txt
+    base: "Workload"                  # batch, head, layer-0 weights and prior KV; embed_bits == table[token_ids]
+    layers: List[LayerWeights]        # one per layer (layers[0] is base.weights)
+    priors: List[PriorKV]             # per-layer prior KV: same (page, slot) list, values of their own
+    table_bits: np.ndarray            # uint16 [vocab, H] embedding table
+    token_ids: np.ndarray             # int32 [T] input tokens
+
+
+@dataclass
 class Workload:
     name: str
     model: ModelDesc
@@ -112,6 +121,8 @@ class Workload:
 # ------------------------------------------------------------------------------------------
 
 STREAM_WEIGHTS, STREAM_EMBEDS, STREAM_KV, STREAM_PAGES, STREAM_CTX, STREAM_MASK, STREAM_HEAD = 1, 2, 3, 4, 5, 6, 7
+STREAM_TABLE, STREAM_TOKENS = 8, 9
+LAYER_STREAM_STEP = 100  # layer l > 0 draws its weights / prior KV from stream + l * LAYER_STREAM_STEP
 
 
 def rng_for(seed: int, stream: int) -> np.random.Generator:
@@ -149,10 +160,10 @@ def pack_mask_rows(allowed: np.ndarray) -> np.ndarray:
 
 
 def make_layer_weights(model: ModelDesc, seed: int, std: float = 0.02, resid_std: Optional[float] = None,
-                       gain_std: float = 0.02) -> LayerWeights:
+                       gain_std: float = 0.02, layer: int = 0) -> LayerWeights:
     """Linear weights ~N(0, std); the two residual-writing projections ~N(0, resid_std);
     norm gains 1 + N(0, gain_std)."""
-    rng = rng_for(seed, STREAM_WEIGHTS)
+    rng = rng_for(seed, STREAM_WEIGHTS + layer * LAYER_STREAM_STEP)
     H, Hq, Hkv, D, I = model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.mlp_dim
     rs = std if resid_std is None else resid_std
     return LayerWeights(
@@ -284,6 +295,28 @@ def build_workload(name: str, model: ModelDesc, requests: List[RequestSpec], n_k
                     notes={"pages_used": cursor, "requests": R, "tokens": T})
 
 
+def build_deep_workload(name: str, model: ModelDesc, requests: List[RequestSpec], n_kv_pages: int, seed: int,
+                        std: float = 0.02, resid_std: Optional[float] = None, top_k: int = 0,
+                        n_embeds: Optional[int] = None) -> DeepWorkload:
+    """`build_workload` for all `model.n_layers` layers: per-layer weights and prior KV values, an embedding
+    table ~N(0,1) and random input tokens whose table rows are the input Embeds."""
+    base = build_workload(name, model, requests, n_kv_pages, seed, std=std, resid_std=resid_std, top_k=top_k,
+                          n_embeds=n_embeds)
+    T = base.batch.n_tokens
+    table = normal_bf16(rng_for(seed, STREAM_TABLE), (model.vocab, model.hidden), 1.0)
+    tokens = rng_for(seed, STREAM_TOKENS).integers(0, model.vocab, size=T).astype(np.int32)
+    base.embed_bits = table[tokens].copy()
+    layers, priors = [base.weights], [base.prior]
+    n_prior = len(base.prior.page_ids)
+    for l in range(1, model.n_layers):
+        layers.append(make_layer_weights(model, seed, std, resid_std, layer=l))
+        rng_kv = rng_for(seed, STREAM_KV + l * LAYER_STREAM_STEP)
+        priors.append(PriorKV(base.prior.page_ids, base.prior.slots,
+                              normal_bf16(rng_kv, (n_prior, model.n_kv_heads, model.head_dim), 1.0),
+                              normal_bf16(rng_kv, (n_prior, model.n_kv_heads, model.head_dim), 1.0)))
+    return DeepWorkload(base=base, layers=layers, priors=priors, table_bits=table, token_ids=tokens)
+
+
 # ------------------------------------------------------------------------------------------
 # mask recipes (return bool [n_new, L])
 # ------------------------------------------------------------------------------------------
@@ -386,3 +419,13 @@ def c5_sparse_long(seed: int = 5000, n_requests: int = 16, ctx: int = 32768, n_s
     reqs = [RequestSpec(1, ctx, mask=mk, in_place=True) for _ in range(n_requests)]
     return build_workload("c5_sparse_long", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m), with_head=with_head,
                           weights=weights, head=head, top_k=50)
+
+
+def deep_tiny(seed: int = 6000, n_layers: int = 3, bitmap: bool = False) -> DeepWorkload:
+    """The tiny model's mixed batch (4 decode requests + one 32-token prefill) through `n_layers` layers."""
+    m = model_tiny()
+    m.n_layers = n_layers
+    mk = causal_bitmap if bitmap else None
+    reqs = [RequestSpec(1, c, mask=mk, in_place=True) for c in (17, 40, 64, 100)] + [RequestSpec(32, 0, mask=mk)]
+    return build_deep_workload("deep_tiny", m, reqs, n_kv_pages=32, seed=seed, std=0.02, resid_std=_resid_std(m),
+                               top_k=8, n_embeds=96)
