@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--top-k", type=int, default=256)
+    ap.add_argument("--layers", type=int, default=1,
+                    help="run the batch through this many layers (pie_forward_all; every layer gets the same "
+                         "synthetic weights and prior KV values); the default 1 is the per-layer metric")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -69,12 +72,14 @@ def main():
     dist_ids = b.out_embed_ids[w.dist_rows]
     n_dist = len(dist_ids)
 
+    NL = max(1, args.layers)
     ctx = Pie(w.model, w.n_kv_pages, w.n_embeds, max_batch_tokens=T, max_batch_requests=b.n_requests,
-              max_top_k=max(256, w.top_k), max_dist_rows=max(n_dist, 1))
-    ctx.load_layer(0, w.weights)
+              max_top_k=max(256, w.top_k), max_dist_rows=max(n_dist, 1), n_layers=NL)
     ctx.load_head(w.head)
     ctx.embed_write(b.in_embed_ids, w.embed_bits)
-    ctx.kv_write(0, w.prior.page_ids, w.prior.slots, w.prior.k_bits, w.prior.v_bits)
+    for l in range(NL):
+        ctx.load_layer(l, w.weights)
+        ctx.kv_write(l, w.prior.page_ids, w.prior.slots, w.prior.k_bits, w.prior.v_bits)
     pb = ctx.batch_create(b, validate=True)
     work = pb.work()
     out_ids = torch.empty((n_dist, w.top_k), dtype=torch.int32, device=ctx.device)
@@ -83,8 +88,14 @@ def main():
     print(f"# setup {time.time() - t_setup:.1f}s: {desc}; T={T} R={b.n_requests} "
           f"kv tokens={int(b.kv_len.sum())} visited pages={work['visited_pages']}", file=sys.stderr, flush=True)
 
+    def fwd():
+        if NL == 1:
+            ctx.forward(0, pb)
+        else:
+            ctx.forward_all(pb)
+
     def step():
-        ctx.forward(0, pb)
+        fwd()
         ctx.get_next_dist_async(dist_ids, w.top_k, w.temperature, out_ids, out_probs)
 
     for _ in range(args.warmup):
@@ -108,7 +119,7 @@ def main():
     ctx.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.forward(0, pb)
+        fwd()
     ctx.synchronize()
     fwd_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -117,7 +128,8 @@ def main():
     acc = {}
     n_prof = min(args.steps, 20)
     for _ in range(n_prof):
-        step()
+        ctx.forward(0, pb)  # the stages of one layer (layer 0) also when the step runs several
+        ctx.get_next_dist_async(dist_ids, w.top_k, w.temperature, out_ids, out_probs)
         for k, v in ctx.stage_times().items():
             acc[k] = acc.get(k, 0.0) + v
     ctx.set_stage_timing(False)
@@ -187,9 +199,9 @@ def main():
         O.get_next_dist(w.model, w.head, emb, dist_sample, w.top_k, w.temperature)
         t_dist = time.perf_counter() - tc
         # scale each part to the whole step (the oracle's cost is linear in rows)
-        cpu_s = t_fwd * T / n_rows + t_dist * n_dist / max(len(dist_sample), 1)
-        sample = (f"forward over {n_rows} of {T} tokens ({t_fwd:.1f}s) + get_next_dist on {len(dist_sample)} of {n_dist} rows "
-                  f"({t_dist:.1f}s), scaled to one whole step; float64 NumPy")
+        cpu_s = NL * t_fwd * T / n_rows + t_dist * n_dist / max(len(dist_sample), 1)
+        sample = (f"one layer over {n_rows} of {T} tokens ({t_fwd:.1f}s) + get_next_dist on {len(dist_sample)} of {n_dist} rows "
+                  f"({t_dist:.1f}s), scaled to one whole step of {NL} layer(s); float64 NumPy")
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -204,7 +216,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": desc, "tokens_per_step": T, "requests": int(b.n_requests), "dist_rows": n_dist,
-                   "top_k": int(w.top_k), "step": "pie_forward (1 layer) + pie_get_next_dist"},
+                   "top_k": int(w.top_k), "layers": NL,
+                   "step": ("pie_forward (1 layer)" if NL == 1 else f"pie_forward_all ({NL} layers)") + " + pie_get_next_dist"},
         "forward_only": {"tokens_per_s": round(T / (fwd_ms * 1e-3), 1), "ms": round(fwd_ms, 5)},
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},
         "roofline": roofline, "other_kernels": extra, "cpu_baseline": cpu,

@@ -73,10 +73,24 @@ pie_status pie_load_layer(pie_ctx* ctx, int32_t layer, const void* g1, const voi
 /* g_final may be NULL: get_next_dist then applies no final norm. */
 pie_status pie_load_head(pie_ctx* ctx, const void* g_final, const void* w_lm /* [vocab, hidden] */);
 
+/* Embedding table for `embed_txt`: dev bf16 [vocab, hidden], copied into library storage (the caller may
+ * free its tensor afterwards).  Errors: PIE_EINVAL (null, context without vocab), PIE_ENOMEM, PIE_EHIP. */
+pie_status pie_load_embedding(pie_ctx* ctx, const void* table);
+
+/* `embed_txt(q, tok, pos, embs)` (Table 1, InputText; Embed API): Embed embed_ids[i] receives row
+ * token_ids[i] of the embedding table, unchanged, and the sequence position positions[i], which a later
+ * forward batch with positions == NULL uses for the rotary step (Forward API: the call works on the sequence
+ * positions associated with its resources).  All three arrays are host int32 [n].  Synchronises the stream.
+ * Errors: PIE_EINVAL (null, no table loaded), PIE_ERANGE (token id, embed id, negative position),
+ * PIE_ECONFLICT (one embed id named twice). */
+pie_status pie_embed_txt(pie_ctx* ctx, const int32_t* token_ids, const int32_t* positions, int32_t n,
+                         const int32_t* embed_ids);
+
 /* Resource seeding / inspection.  Stand-ins for what `embed_txt` and earlier `forward` calls
  * leave in the pools (Table 1; Embed API), used by tests and the benchmark.  ids/slots: host
  * int32 [n]; data: dev bf16.  KV rows are token-major [n, n_kv_heads, head_dim]; K is stored as
- * given (already rotated).  The pool layout itself is private to the library. */
+ * given (already rotated).  The pool layout itself is private to the library.  pie_embed_write leaves the
+ * written Embeds without a recorded position. */
 pie_status pie_embed_write(pie_ctx* ctx, const int32_t* embed_ids, int32_t n, const void* src /* dev [n, hidden] */);
 pie_status pie_embed_read(pie_ctx* ctx, const int32_t* embed_ids, int32_t n, void* dst /* dev [n, hidden] */);
 pie_status pie_kv_write(pie_ctx* ctx, int32_t layer, const int32_t* page_ids, const int32_t* slots, int32_t n,
@@ -94,7 +108,9 @@ pie_status pie_kv_read(pie_ctx* ctx, int32_t layer, const int32_t* page_ids, con
  *     j % page_size of that list
  *   kv_len[r]: KV length AFTER this call's append; new token i of r is stored at logical index
  *     kv_len[r] - n_new_r + i, whatever its position
- *   positions[t]: explicit rotary position of token t (Forward API: explicit sequence positions)
+ *   positions[t]: explicit rotary position of token t (Forward API: explicit sequence positions); NULL
+ *     takes, for every token, the position recorded with its input Embed by pie_embed_txt (PIE_EINVAL
+ *     when an input Embed carries none)
  *   out_embed_ids[t]: Embed that receives the layer output of token t, or -1 to drop the row
  *     (fewer output than input Embeds: the example with 9 inputs and 1 output).  An Embed may be
  *     both input and output of one call (autoregressive-loop example).
@@ -113,7 +129,7 @@ typedef struct {
   const int32_t* tok_indptr;    /* [R+1] */
   const int32_t* in_embed_ids;  /* [T] */
   const int32_t* out_embed_ids; /* [T] */
-  const int32_t* positions;     /* [T] */
+  const int32_t* positions;     /* [T] or NULL */
   const int32_t* page_indptr;   /* [R+1] */
   const int32_t* page_ids;      /* [page_indptr[R]] */
   const int32_t* kv_len;        /* [R] */
@@ -134,6 +150,13 @@ pie_status pie_batch_destroy(pie_ctx* ctx, pie_batch* batch);
  * output projection + residual, RMSNorm, SwiGLU MLP + residual, output Embeds.  Enqueues only;
  * allocates nothing.  The batch may be reused across calls and layers. */
 pie_status pie_forward(pie_ctx* ctx, int32_t layer, const pie_batch* batch);
+
+/* The same call through every layer of the model (Forward API: the core Transformer forward pass; the
+ * autoregressive-loop example): layer l appends to and attends over its own KvPage pool with the batch's
+ * page table, its input is the output of layer l-1 (kept in fp32 between layers), layer 0 reads the input
+ * Embeds and the last layer stores the output Embeds as bf16.  Every layer must be loaded.  Enqueues only;
+ * allocates nothing.  Errors: PIE_EINVAL (null, a layer without weights), PIE_EBATCH, PIE_EHIP. */
+pie_status pie_forward_all(pie_ctx* ctx, const pie_batch* batch);
 
 /* Convenience: pie_batch_create + pie_forward + pie_batch_destroy (synchronises the stream). */
 pie_status pie_forward_host(pie_ctx* ctx, int32_t layer, const pie_forward_batch* batch, int32_t validate);

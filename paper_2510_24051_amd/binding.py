@@ -76,6 +76,9 @@ def load_library():
         "pie_batch_create": [vp, C.POINTER(ForwardBatchC), i32, C.POINTER(vp)],
         "pie_batch_destroy": [vp, vp],
         "pie_forward": [vp, i32, vp],
+        "pie_forward_all": [vp, vp],
+        "pie_load_embedding": [vp, vp],
+        "pie_embed_txt": [vp, vp, vp, i32, vp],
         "pie_forward_host": [vp, i32, C.POINTER(ForwardBatchC), i32],
         "pie_get_next_dist": [vp, vp, i32, i32, f32, vp, vp],
         "pie_synchronize": [vp],
@@ -186,7 +189,18 @@ class Pie:
         self._check(self.lib.pie_load_head(self.ctx, None if g is None else C.c_void_p(g.data_ptr()),
                                            C.c_void_p(w.data_ptr())))
 
+    def load_embedding(self, table_bits):
+        t = self._dev_bf16(table_bits)
+        torch.cuda.synchronize(self.device)
+        self._check(self.lib.pie_load_embedding(self.ctx, C.c_void_p(t.data_ptr())))
+
     # ---- resources ----
+    def embed_txt(self, token_ids, positions, embed_ids):
+        tok, pos, ids = _i32(token_ids), _i32(positions), _i32(embed_ids)
+        if not (len(tok) == len(pos) == len(ids)):
+            raise ValueError("embed_txt: token_ids, positions and embed_ids must have one length")
+        self._check(self.lib.pie_embed_txt(self.ctx, _ptr(tok), _ptr(pos), len(tok), _ptr(ids)))
+
     def embed_write(self, embed_ids, bits):
         ids = _i32(embed_ids)
         t = self._dev_bf16(bits)
@@ -225,7 +239,8 @@ class Pie:
     # ---- forward ----
     def _batch_struct(self, b):
         arrs = dict(tok_indptr=_i32(b.tok_indptr), in_embed_ids=_i32(b.in_embed_ids),
-                    out_embed_ids=_i32(b.out_embed_ids), positions=_i32(b.positions),
+                    out_embed_ids=_i32(b.out_embed_ids),
+                    positions=None if b.positions is None else _i32(b.positions),
                     page_indptr=_i32(b.page_indptr), page_ids=_i32(b.page_ids), kv_len=_i32(b.kv_len))
         mi = None if b.mask_indptr is None else np.ascontiguousarray(b.mask_indptr, dtype=np.int64)
         mw = None if b.mask_words is None else np.ascontiguousarray(b.mask_words, dtype=np.uint32)
@@ -242,6 +257,9 @@ class Pie:
 
     def forward(self, layer: int, batch: PieBatch):
         self._check(self.lib.pie_forward(self.ctx, layer, batch.handle))
+
+    def forward_all(self, batch: PieBatch):
+        self._check(self.lib.pie_forward_all(self.ctx, batch.handle))
 
     def forward_host(self, layer: int, batch, validate: bool = True):
         fb, keep = self._batch_struct(batch)

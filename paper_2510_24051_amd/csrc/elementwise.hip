@@ -189,6 +189,25 @@ __global__ void embed_copy_kernel(bf16_t* __restrict__ embeds, const int32_t* __
   else *reinterpret_cast<u32x4*>(b) = *reinterpret_cast<const u32x4*>(p);
 }
 
+// embed_txt: Embed ids[r] receives row tok[r] of the embedding table, 16 bytes per thread.
+__global__ void embed_gather_kernel(bf16_t* __restrict__ embeds, const int32_t* __restrict__ ids,
+                                    const int32_t* __restrict__ tok, int n, int H, const bf16_t* __restrict__ table) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int per_row = H / 8;
+  if (idx >= (int64_t)n * per_row) return;
+  int r = (int)(idx / per_row), c = (int)(idx % per_row) * 8;
+  *reinterpret_cast<u32x4*>(embeds + (int64_t)ids[r] * H + c) =
+      *reinterpret_cast<const u32x4*>(table + (int64_t)tok[r] * H + c);
+}
+
+hipError_t launch_embed_gather(bf16_t* embeds, const int32_t* ids, const int32_t* tok, int n, int H,
+                               const bf16_t* table, hipStream_t s) {
+  int64_t total = (int64_t)n * (H / 8);
+  if (total <= 0) return hipSuccess;
+  embed_gather_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(embeds, ids, tok, n, H, table);
+  return hipGetLastError();
+}
+
 hipError_t launch_embed_copy(bf16_t* embeds, const int32_t* ids, int n, int H, bf16_t* buf, int to_pool,
                              hipStream_t s) {
   int64_t total = (int64_t)n * (H / 8);

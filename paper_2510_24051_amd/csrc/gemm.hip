@@ -44,26 +44,40 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
     for (int v = 0; v < 16; ++v)
       if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + nc] = f32_to_bf16(silu_f(acc[v]) * acc2[v]);
   } else if (MODE == EPI_RESID_EMBED) {
-    int id[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) id[v] = rows[v] < M ? e.ids[rows[v]] : 0;
     float r[16];
+    if (e.resid != nullptr) {  // wide residual stream of an inner layer
 #pragma unroll
-    for (int v = 0; v < 16; ++v) r[v] = bf16_to_f32(e.embeds[(int64_t)id[v] * e.H + n]);
+      for (int v = 0; v < 16; ++v) r[v] = rows[v] < M ? e.resid[(int64_t)rows[v] * e.H + n] : 0.f;
+    } else {
+      int id[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) id[v] = rows[v] < M ? e.ids[rows[v]] : 0;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) r[v] = bf16_to_f32(e.embeds[(int64_t)id[v] * e.H + n]);
+    }
     float* out = reinterpret_cast<float*>(e.out);
 #pragma unroll
     for (int v = 0; v < 16; ++v)
       if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = r[v] + acc[v];
   } else if (MODE == EPI_RESID_OUT) {
-    int id[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) id[v] = rows[v] < M ? e.ids[rows[v]] : -1;
     float r[16];
+    if (e.out != nullptr) {  // inner layer: the sum stays wide and feeds the next layer
 #pragma unroll
-    for (int v = 0; v < 16; ++v) r[v] = id[v] >= 0 ? e.resid[(int64_t)rows[v] * e.H + n] : 0.f;
+      for (int v = 0; v < 16; ++v) r[v] = rows[v] < M ? e.resid[(int64_t)rows[v] * e.H + n] : 0.f;
+      float* out = reinterpret_cast<float*>(e.out);
 #pragma unroll
-    for (int v = 0; v < 16; ++v)
-      if (id[v] >= 0) e.embeds[(int64_t)id[v] * e.H + n] = f32_to_bf16(r[v] + acc[v]);
+      for (int v = 0; v < 16; ++v)
+        if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = r[v] + acc[v];
+    } else {
+      int id[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) id[v] = rows[v] < M ? e.ids[rows[v]] : -1;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) r[v] = id[v] >= 0 ? e.resid[(int64_t)rows[v] * e.H + n] : 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (id[v] >= 0) e.embeds[(int64_t)id[v] * e.H + n] = f32_to_bf16(r[v] + acc[v]);
+    }
   }
 }
 
@@ -215,11 +229,17 @@ __global__ void splitk_epilogue_kernel(const float* __restrict__ part, int split
     float x = total(c);
     if (MODE == EPI_STORE_BF16) reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + c] = f32_to_bf16(x);
     else if (MODE == EPI_STORE_F32) reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = x;
-    else if (MODE == EPI_RESID_EMBED)
-      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = bf16_to_f32(e.embeds[(int64_t)e.ids[m] * e.H + c]) + x;
-    else if (MODE == EPI_RESID_OUT) {
-      int id = e.ids[m];
-      if (id >= 0) e.embeds[(int64_t)id * e.H + c] = f32_to_bf16(e.resid[(int64_t)m * e.H + c] + x);
+    else if (MODE == EPI_RESID_EMBED) {
+      const float r = e.resid != nullptr ? e.resid[(int64_t)m * e.H + c]
+                                         : bf16_to_f32(e.embeds[(int64_t)e.ids[m] * e.H + c]);
+      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = r + x;
+    } else if (MODE == EPI_RESID_OUT) {
+      if (e.out != nullptr) {
+        reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = e.resid[(int64_t)m * e.H + c] + x;
+      } else {
+        int id = e.ids[m];
+        if (id >= 0) e.embeds[(int64_t)id * e.H + c] = f32_to_bf16(e.resid[(int64_t)m * e.H + c] + x);
+      }
     }
   }
 }
@@ -512,9 +532,10 @@ static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight
 template <int MODE>
 static EpiArgs offset_rows(EpiArgs e, int m0) {
   if (MODE == EPI_STORE_BF16 || MODE == EPI_SWIGLU) e.out = reinterpret_cast<bf16_t*>(e.out) + (int64_t)m0 * e.ldo;
-  if (MODE == EPI_STORE_F32 || MODE == EPI_RESID_EMBED) e.out = reinterpret_cast<float*>(e.out) + (int64_t)m0 * e.ldo;
-  if (MODE == EPI_RESID_EMBED || MODE == EPI_RESID_OUT) e.ids += m0;
-  if (MODE == EPI_RESID_OUT) e.resid += (int64_t)m0 * e.H;
+  if (MODE == EPI_STORE_F32 || MODE == EPI_RESID_EMBED || (MODE == EPI_RESID_OUT && e.out != nullptr))
+    e.out = reinterpret_cast<float*>(e.out) + (int64_t)m0 * e.ldo;
+  if ((MODE == EPI_RESID_EMBED || MODE == EPI_RESID_OUT) && e.ids != nullptr) e.ids += m0;
+  if ((MODE == EPI_RESID_EMBED || MODE == EPI_RESID_OUT) && e.resid != nullptr) e.resid += (int64_t)m0 * e.H;
   return e;
 }
 

@@ -96,6 +96,9 @@ struct pie_ctx {
   bf16_t* g_final = nullptr;
   PackedWeight wlm;
   double* inv_freq = nullptr;
+  bf16_t* table = nullptr;             // embedding table [vocab, H] (embed_txt)
+  std::vector<int32_t> embed_pos;      // host: sequence position recorded with each Embed by embed_txt, -1 = none
+  float* x32 = nullptr;                // [T, H] wide layer input of the layers after the first (n_layers > 1)
   // workspace
   bf16_t *xn = nullptr, *qkv = nullptr, *attn = nullptr, *act = nullptr, *en = nullptr;
   float *h = nullptr, *splitk = nullptr, *logits = nullptr, *topk_stats = nullptr;
@@ -122,14 +125,17 @@ hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const 
                               const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, hipStream_t s);
 hipError_t launch_embed_copy(bf16_t* embeds, const int32_t* ids, int n, int H, bf16_t* buf, int to_pool,
                              hipStream_t s);
+hipError_t launch_embed_gather(bf16_t* embeds, const int32_t* ids, const int32_t* tok, int n, int H,
+                               const bf16_t* table, hipStream_t s);
 hipError_t launch_kv_copy(bf16_t* kv_layer, const int32_t* pages, const int32_t* slots, int n, int Hkv, int D,
                           bf16_t* k, bf16_t* v, int to_pool, hipStream_t s);
 
 enum EpiMode {
   EPI_STORE_BF16 = 0,    // out bf16 [M, N]
-  EPI_RESID_EMBED = 1,   // out fp32 [M, N] = embeds[in_ids[m]][n] + acc
+  EPI_RESID_EMBED = 1,   // out fp32 [M, N] = embeds[in_ids[m]][n] + acc, or resid[m][n] + acc when resid is given
   EPI_SWIGLU = 2,        // out bf16 [M, N/2] = silu(gate) * up, gate/up interleaved in 32-column blocks
-  EPI_RESID_OUT = 3,     // embeds[out_ids[m]][n] = bf16(resid[m][n] + acc) when out_ids[m] >= 0
+  EPI_RESID_OUT = 3,     // embeds[out_ids[m]][n] = bf16(resid[m][n] + acc) when out_ids[m] >= 0, or, when out is
+                         // given, out fp32 [M, N] = resid[m][n] + acc for every row
   EPI_STORE_F32 = 4      // out fp32 [M, N]
 };
 struct EpiArgs {

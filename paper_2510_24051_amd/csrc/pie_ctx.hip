@@ -87,6 +87,8 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   chk(dev_alloc(&c->qkv, T * (QD + 2 * KD), false, c->stream));
   chk(dev_alloc(&c->attn, T * QD, false, c->stream));
   chk(dev_alloc(&c->h, T * H, false, c->stream));
+  if (m->n_layers > 1) chk(dev_alloc(&c->x32, T * H, false, c->stream));
+  c->embed_pos.assign((size_t)p->n_embeds, -1);
   chk(dev_alloc(&c->act, T * I, false, c->stream));
   // split-K workspace: only batches of <= 256 rows use it; 8 partial copies of the widest output
   {
@@ -135,7 +137,7 @@ extern "C" pie_status pie_destroy(pie_ctx* c) {
   }
   free_packed(c->wlm);
   void* bufs[] = {c->embeds, c->kv, c->xn, c->qkv, c->attn, c->h, c->act, c->splitk, c->logits, c->en,
-                  c->ids_dev, c->inv_freq, c->g_final, c->topk_cand, c->topk_stats};
+                  c->ids_dev, c->inv_freq, c->g_final, c->topk_cand, c->topk_stats, c->table, c->x32};
   for (void* b : bufs) if (b) (void)hipFree(b);
   for (int i = 0; i < 2 * PIE_N_STAGES; ++i) if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
   delete c;
@@ -202,6 +204,20 @@ extern "C" pie_status pie_load_head(pie_ctx* c, const void* g_final, const void*
   return PIE_OK;
 }
 
+extern "C" pie_status pie_load_embedding(pie_ctx* c, const void* table) {
+  if (!c) return PIE_EINVAL;
+  if (!table) return fail(c, PIE_EINVAL, "pie_load_embedding: null table");
+  if (c->m.vocab <= 0) return fail(c, PIE_EINVAL, "pie_load_embedding: context created without vocab");
+  const size_t bytes = (size_t)c->m.vocab * c->m.hidden * sizeof(bf16_t);
+  if (!c->table) {
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->table), bytes);
+    if (e != hipSuccess) return fail(c, e == hipErrorOutOfMemory ? PIE_ENOMEM : PIE_EHIP, "pie_load_embedding: %s", hipGetErrorString(e));
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->table, table, bytes, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PIE_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // resource seeding / inspection
 // ---------------------------------------------------------------------------------------------
@@ -231,7 +247,35 @@ static pie_status embed_copy(pie_ctx* c, const int32_t* ids, int32_t n, void* bu
   return PIE_OK;
 }
 extern "C" pie_status pie_embed_write(pie_ctx* c, const int32_t* ids, int32_t n, const void* src) {
-  return embed_copy(c, ids, n, const_cast<void*>(src), 1);
+  pie_status st = embed_copy(c, ids, n, const_cast<void*>(src), 1);
+  if (st == PIE_OK)
+    for (int i = 0; i < n; ++i) c->embed_pos[ids[i]] = -1;  // raw contents carry no sequence position
+  return st;
+}
+
+extern "C" pie_status pie_embed_txt(pie_ctx* c, const int32_t* token_ids, const int32_t* positions, int32_t n,
+                                    const int32_t* embed_ids) {
+  if (!c) return PIE_EINVAL;
+  if (n < 0 || (n > 0 && (!token_ids || !positions || !embed_ids))) return fail(c, PIE_EINVAL, "pie_embed_txt: null argument");
+  if (!c->table) return fail(c, PIE_EINVAL, "pie_embed_txt: no embedding table loaded");
+  if (n == 0) return PIE_OK;
+  std::unordered_set<int32_t> seen;
+  seen.reserve((size_t)n * 2);
+  for (int i = 0; i < n; ++i) {
+    if (token_ids[i] < 0 || token_ids[i] >= c->m.vocab)
+      return fail(c, PIE_ERANGE, "token id %d at %d outside [0, %d)", token_ids[i], i, c->m.vocab);
+    if (embed_ids[i] < 0 || embed_ids[i] >= c->p.n_embeds)
+      return fail(c, PIE_ERANGE, "embed id %d at %d outside [0, %d)", embed_ids[i], i, c->p.n_embeds);
+    if (positions[i] < 0) return fail(c, PIE_ERANGE, "negative position %d at %d", positions[i], i);
+    if (!seen.insert(embed_ids[i]).second)
+      return fail(c, PIE_ECONFLICT, "embed id %d is written twice by one embed_txt call", embed_ids[i]);
+  }
+  pie_status st = stage_ids(c, embed_ids, token_ids, n);
+  if (st != PIE_OK) return st;
+  HIP_TRY(c, launch_embed_gather(c->embeds, c->ids_dev, c->ids_dev + n, n, c->m.hidden, c->table, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));  // ids_dev is reused by the next call
+  for (int i = 0; i < n; ++i) c->embed_pos[embed_ids[i]] = positions[i];
+  return PIE_OK;
 }
 extern "C" pie_status pie_embed_read(pie_ctx* c, const int32_t* ids, int32_t n, void* dst) {
   return embed_copy(c, ids, n, dst, 0);
@@ -287,8 +331,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   if (R > c->p.max_batch_requests || T > c->p.max_batch_tokens)
     return fail(c, PIE_EBATCH, "batch of %d requests / %d tokens exceeds the context's %d / %d", R, T,
                 c->p.max_batch_requests, c->p.max_batch_tokens);
-  if (!b->tok_indptr || !b->in_embed_ids || !b->out_embed_ids || !b->positions || !b->page_indptr || !b->page_ids ||
-      !b->kv_len)
+  if (!b->tok_indptr || !b->in_embed_ids || !b->out_embed_ids || !b->page_indptr || !b->page_ids || !b->kv_len)
     return fail(c, PIE_EINVAL, "pie_batch_create: null array");
   if (b->mask_indptr && !b->mask_words && b->mask_indptr[R] > 0) return fail(c, PIE_EINVAL, "mask_indptr without mask_words");
   const int G = c->m.n_q_heads / c->m.n_kv_heads, Hkv = c->m.n_kv_heads, D = c->m.head_dim;
@@ -297,6 +340,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
 
   std::vector<ReqInfo> reqs(R);
   std::vector<int32_t> tok_page(T), tok_slot(T), visit_phys, visit_logical, dec_reqs;
+  std::vector<int32_t> pos_from_embeds;  // positions recorded by embed_txt, when the batch names none
+  if (!b->positions) pos_from_embeds.resize(T);
   std::vector<PrefillItem> pitems;
   int rows_cap = 0;
   int64_t kv_bytes = 0, kv_bytes_dec = 0, flops = 0;
@@ -322,7 +367,13 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
         return fail(c, PIE_ERANGE, "token %d: input embed id %d outside [0, %d)", t, b->in_embed_ids[t], c->p.n_embeds);
       if (b->out_embed_ids[t] < -1 || b->out_embed_ids[t] >= c->p.n_embeds)
         return fail(c, PIE_ERANGE, "token %d: output embed id %d outside [-1, %d)", t, b->out_embed_ids[t], c->p.n_embeds);
-      if (b->positions[t] < 0) return fail(c, PIE_ERANGE, "token %d: negative position", t);
+      if (b->positions) {
+        if (b->positions[t] < 0) return fail(c, PIE_ERANGE, "token %d: negative position", t);
+      } else {
+        pos_from_embeds[t] = c->embed_pos[b->in_embed_ids[t]];
+        if (pos_from_embeds[t] < 0)
+          return fail(c, PIE_EINVAL, "token %d: the batch names no positions and input embed %d carries none", t, b->in_embed_ids[t]);
+      }
       tok_page[t] = b->page_ids[p0 + j / PAGE];
       tok_slot[t] = j % PAGE;
     }
@@ -461,7 +512,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   pb->work[0] = kv_bytes; pb->work[1] = kv_bytes_dec; pb->work[2] = flops; pb->work[3] = (int64_t)visit_phys.size();
   Blob blob;
   const size_t o_in = blob.add(b->in_embed_ids, (size_t)T * 4), o_out = blob.add(b->out_embed_ids, (size_t)T * 4);
-  const size_t o_pos = blob.add(b->positions, (size_t)T * 4), o_tp = blob.add(tok_page.data(), (size_t)T * 4);
+  const size_t o_pos = blob.add(b->positions ? b->positions : pos_from_embeds.data(), (size_t)T * 4), o_tp = blob.add(tok_page.data(), (size_t)T * 4);
   const size_t o_ts = blob.add(tok_slot.data(), (size_t)T * 4);
   const size_t o_vp = blob.add(visit_phys.data(), visit_phys.size() * 4, 8);
   const size_t o_vl = blob.add(visit_logical.data(), visit_logical.size() * 4, 8);
@@ -531,23 +582,25 @@ struct StageTimer {
 };
 }  // namespace
 
-extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b) {
-  if (!c) return PIE_EINVAL;
-  if (!b) return fail(c, PIE_EINVAL, "pie_forward: null batch");
-  if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "pie_forward: layer %d of %d", layer, c->m.n_layers);
+// One decoder layer.  x_in: wide [T, H] layer input, or null to read the batch's input Embeds; y_out: wide
+// [T, H] destination of the layer output, or null to store it as bf16 into the batch's output Embeds.
+static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const float* x_in, float* y_out,
+                            bool timed) {
   const LayerWeights& L = c->layers[layer];
-  if (!L.loaded) return fail(c, PIE_EINVAL, "pie_forward: layer %d has no weights", layer);
-  if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "batch larger than the context");
   const pie_model_desc& m = c->m;
   const int T = b->T, H = m.hidden, Hq = m.n_q_heads, Hkv = m.n_kv_heads, D = m.head_dim, I = m.mlp_dim;
   const int QKV = (Hq + 2 * Hkv) * D;
   hipStream_t s = c->stream;
   bf16_t* kv_layer = c->kv + (size_t)layer * c->kv_layer_elems;
+  const bool was_timing = c->timing;
+  if (!timed) c->timing = false;
   StageTimer tm(c, PIE_STAGE_NORM1, PIE_STAGE_DOWN);
+  struct Restore { pie_ctx* c; bool v; ~Restore() { c->timing = v; } } restore{c, was_timing};
   EpiArgs e{};
 
   tm.begin(PIE_STAGE_NORM1);
-  HIP_TRY(c, launch_rmsnorm_embed(c->embeds, b->in_ids, L.g1, c->xn, T, H, m.rms_eps, s));
+  if (x_in) HIP_TRY(c, launch_rmsnorm_f32(x_in, L.g1, c->xn, T, H, m.rms_eps, s));
+  else HIP_TRY(c, launch_rmsnorm_embed(c->embeds, b->in_ids, L.g1, c->xn, T, H, m.rms_eps, s));
   tm.end(PIE_STAGE_NORM1);
 
   tm.begin(PIE_STAGE_QKV);
@@ -578,7 +631,7 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
   }
 
   tm.begin(PIE_STAGE_OPROJ);
-  e = EpiArgs{EPI_RESID_EMBED, c->h, H, c->embeds, b->in_ids, nullptr, H};
+  e = EpiArgs{EPI_RESID_EMBED, c->h, H, c->embeds, b->in_ids, x_in, H};
   HIP_TRY(c, launch_gemm(c->attn, Hq * D, T, L.wo, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_OPROJ);
 
@@ -592,10 +645,34 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
   tm.end(PIE_STAGE_GATEUP);
 
   tm.begin(PIE_STAGE_DOWN);
-  e = EpiArgs{EPI_RESID_OUT, nullptr, 0, c->embeds, b->out_ids, c->h, H};
+  e = EpiArgs{EPI_RESID_OUT, y_out, y_out ? H : 0, c->embeds, b->out_ids, c->h, H};
   HIP_TRY(c, launch_gemm(c->act, I, T, L.wdown, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_DOWN);
   c->last_T = T;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b) {
+  if (!c) return PIE_EINVAL;
+  if (!b) return fail(c, PIE_EINVAL, "pie_forward: null batch");
+  if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "pie_forward: layer %d of %d", layer, c->m.n_layers);
+  if (!c->layers[layer].loaded) return fail(c, PIE_EINVAL, "pie_forward: layer %d has no weights", layer);
+  if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "batch larger than the context");
+  return run_layer(c, layer, b, nullptr, nullptr, true);
+}
+
+extern "C" pie_status pie_forward_all(pie_ctx* c, const pie_batch* b) {
+  if (!c) return PIE_EINVAL;
+  if (!b) return fail(c, PIE_EINVAL, "pie_forward_all: null batch");
+  const int NL = c->m.n_layers;
+  for (int l = 0; l < NL; ++l)
+    if (!c->layers[l].loaded) return fail(c, PIE_EINVAL, "pie_forward_all: layer %d has no weights", l);
+  if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "batch larger than the context");
+  for (int l = 0; l < NL; ++l) {
+    // the layer output stays wide between layers; only the last layer stores bf16 Embeds
+    pie_status st = run_layer(c, l, b, l == 0 ? nullptr : c->x32, l == NL - 1 ? nullptr : c->x32, NL == 1);
+    if (st != PIE_OK) return st;
+  }
   return PIE_OK;
 }
 
