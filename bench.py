@@ -137,13 +137,26 @@ def main():
 
     m = w.model
     kv_token_bytes = 2 * m.n_kv_heads * m.head_dim * 2
-    dec_tokens = sum(int(b.kv_len[r]) for r in range(b.n_requests) if (b.tok_indptr[r + 1] - b.tok_indptr[r]) * (m.n_q_heads // m.n_kv_heads) <= 16)
-    attn_bytes = work["kv_bytes_decode"] if b.mask_indptr is not None else dec_tokens * kv_token_bytes
+    # algorithmic HBM bytes of decode attention: every distinct visited page once (requests that share pages
+    # do not multiply them); `logical` counts a page once per request that sees it, `requested` is what the
+    # kernel asks the memory system for after grouping such requests
+    shared = work["kv_bytes_unique"] != work["kv_bytes_decode"]
+    if shared or b.mask_indptr is not None:
+        attn_bytes = work["kv_bytes_unique"]  # pages with at least one visible key, each once
+    else:  # inferred causal, nothing shared: every KV token of every decode-path request once
+        G = m.n_q_heads // m.n_kv_heads
+        attn_bytes = kv_token_bytes * sum(int(b.kv_len[r]) for r in range(b.n_requests)
+                                          if (b.tok_indptr[r + 1] - b.tok_indptr[r]) * G <= 16)
     attn_ms = stages.get("attn_decode", 0.0)
     achieved = attn_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
     roofline = {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": PMC_TRAFFIC_BYTES.get(args.workload),
                 "algorithmic_bytes": attn_bytes, "avg_ms": round(attn_ms, 5)}
+    if shared and attn_ms > 0:
+        roofline["shared_pages"] = {
+            "logical_bytes": work["kv_bytes_decode"], "requested_bytes": work["kv_bytes_requested"],
+            "requested_GBs": round(work["kv_bytes_requested"] / (attn_ms * 1e-3) / 1e9, 1),
+            "note": "requests alias prefix pages: the kernel is bound by cache reads of the requested bytes, not by HBM"}
 
     weight_elems = (m.hidden * (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim + m.n_q_heads * m.head_dim * m.hidden
                     + 3 * m.hidden * m.mlp_dim)

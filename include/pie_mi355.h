@@ -194,9 +194,11 @@ pie_status pie_set_stage_timing(pie_ctx* ctx, int32_t enabled);
 pie_status pie_stage_times(pie_ctx* ctx, float* ms_out);
 
 /* Algorithmic work of a batch for roofline accounting: out[0] = KV bytes the attention stage has
- * to read (visible pages x page bytes, K and V, all kv heads), out[1] = decode-path share of
- * out[0], out[2] = attention flops (QK^T and PV over visible pages), out[3] = number of visited
- * (request, page) pairs.  Host int64[4]. */
+ * to read (visible pages x page bytes, K and V, all kv heads, counted per request), out[1] = decode-path
+ * share of out[0], out[2] = attention flops (QK^T and PV over visible pages), out[3] = number of visited
+ * (request, page) pairs, out[4] = page bytes of the distinct physical pages visited by the decode-path requests
+ * (what HBM has to deliver to them when pages are shared), out[5] = KV bytes the decode kernel asks for after requests
+ * that share pages have been grouped (<= out[1]).  Host int64[6]. */
 pie_status pie_batch_work(const pie_batch* batch, int64_t* out);
 
 #ifdef __cplusplus

@@ -110,10 +110,10 @@ class PieBatch:
         self.owner, self.handle, self._keep = owner, handle, keepalive
 
     def work(self) -> dict:
-        out = np.zeros(4, dtype=np.int64)
+        out = np.zeros(6, dtype=np.int64)
         self.owner._check(self.owner.lib.pie_batch_work(self.handle, _ptr(out)))
         return {"kv_bytes": int(out[0]), "kv_bytes_decode": int(out[1]), "attn_flops": int(out[2]),
-                "visited_pages": int(out[3])}
+                "visited_pages": int(out[3]), "kv_bytes_unique": int(out[4]), "kv_bytes_requested": int(out[5])}
 
     def destroy(self):
         if self.handle is not None:

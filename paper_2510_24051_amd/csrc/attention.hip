@@ -208,9 +208,9 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 }
 
 // Visible-key bits of the 4 keys j0 .. j0+3 of a page (j0 = logical index of the first), from a preloaded
-// mask word (bitmap requests) or from the causal rule.
-__device__ __forceinline__ uint32_t key_bits4(int kv_len, int n_new, bool has_bitmap, uint32_t word, int i_tok, int pl,
-                                              int quad, bool row_valid) {
+// mask word (bitmap requests) or from the causal rule (keys up to logical index `lim`).
+__device__ __forceinline__ uint32_t key_bits4(int kv_len, int lim, bool has_bitmap, uint32_t word, int pl, int quad,
+                                              bool row_valid) {
   if (!row_valid) return 0u;
   const int j0 = pl * PAGE + quad * 4;
   int cnt = kv_len - j0;
@@ -219,17 +219,20 @@ __device__ __forceinline__ uint32_t key_bits4(int kv_len, int n_new, bool has_bi
   if (has_bitmap) {
     bits &= (word >> ((pl & 1) * 16 + quad * 4)) & 0xFu;
   } else {
-    int lim = kv_len - n_new + i_tok - j0 + 1;
-    lim = lim < 0 ? 0 : (lim > 4 ? 4 : lim);
-    bits &= (1u << lim) - 1u;
+    int c = lim - j0 + 1;
+    c = c < 0 ? 0 : (c > 4 ? 4 : c);
+    bits &= (1u << c) - 1u;
   }
   return bits;
 }
 
 // Decode attention (requests with n_new * group <= 16 query rows), HBM-bound.
-// Grid: one wave per equal share of the flattened (request, kv head, page pair) list.  A share may cover the
-// end of one (request, head) and the start of the next; each such run is a segment, and the wave writes one
-// unnormalised partial (running max, sum, O) per segment.
+// Grid: one wave per equal share of the flattened (column group, kv head, page pair) list.  A column group is
+// up to 16 query columns that walk the same pages: the rows of one request, or of several requests that share
+// physical pages at the same logical index (each K/V block is then read once for all of them); every column
+// carries its own length, causal limit and mask row.  A share may cover the end of one (group, head) and the
+// start of the next; each such run is a segment, and the wave writes one unnormalised partial (running max,
+// sum, O) per segment and column.
 // Per page pair and kv head, on 16x16x32 MFMAs (16 query columns, so accumulators are half the size of the
 // 32-wide prefill tile and two waves per SIMD fit with K and V double-buffered in registers):
 //     S^T[16 keys, 16 q]  = K_page[16, D] Q^T[D, 16]          per page, D/32 MFMAs; a K operand is one
@@ -245,7 +248,8 @@ __device__ __forceinline__ uint32_t key_bits4(int kv_len, int n_new, bool has_bi
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const DecodeWave* __restrict__ waves,
                                                              const int2* __restrict__ wave_pg, int slots,
-                                                             const DecodeSeg* __restrict__ segs, int n_waves,
+                                                             const DecodeSeg* __restrict__ segs,
+                                                             const DecodeCol* __restrict__ cols, int n_waves,
                                                              int rows_cap, float* __restrict__ part_o,
                                                              float* __restrict__ part_ml) {
   constexpr int KS = D / 32;  // K operands per page
@@ -268,10 +272,9 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
   int cur_sg = __builtin_amdgcn_readfirstlane(wv.seg0) - 1;
   int seg_end = 0;  // wave-local index of the first pair after the current segment
 
-  // per-segment state
-  int s_kv_len = 0, s_n_new = 1;
+  // per-segment state (the column's own values: lane l works for column l % 16)
+  int c_kv_len = 0, c_lim = 0;
   bool valid = false, has_bitmap = false;
-  int i_tok = 0;
   const uint32_t* mrow = a.mask_words;
   bf16x8 qf[KS];
 #pragma unroll
@@ -334,14 +337,13 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
   auto begin_segment = [&](int j) {
     ++cur_sg;
     const DecodeSeg it = segs[cur_sg];
-    const int rows = it.n_new * G;
-    valid = qcol < rows;
-    i_tok = valid ? qcol / G : 0;
-    const int hg = valid ? qcol % G : 0;
-    has_bitmap = it.wpr > 0;
-    s_kv_len = it.kv_len; s_n_new = it.n_new;
-    mrow = a.mask_words + it.mask_off + (int64_t)i_tok * it.wpr;
-    const bf16_t* qrow = a.q + (int64_t)(it.tok0 + i_tok) * a.q_stride + (it.hk * G + hg) * D + g4 * 8;
+    const DecodeCol col = cols[(int64_t)it.cgroup * 16 + qcol];
+    valid = col.tok >= 0;
+    has_bitmap = col.wpr > 0;
+    c_kv_len = col.kv_len;
+    c_lim = col.lim;
+    mrow = a.mask_words + col.mask_row;
+    const bf16_t* qrow = a.q + (int64_t)(valid ? col.tok : 0) * a.q_stride + (it.hk * G + col.hg) * D + g4 * 8;
 #pragma unroll
     for (int k = 0; k < KS; ++k) {
       Pack16 p;
@@ -364,9 +366,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
       load_mask(set_c);
       if (j + 1 < seg_end && j + 1 < n_pairs) load_mask(other_c);
     }
-    const uint32_t bits_a = key_bits4(s_kv_len, s_n_new, has_bitmap, mw_a[S], i_tok, pl_a[S], quad, valid);
-    const uint32_t bits_b =
-        has_b[S] ? key_bits4(s_kv_len, s_n_new, has_bitmap, mw_b[S], i_tok, pl_b[S], quad, valid) : 0u;
+    const uint32_t bits_a = key_bits4(c_kv_len, c_lim, has_bitmap, mw_a[S], pl_a[S], quad, valid);
+    const uint32_t bits_b = has_b[S] ? key_bits4(c_kv_len, c_lim, has_bitmap, mw_b[S], pl_b[S], quad, valid) : 0u;
     f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < KS; ++k) {
@@ -420,39 +421,44 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
   end_segment();
 }
 
-// One wave per (decode-path request, kv head, query row): lanes first share the segments' (max, sum) pairs,
-// then each lane combines D/64 output elements over the segments with independent loads.
+// One wave per (decode-path request, kv head, query row): lanes first share the (max, sum) pairs of the row's
+// partials (one per segment in which the request has a column), then each lane combines D/64 output elements
+// over the partials with independent loads.
 template <int D>
 __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, const int32_t* __restrict__ dec_reqs,
-                                                        const SegRange* __restrict__ ranges, int rows_cap,
+                                                        const int32_t* __restrict__ mref_indptr,
+                                                        const int32_t* __restrict__ mrefs, int rows_cap,
                                                         const float* __restrict__ part_o,
                                                         const float* __restrict__ part_ml) {
   const ReqInfo rq = a.reqs[dec_reqs[blockIdx.x]];
   const int hk = blockIdx.y, row = blockIdx.z, lane = threadIdx.x;
   const int G = a.Hq / a.Hkv;
   if (row >= rq.n_new * G) return;
-  const SegRange rg = ranges[blockIdx.x * a.Hkv + hk];
+  const int ref0 = mref_indptr[blockIdx.x * a.Hkv + hk];
+  const int count = mref_indptr[blockIdx.x * a.Hkv + hk + 1] - ref0;
   constexpr int E = D / 64;
   float num[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) num[e] = 0.f;
-  auto prow_of = [&](int c) { return (int64_t)(rg.first + c) * rows_cap + row; };
   float M = -INFINITY;
-  for (int c = lane; c < rg.count; c += 64) M = fmaxf(M, part_ml[prow_of(c) * 2]);
+  for (int c = lane; c < count; c += 64) M = fmaxf(M, part_ml[(int64_t)(mrefs[ref0 + c] + row) * 2]);
   M = wave_max(M);
   float den = 0.f;
   if (M != -INFINITY) {
-    for (int c0 = 0; c0 < rg.count; c0 += 64) {
+    for (int c0 = 0; c0 < count; c0 += 64) {
       const int c = c0 + lane;
       float w = 0.f;
-      if (c < rg.count) {
-        w = __builtin_amdgcn_exp2f(part_ml[prow_of(c) * 2] - M);
-        den += w * part_ml[prow_of(c) * 2 + 1];
+      int64_t prow = 0;
+      if (c < count) {
+        prow = mrefs[ref0 + c] + row;
+        w = __builtin_amdgcn_exp2f(part_ml[prow * 2] - M);
+        den += w * part_ml[prow * 2 + 1];
       }
-      const int cnt = min(64, rg.count - c0);
+      const int cnt = min(64, count - c0);
       for (int j = 0; j < cnt; ++j) {
         const float wj = __shfl(w, j);
-        const float* po = part_o + prow_of(c0 + j) * D + lane * E;
+        const int64_t pj = __shfl((int)prow, j);
+        const float* po = part_o + pj * D + lane * E;
 #pragma unroll
         for (int e = 0; e < E; ++e) num[e] += wj * po[e];
       }
@@ -690,25 +696,26 @@ __global__ __launch_bounds__(512) void attn_prefill_direct_kernel(AttnArgs a, co
 // launchers
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const int2* wave_pg, int slots,
-                              const DecodeSeg* segs, int n_waves, int rows_cap, float* part_o, float* part_ml,
-                              hipStream_t s) {
+                              const DecodeSeg* segs, const DecodeCol* cols, int n_waves, int rows_cap, float* part_o,
+                              float* part_ml, hipStream_t s) {
   if (n_waves <= 0) return hipSuccess;
   if (slots < 2 || slots > 128 || (slots & 1)) return hipErrorInvalidValue;  // the page list must fit two registers
   dim3 grid((n_waves + 3) / 4), block(256);
   if (a.D == 128)
-    attn_decode_kernel<128><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, n_waves, rows_cap, part_o, part_ml);
+    attn_decode_kernel<128><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
   else if (a.D == 64)
-    attn_decode_kernel<64><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, n_waves, rows_cap, part_o, part_ml);
+    attn_decode_kernel<64><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
-hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const SegRange* ranges,
-                             int rows_cap, const float* part_o, const float* part_ml, hipStream_t s) {
+hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const int32_t* mref_indptr,
+                             const int32_t* mrefs, int rows_cap, const float* part_o, const float* part_ml,
+                             hipStream_t s) {
   if (n_dec_reqs <= 0) return hipSuccess;
   dim3 grid(n_dec_reqs, a.Hkv, rows_cap), block(64);
-  if (a.D == 128) attn_merge_kernel<128><<<grid, block, 0, s>>>(a, dec_reqs, ranges, rows_cap, part_o, part_ml);
-  else if (a.D == 64) attn_merge_kernel<64><<<grid, block, 0, s>>>(a, dec_reqs, ranges, rows_cap, part_o, part_ml);
+  if (a.D == 128) attn_merge_kernel<128><<<grid, block, 0, s>>>(a, dec_reqs, mref_indptr, mrefs, rows_cap, part_o, part_ml);
+  else if (a.D == 64) attn_merge_kernel<64><<<grid, block, 0, s>>>(a, dec_reqs, mref_indptr, mrefs, rows_cap, part_o, part_ml);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -52,15 +52,20 @@ struct ReqInfo {       // one per request, device + host
   int32_t pad;
 };
 
-struct DecodeSeg {     // a run of page pairs of one (decode-path request, kv head) inside one wave's share
-  int32_t tok0, n_new, kv_len;
-  int32_t n_pairs;     // page pairs of the run (the last pair of a (request, head) may hold one page)
-  int32_t wpr;
-  int32_t hk;
-  int64_t mask_off;
+struct DecodeCol {     // one query column of a column group: (request token, head within the kv group)
+  int32_t tok;         // token index (row of q), -1 = unused column
+  int32_t hg;          // head within the group
+  int32_t kv_len;      // of the column's request
+  int32_t lim;         // last logical index visible under the causal rule: kv_len - n_new + i
+  int32_t wpr;         // mask words per row, 0 = inferred causal
+  int32_t pad;
+  int64_t mask_row;    // word offset of this token's mask row
 };
+// A column group is a set of up to 16 query columns that walk the same pages: the rows of one decode-path
+// request, or of several requests whose page tables name the same physical page at the same logical index
+// (shared prefixes), so that each K/V block is read once for all of them.
+struct DecodeSeg { int32_t cgroup, hk, n_pairs, pad; };  // a run of page pairs of one (column group, kv head) inside one wave's share
 struct DecodeWave { int32_t seg0, n_seg, n_pairs, pad; };  // a wave's share: segments [seg0, seg0 + n_seg)
-struct SegRange { int32_t first, count; };  // segments of one (decode-path request, kv head), in key order
 struct PrefillItem { int32_t r, qb; };           // query block qb (32 tokens) of request r
 
 struct pie_batch {
@@ -73,13 +78,15 @@ struct pie_batch {
   DecodeSeg* dsegs = nullptr;
   DecodeWave* dwaves = nullptr;  // [n_dwaves]
   int2* wave_pg = nullptr;       // [n_dwaves, dslots] (page * Hkv + kv head, logical page) of every pair slot
-  SegRange* seg_ranges = nullptr;  // [n_dec_reqs * Hkv]
+  DecodeCol* dcols = nullptr;      // [n_cgroups, 16]
+  int32_t* mref_indptr = nullptr;  // [n_dec_reqs * Hkv + 1] partial rows to merge per (decode request, kv head)
+  int32_t* mrefs = nullptr;        // first partial row (segment * rows_cap + first column of the request)
   PrefillItem* pitems = nullptr;
   int32_t* dec_reqs = nullptr;  // request indices on the decode path
   int32_t n_dsegs = 0, n_dwaves = 0, dslots = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
   float* part_o = nullptr;   // [n_dsegs * rows_cap, D]
   float* part_ml = nullptr;  // [n_dsegs * rows_cap, 2]
-  int64_t work[4] = {0, 0, 0, 0};
+  int64_t work[6] = {0, 0, 0, 0, 0, 0};
 };
 
 struct pie_ctx {
@@ -164,10 +171,11 @@ struct AttnArgs {
   const uint32_t* mask_words;
 };
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const int2* wave_pg, int slots,
-                              const DecodeSeg* segs, int n_waves, int rows_cap, float* part_o, float* part_ml,
-                              hipStream_t s);
-hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const SegRange* ranges,
-                             int rows_cap, const float* part_o, const float* part_ml, hipStream_t s);
+                              const DecodeSeg* segs, const DecodeCol* cols, int n_waves, int rows_cap, float* part_o,
+                              float* part_ml, hipStream_t s);
+hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const int32_t* mref_indptr,
+                             const int32_t* mrefs, int rows_cap, const float* part_o, const float* part_ml,
+                             hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s);
 
 int topk_chunks(int V, int k);  // chunks per row used by launch_topk (<= 16), 0 if unsupported

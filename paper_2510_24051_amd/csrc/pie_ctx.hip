@@ -426,19 +426,107 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
       if (!seen.insert((int64_t)tok_page[t] * PAGE + tok_slot[t]).second)
         return fail(c, PIE_ECONFLICT, "token %d writes (page %d, slot %d) that another token of the batch writes", t, tok_page[t], tok_slot[t]);
   }
-  // Decode path: the page pairs of all (request, kv head) combinations form one flat list that is cut into
-  // equal shares, one per wave, for as many waves as the chip keeps resident (more when a share would exceed
-  // the 64 pairs whose page ids a wave holds in registers).  A share may cover the end of one (request, head)
-  // and the start of the next; each such run is a segment with its own partial result.  Every wave gets its
-  // page list (block index = page * Hkv + kv head, logical page) at a fixed stride, two slots per pair.
+  // Decode path.  Query columns are gathered into column groups of up to 16 columns that walk the same pages:
+  // the rows of one request, or of several requests whose page tables name the same physical page at the same
+  // logical index (shared prefixes), so that each K/V block is read once for all of them; what such requests
+  // do not share stays in groups of their own.  The page pairs of all (column group, kv head) combinations form
+  // one flat list that is cut into equal shares, one per wave, for as many waves as the chip keeps resident
+  // (more when a share would exceed the 64 pairs whose page ids a wave holds in registers).  A share may cover
+  // the end of one (group, head) and the start of the next; each such run is a segment with its own partial
+  // result.  Every wave gets its page list (block index = page * Hkv + kv head, logical page) at a fixed
+  // stride, two slots per pair.
+  struct CGroup { std::vector<int> members; int rows; std::vector<int2> pages; };  // members: decode request indices
+  std::vector<CGroup> cgroups;
+  {
+    std::unordered_map<int64_t, size_t> class_of;  // (rows, first physical page) -> index into classes
+    std::vector<std::vector<int>> classes;
+    for (size_t di = 0; di < dec_reqs.size(); ++di) {
+      const int r = dec_reqs[di];
+      const int rows = reqs[r].n_new * G;
+      if (16 / rows < 2) {  // the request fills the 16 columns by itself
+        classes.emplace_back(1, (int)di);
+        continue;
+      }
+      const int64_t key = ((int64_t)rows << 32) | (uint32_t)b->page_ids[b->page_indptr[r]];
+      auto ins = class_of.emplace(key, classes.size());
+      if (ins.second) classes.emplace_back();
+      classes[ins.first->second].push_back((int)di);
+    }
+    auto single = [&](int di, const std::vector<char>* skip) {
+      const ReqInfo& q = reqs[dec_reqs[di]];
+      CGroup g;
+      g.members.push_back(di);
+      g.rows = q.n_new * G;
+      for (int v = 0; v < q.n_visit; ++v)
+        if (!skip || !(*skip)[visit_logical[q.visit0 + v]])
+          g.pages.push_back(make_int2(visit_phys[q.visit0 + v], visit_logical[q.visit0 + v]));
+      if (!g.pages.empty() || !skip) cgroups.push_back(std::move(g));
+    };
+    for (const auto& cls : classes) {
+      const int rows = reqs[dec_reqs[cls[0]]].n_new * G;
+      const int cap = 16 / rows;
+      for (size_t c0 = 0; c0 < cls.size(); c0 += cap) {
+        const size_t c1 = std::min(cls.size(), c0 + cap);
+        if (c1 - c0 < 2) { single(cls[c0], nullptr); continue; }
+        // logical pages on which every member's table names the same physical page, visited by at least one
+        int common = INT32_MAX;
+        for (size_t k = c0; k < c1; ++k) common = std::min(common, (reqs[dec_reqs[cls[k]]].kv_len + PAGE - 1) / PAGE);
+        std::vector<char> shared(common, 1), visited(common, 0);
+        const int32_t* pg0 = b->page_ids + b->page_indptr[dec_reqs[cls[c0]]];
+        for (size_t k = c0; k < c1; ++k) {
+          const ReqInfo& q = reqs[dec_reqs[cls[k]]];
+          const int32_t* pg = b->page_ids + b->page_indptr[dec_reqs[cls[k]]];
+          for (int pgi = 0; pgi < common; ++pgi) if (pg[pgi] != pg0[pgi]) shared[pgi] = 0;
+          for (int v = 0; v < q.n_visit; ++v)
+            if (visit_logical[q.visit0 + v] < common) visited[visit_logical[q.visit0 + v]] = 1;
+        }
+        CGroup g;
+        g.rows = rows;
+        for (int pgi = 0; pgi < common; ++pgi) {
+          shared[pgi] = shared[pgi] && visited[pgi];
+          if (shared[pgi]) g.pages.push_back(make_int2(pg0[pgi], pgi));
+        }
+        if (g.pages.size() < 2) {  // nothing worth sharing
+          for (size_t k = c0; k < c1; ++k) single(cls[k], nullptr);
+          continue;
+        }
+        for (size_t k = c0; k < c1; ++k) g.members.push_back(cls[k]);
+        cgroups.push_back(std::move(g));
+        // what a member visits outside the shared pages (private suffix, pages beyond the shortest member)
+        std::vector<char> skip;
+        for (size_t k = c0; k < c1; ++k) {
+          const int n_pg = (reqs[dec_reqs[cls[k]]].kv_len + PAGE - 1) / PAGE;
+          skip.assign(n_pg, 0);
+          std::copy(shared.begin(), shared.end(), skip.begin());
+          single(cls[k], &skip);
+        }
+      }
+    }
+  }
+  std::vector<DecodeCol> dcols(cgroups.size() * 16, DecodeCol{-1, 0, 0, 0, 0, 0, 0});
   std::vector<DecodeSeg> dsegs;
   std::vector<DecodeWave> dwaves;
   std::vector<int2> wave_pg;
-  std::vector<SegRange> seg_ranges(dec_reqs.size() * Hkv, SegRange{0, 0});
+  std::vector<std::vector<int32_t>> mref_lists(dec_reqs.size() * Hkv);
   int dslots = 2;
+  int64_t kv_bytes_req = 0;  // bytes the decode kernel asks for after grouping
   {
+    rows_cap = 1;
     int64_t total_pairs = 0;
-    for (int r : dec_reqs) total_pairs += (int64_t)((reqs[r].n_visit + 1) / 2) * Hkv;
+    for (size_t gi = 0; gi < cgroups.size(); ++gi) {
+      const CGroup& g = cgroups[gi];
+      rows_cap = std::max(rows_cap, (int)g.members.size() * g.rows);
+      total_pairs += (int64_t)((g.pages.size() + 1) / 2) * Hkv;
+      kv_bytes_req += (int64_t)g.pages.size() * page_bytes;
+      for (size_t mi = 0; mi < g.members.size(); ++mi) {
+        const ReqInfo& q = reqs[dec_reqs[g.members[mi]]];
+        for (int rr = 0; rr < g.rows; ++rr) {
+          const int i_tok = rr / G;
+          dcols[gi * 16 + mi * g.rows + rr] = DecodeCol{q.tok0 + i_tok, rr % G, q.kv_len, q.kv_len - q.n_new + i_tok,
+                                                       q.wpr, 0, q.mask_off + (int64_t)i_tok * q.wpr};
+        }
+      }
+    }
     int64_t per_wave = (total_pairs + c->wave_slots - 1) / c->wave_slots;
     per_wave = std::min<int64_t>(std::max<int64_t>(per_wave, 2), 64);
     dslots = (int)(2 * per_wave);
@@ -452,28 +540,27 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
       cur = DecodeWave{(int32_t)dsegs.size(), 0, 0, 0};
       filled = 0;
     };
-    for (size_t di = 0; di < dec_reqs.size(); ++di) {
-      const ReqInfo& q = reqs[dec_reqs[di]];
-      const int P = (q.n_visit + 1) / 2;
+    for (size_t gi = 0; gi < cgroups.size(); ++gi) {
+      const CGroup& g = cgroups[gi];
+      const int n_pg = (int)g.pages.size();
+      const int P = (n_pg + 1) / 2;
       for (int hk = 0; hk < Hkv; ++hk) {
-        SegRange& rg = seg_ranges[di * Hkv + hk];
-        rg.first = (int32_t)dsegs.size();
         int p = 0;
         while (p < P) {
           const int take = (int)std::min<int64_t>(per_wave - filled, P - p);
-          dsegs.push_back(DecodeSeg{q.tok0, q.n_new, q.kv_len, take, q.wpr, hk, q.mask_off});
+          for (size_t mi = 0; mi < g.members.size(); ++mi)  // partial rows start at segment * rows_cap (set below)
+            mref_lists[(size_t)g.members[mi] * Hkv + hk].push_back((int32_t)(dsegs.size() * 16 + mi * g.rows));
+          dsegs.push_back(DecodeSeg{(int32_t)gi, hk, take, 0});
           ++cur.n_seg;
           for (int pr = p; pr < p + take; ++pr)
             for (int e = 0; e < 2; ++e) {
               const int v = 2 * pr + e;
-              wave_pg.push_back(v < q.n_visit ? make_int2(visit_phys[q.visit0 + v] * Hkv + hk, visit_logical[q.visit0 + v])
-                                              : make_int2(-1, 0));
+              wave_pg.push_back(v < n_pg ? make_int2(g.pages[v].x * Hkv + hk, g.pages[v].y) : make_int2(-1, 0));
             }
           p += take;
           filled += take;
           if (filled == per_wave) close_wave();
         }
-        rg.count = (int32_t)dsegs.size() - rg.first;
       }
     }
     if (filled > 0) close_wave();
@@ -482,15 +569,28 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
     for (size_t w = 0; w < dwaves.size(); ++w) {
       const DecodeWave& dw = dwaves[w];
       int pairs = 0;
-      for (int sg = dw.seg0; sg < dw.seg0 + dw.n_seg; ++sg) pairs += dsegs[sg].n_pairs;
-      bool ok = dw.n_seg > 0 && dw.seg0 >= 0 && dw.seg0 + dw.n_seg <= (int)dsegs.size() && pairs == dw.n_pairs &&
-                dw.n_pairs > 0 && 2 * dw.n_pairs <= dslots;
+      bool ok = dw.n_seg > 0 && dw.seg0 >= 0 && dw.seg0 + dw.n_seg <= (int)dsegs.size();
+      for (int sg = dw.seg0; ok && sg < dw.seg0 + dw.n_seg; ++sg) {
+        pairs += dsegs[sg].n_pairs;
+        ok = dsegs[sg].n_pairs > 0 && dsegs[sg].cgroup >= 0 && dsegs[sg].cgroup < (int)cgroups.size() &&
+             dsegs[sg].hk >= 0 && dsegs[sg].hk < Hkv;
+      }
+      ok = ok && pairs == dw.n_pairs && dw.n_pairs > 0 && 2 * dw.n_pairs <= dslots;
       for (int j = 0; ok && j < 2 * dw.n_pairs; ++j) {
         const int2 e = wave_pg[w * dslots + j];
         ok = (e.x >= 0 || (j & 1)) && e.x < n_blocks && e.y >= 0;
       }
       if (!ok) return fail(c, PIE_EINVAL, "internal: inconsistent decode plan for wave %zu", w);
     }
+    for (const DecodeCol& dc : dcols)
+      if (dc.tok >= T || dc.hg < 0 || dc.hg >= G || (dc.tok >= 0 && dc.wpr > 0 && dc.mask_row + dc.wpr > (int64_t)b->mask_indptr[R]))
+        return fail(c, PIE_EINVAL, "internal: inconsistent decode column");
+  }
+  // partial rows a (decode request, kv head) has to merge: segment * rows_cap + the request's first column
+  std::vector<int32_t> mref_indptr(dec_reqs.size() * Hkv + 1, 0), mrefs;
+  for (size_t i = 0; i < mref_lists.size(); ++i) {
+    for (int32_t v : mref_lists[i]) mrefs.push_back((v / 16) * rows_cap + (v % 16));
+    mref_indptr[i + 1] = (int32_t)mrefs.size();
   }
   // heavy query blocks first
   std::stable_sort(pitems.begin(), pitems.end(), [&](const PrefillItem& x, const PrefillItem& y) {
@@ -510,6 +610,13 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   pb->n_dec_reqs = (int32_t)dec_reqs.size();
   pb->rows_cap = std::max(rows_cap, 1);
   pb->work[0] = kv_bytes; pb->work[1] = kv_bytes_dec; pb->work[2] = flops; pb->work[3] = (int64_t)visit_phys.size();
+  {
+    std::unordered_set<int32_t> distinct;
+    for (int r : dec_reqs)
+      distinct.insert(visit_phys.begin() + reqs[r].visit0, visit_phys.begin() + reqs[r].visit0 + reqs[r].n_visit);
+    pb->work[4] = (int64_t)distinct.size() * page_bytes;
+  }
+  pb->work[5] = kv_bytes_req;
   Blob blob;
   const size_t o_in = blob.add(b->in_embed_ids, (size_t)T * 4), o_out = blob.add(b->out_embed_ids, (size_t)T * 4);
   const size_t o_pos = blob.add(b->positions ? b->positions : pos_from_embeds.data(), (size_t)T * 4), o_tp = blob.add(tok_page.data(), (size_t)T * 4);
@@ -522,7 +629,9 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   const size_t o_di = blob.add(dsegs.data(), dsegs.size() * sizeof(DecodeSeg), 16);
   const size_t o_ws = blob.add(dwaves.data(), dwaves.size() * sizeof(DecodeWave), 16);
   const size_t o_wp = blob.add(wave_pg.data(), wave_pg.size() * sizeof(int2), 16);
-  const size_t o_sr = blob.add(seg_ranges.data(), seg_ranges.size() * sizeof(SegRange), 8);
+  const size_t o_dc = blob.add(dcols.data(), dcols.size() * sizeof(DecodeCol), 16);
+  const size_t o_mi = blob.add(mref_indptr.data(), mref_indptr.size() * 4, 4);
+  const size_t o_mr = blob.add(mrefs.data(), mrefs.size() * 4, 4);
   const size_t o_pi = blob.add(pitems.data(), pitems.size() * sizeof(PrefillItem), 8);
   const size_t o_dr = blob.add(dec_reqs.data(), dec_reqs.size() * 4, 4);
   const size_t part_rows = (size_t)pb->n_dsegs * pb->rows_cap;
@@ -547,7 +656,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   pb->tok_page = (int32_t*)(d + o_tp); pb->tok_slot = (int32_t*)(d + o_ts);
   pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl);
   pb->mask_words = (uint32_t*)(d + o_mw); pb->reqs = (ReqInfo*)(d + o_rq);
-  pb->dsegs = (DecodeSeg*)(d + o_di); pb->dwaves = (DecodeWave*)(d + o_ws); pb->wave_pg = (int2*)(d + o_wp); pb->seg_ranges = (SegRange*)(d + o_sr);
+  pb->dsegs = (DecodeSeg*)(d + o_di); pb->dwaves = (DecodeWave*)(d + o_ws); pb->wave_pg = (int2*)(d + o_wp);
+  pb->dcols = (DecodeCol*)(d + o_dc); pb->mref_indptr = (int32_t*)(d + o_mi); pb->mrefs = (int32_t*)(d + o_mr);
   pb->pitems = (PrefillItem*)(d + o_pi); pb->dec_reqs = (int32_t*)(d + o_dr);
   pb->part_o = (float*)(d + o_po); pb->part_ml = (float*)(d + o_pm);
   *out = pb;
@@ -564,7 +674,7 @@ extern "C" pie_status pie_batch_destroy(pie_ctx* c, pie_batch* b) {
 
 extern "C" pie_status pie_batch_work(const pie_batch* b, int64_t* out) {
   if (!b || !out) return PIE_EINVAL;
-  for (int i = 0; i < 4; ++i) out[i] = b->work[i];
+  for (int i = 0; i < 6; ++i) out[i] = b->work[i];
   return PIE_OK;
 }
 
@@ -618,10 +728,10 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
   a.reqs = b->reqs; a.visit_phys = b->visit_phys; a.visit_logical = b->visit_logical; a.mask_words = b->mask_words;
   if (b->n_dec_reqs > 0) {
     tm.begin(PIE_STAGE_ATTN_DECODE);
-    HIP_TRY(c, launch_attn_decode(a, b->dwaves, b->wave_pg, b->dslots, b->dsegs, b->n_dwaves, b->rows_cap, b->part_o, b->part_ml, s));
+    HIP_TRY(c, launch_attn_decode(a, b->dwaves, b->wave_pg, b->dslots, b->dsegs, b->dcols, b->n_dwaves, b->rows_cap, b->part_o, b->part_ml, s));
     tm.end(PIE_STAGE_ATTN_DECODE);
     tm.begin(PIE_STAGE_ATTN_MERGE);
-    HIP_TRY(c, launch_attn_merge(a, b->dec_reqs, b->n_dec_reqs, b->seg_ranges, b->rows_cap, b->part_o, b->part_ml, s));
+    HIP_TRY(c, launch_attn_merge(a, b->dec_reqs, b->n_dec_reqs, b->mref_indptr, b->mrefs, b->rows_cap, b->part_o, b->part_ml, s));
     tm.end(PIE_STAGE_ATTN_MERGE);
   }
   if (b->n_pitems > 0) {

@@ -138,6 +138,74 @@ def test_large_batches_on_small_models(hidden, mlp, n_q, n_kv, T_prefill):
     compare_layer(w, what=f"T={w.batch.n_tokens} H{hidden} I{mlp} {n_q}/{n_kv}")
 
 
+# ---------------------------------------------------------------- shared prefixes (requests aliasing pages)
+def hide_span(a0, a1):
+    def f(n_new, L, rng):
+        m = W.causal_bitmap(n_new, L)
+        m[:, a0:a1] = False
+        return m
+    return f
+
+
+@pytest.mark.parametrize("head_dim,n_q,n_kv", [(64, 4, 2), (128, 8, 2), (64, 2, 2)])
+def test_shared_prefix_requests_are_grouped_and_match(head_dim, n_q, n_kv):
+    """Requests whose page tables alias the same prefix pages: the decode kernel reads each shared K/V block
+    once for several requests (fewer bytes requested than the per-request count), same result as the oracle,
+    which gathers every request's KV separately."""
+    m = small_model(head_dim, n_q, n_kv)
+    P = 16
+    reqs = [W.RequestSpec(1, 5 * P + 3, prefix_group=0, prefix_len=5 * P),                       # causal
+            W.RequestSpec(1, 5 * P + 40, prefix_group=0, prefix_len=5 * P, mask=hide_span(P, 3 * P)),  # hides pages 1-2
+            W.RequestSpec(1, 5 * P, prefix_group=0, prefix_len=5 * P, in_place=True),            # no private prior
+            W.RequestSpec(1, 9 * P + 1, prefix_group=0, prefix_len=5 * P, mask=W.causal_bitmap),
+            W.RequestSpec(1, 5 * P + 7, prefix_group=0, prefix_len=5 * P, mask=random_mask(0.2)),
+            W.RequestSpec(1, 33),                                                              # unrelated
+            W.RequestSpec(2, 3 * P + 5, prefix_group=1, prefix_len=3 * P),                       # two rows per head
+            W.RequestSpec(2, 3 * P + 20, prefix_group=1, prefix_len=3 * P, mask=hide_span(0, 20)),
+            W.RequestSpec(1, 6 * P, prefix_group=0, prefix_len=5 * P),
+            W.RequestSpec(40, 3 * P, prefix_group=1, prefix_len=3 * P),                          # prefill over a shared prefix
+            W.RequestSpec(1, 2 * P + 2, prefix_group=2, prefix_len=2 * P),
+            W.RequestSpec(1, 2 * P + 9, prefix_group=2, prefix_len=2 * P)]
+    w = W.build_workload("shared", m, reqs, n_kv_pages=96, seed=700 + head_dim + n_q, std=0.05)
+    ctx, pb, _, _ = compare_layer(w, what=f"shared prefixes D{head_dim} {n_q}/{n_kv}")
+    work = pb.work()
+    print(f"    decode KV bytes: per request {work['kv_bytes_decode']}, requested {work['kv_bytes_requested']}, "
+          f"distinct pages {work['kv_bytes_unique']}", flush=True)
+    assert work["kv_bytes_requested"] < work["kv_bytes_decode"]
+
+
+def test_partially_shared_tables_and_tables_in_another_order():
+    """Same first page, one differing page in the middle (only the equal positions are shared); and two
+    requests naming the same prefix pages in a different logical order (only position 0 matches: nothing is
+    grouped, the result is still the oracle's)."""
+    m = small_model()
+    P = 16
+    reqs = [W.RequestSpec(1, 4 * P + 5, prefix_group=0, prefix_len=4 * P),
+            W.RequestSpec(1, 4 * P + 9, prefix_group=0, prefix_len=4 * P),
+            W.RequestSpec(1, 4 * P + 1, prefix_group=0, prefix_len=4 * P),
+            W.RequestSpec(1, 3 * P + 4, prefix_group=1, prefix_len=3 * P),
+            W.RequestSpec(1, 3 * P + 11, prefix_group=1, prefix_len=3 * P)]
+    w = W.build_workload("partial", m, reqs, n_kv_pages=64, seed=77, std=0.05)
+    b = w.batch
+    used = set(b.page_ids.tolist())
+    spare = [p for p in range(64) if p not in used]
+    # request 1: logical page 2 becomes a private page with contents of its own
+    rng = W.rng_for(77, 99)
+    b.page_ids[b.page_indptr[1] + 2] = spare[0]
+    w.prior.page_ids = np.concatenate([w.prior.page_ids, np.full(P, spare[0], np.int32)])
+    w.prior.slots = np.concatenate([w.prior.slots, np.arange(P, dtype=np.int32)])
+    w.prior.k_bits = np.concatenate([w.prior.k_bits, W.normal_bf16(rng, (P, m.n_kv_heads, m.head_dim))])
+    w.prior.v_bits = np.concatenate([w.prior.v_bits, W.normal_bf16(rng, (P, m.n_kv_heads, m.head_dim))])
+    # request 4 reads the shared prefix pages 1 and 2 in the other order
+    a4 = b.page_indptr[4]
+    b.page_ids[a4 + 1], b.page_ids[a4 + 2] = b.page_ids[a4 + 2], b.page_ids[a4 + 1]
+    ctx, pb, _, _ = compare_layer(w, what="partially shared tables")
+    work = pb.work()
+    # requests 0-2 share logical pages 0, 1, 3 (3 pages read once instead of three times); 3-4 share nothing
+    page_bytes = m.n_kv_heads * 2 * P * m.head_dim * 2
+    assert work["kv_bytes_decode"] - work["kv_bytes_requested"] == 2 * 3 * page_bytes
+
+
 def test_rows_without_visible_keys_output_the_residual_only():
     m = small_model()
 
