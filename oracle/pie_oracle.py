@@ -1,7 +1,9 @@
 """CPU oracle for the batched `forward` handler (one Llama-class decoder layer over a
 heterogeneous batch of commands against KvPage page tables with per-token masks and KV append,
 and the same call through every layer of the model), for the `embed_txt` handler (token ids and
-positions into Embeds) and for the `get_next_dist` handler (vocab softmax truncated to top-K).
+positions into Embeds), for the KvPage control calls `mask_kvpage` / `copy_kvpage` (token-level
+masking and copying of the KV cache) and for the `get_next_dist` handler (vocab softmax truncated
+to top-K).
 
 THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, dense NumPy implementation written from the
 paper's statement of the two calls (Programming Model and API: Resources; Forward API; Sample
@@ -29,6 +31,10 @@ Parity pins (tests/test_oracle_*.py, all CPU):
   whole layer         torch CPU expression of a textbook Llama layer on one contiguous request
   softmax / top-k     torch.softmax + torch.topk, k=V sums to 1, shift invariance
   embed_txt           one-hot matrix product, positions recorded with the Embed
+  mask_kvpage         equals the same call with the masked tokens cleared in an explicit bitmap;
+                      all-ones mask is a no-op; a fully masked page equals an omitted page
+  copy_kvpage         a request over token-wise copied pages equals the request over the originals;
+                      bit-exact against a hand-written slot loop, in every layer's pool
   full depth          torch CPU expression of a textbook L-layer Llama on one contiguous request;
                       zero Wo and Wdown in every layer -> output == input; prefill of n tokens ==
                       n-1 tokens writing pages + 1 token reading them, through all layers
@@ -102,6 +108,7 @@ class KvPool:
         self.page_size = page_size
         self.k_bits = np.zeros((n_pages, page_size, n_kv_heads, head_dim), dtype=np.uint16)
         self.v_bits = np.zeros((n_pages, page_size, n_kv_heads, head_dim), dtype=np.uint16)
+        self.visible = np.ones((n_pages, page_size), dtype=bool)  # token-level page masks set by mask_kvpage
 
     def write(self, page_ids, slots, k_bits, v_bits):
         p = np.asarray(page_ids, dtype=np.int64)
@@ -298,6 +305,8 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
                 allowed[a] = mask_row_bits(batch.mask_words[base + i * wpr: base + (i + 1) * wpr], L)
         else:  # causal on logical order
             allowed = j[None, :] <= (L - n_new + i_new)[:, None]
+        # tokens hidden by mask_kvpage are invisible to every row, whatever the call's own mask says
+        allowed = allowed & kv.visible[pages_r[j // P], j % P][None, :]
         o = masked_attention(q, kk, vv, allowed)
         q_out[sel] = q
         o_out[sel] = _maybe_round(o, rnd)
@@ -354,6 +363,40 @@ def forward_model(model, layers, kvs, emb: EmbedPool, batch, *, rows: Optional[S
         results.append(res)
         x = res.y
     return results
+
+
+# --------------------------------------------------------------------------------------------
+# KvPage control calls
+# --------------------------------------------------------------------------------------------
+
+
+def mask_kvpage(kvs, page_ids, visible_bits) -> None:
+    """`mask_kvpage(tgt, mask)` (Table 1, Forward row): sets the token-level mask of each target KvPage.
+    `visible_bits[k]` is an integer whose bit s says whether the token in slot s of page `page_ids[k]`
+    stays visible; the mask replaces the page's previous one, belongs to the page in every layer
+    (`kvs` is the list of per-layer pools) and is honoured by every later `forward` call on top of that
+    call's own mask."""
+    P = kvs[0].page_size
+    for pg, bits in zip(np.asarray(page_ids, dtype=np.int64), np.asarray(visible_bits, dtype=np.int64)):
+        row = np.array([(int(bits) >> s) & 1 for s in range(P)], dtype=bool)
+        for kv in kvs:
+            kv.visible[pg] = row
+
+
+def copy_kvpage(kvs, src_pages, src_slots, dst_pages, dst_slots) -> None:
+    """`copy_kvpage(src, dst)` (Table 1, Allocate row): token-level copy of KV cache contents.  Token k of
+    the call is read from (src_pages[k], src_slots[k]) and written to (dst_pages[k], dst_slots[k]), K and V,
+    unchanged bits, in every layer; page masks are not copied.  Source and destination tokens are disjoint."""
+    sp, ss = np.asarray(src_pages, dtype=np.int64), np.asarray(src_slots, dtype=np.int64)
+    dp, ds = np.asarray(dst_pages, dtype=np.int64), np.asarray(dst_slots, dtype=np.int64)
+    assert sp.shape == ss.shape == dp.shape == ds.shape
+    src = set(zip(sp.tolist(), ss.tolist()))
+    dst = list(zip(dp.tolist(), ds.tolist()))
+    assert len(set(dst)) == len(dst) and not (src & set(dst)), "source and destination tokens must be disjoint"
+    for kv in kvs:
+        k, v = kv.k_bits[sp, ss].copy(), kv.v_bits[sp, ss].copy()
+        kv.k_bits[dp, ds] = k
+        kv.v_bits[dp, ds] = v
 
 
 # --------------------------------------------------------------------------------------------
