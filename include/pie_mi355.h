@@ -98,6 +98,22 @@ pie_status pie_kv_write(pie_ctx* ctx, int32_t layer, const int32_t* page_ids, co
 pie_status pie_kv_read(pie_ctx* ctx, int32_t layer, const int32_t* page_ids, const int32_t* slots, int32_t n,
                        void* k /* dev */, void* v /* dev */);
 
+/* `mask_kvpage(q, tgt, mask)` (Table 1, Forward row: masks the KV cache in a token-level manner): sets the
+ * token-level mask of each target KvPage; bit s of visible_bits[k] says whether the token in slot s of page
+ * page_ids[k] stays visible (bits at and above page_size are ignored).  The mask replaces the page's previous
+ * one, holds in every layer, and is honoured, on top of a call's own mask, by every batch deserialised
+ * afterwards (pie_batch_create reads the masks; a batch created earlier keeps what it saw).  A fresh context has
+ * every token visible.  Host arrays [n]; no GPU work.  Errors: PIE_EINVAL, PIE_ERANGE. */
+pie_status pie_mask_kvpage(pie_ctx* ctx, const int32_t* page_ids, const uint32_t* visible_bits, int32_t n);
+
+/* `copy_kvpage(q, src, dst)` (Table 1, Allocate row: copies KV cache contents at token level): token k is
+ * read from (src_pages[k], src_slots[k]) and written to (dst_pages[k], dst_slots[k]), K and V, bit for bit,
+ * in every layer.  Page masks are not copied.  Host int32 arrays [n].  No token may be written twice or be
+ * both read and written by one call (PIE_ECONFLICT).  Synchronises the stream.
+ * Errors: PIE_EINVAL, PIE_ERANGE, PIE_ECONFLICT, PIE_EHIP. */
+pie_status pie_copy_kvpage(pie_ctx* ctx, const int32_t* src_pages, const int32_t* src_slots,
+                           const int32_t* dst_pages, const int32_t* dst_slots, int32_t n);
+
 /* One batch of `forward(q, ikv, iemb, okv, oemb, mask)` commands as the batch scheduler hands it
  * to the handler (Table 1 `forward`; Forward API; Batch scheduler: horizontal + vertical
  * batching).  The command queue argument is gone: batching has been done.  All arrays are host.

@@ -79,6 +79,8 @@ def load_library():
         "pie_forward_all": [vp, vp],
         "pie_load_embedding": [vp, vp],
         "pie_embed_txt": [vp, vp, vp, i32, vp],
+        "pie_mask_kvpage": [vp, vp, vp, i32],
+        "pie_copy_kvpage": [vp, vp, vp, vp, vp, i32],
         "pie_forward_host": [vp, i32, C.POINTER(ForwardBatchC), i32],
         "pie_get_next_dist": [vp, vp, i32, i32, f32, vp, vp],
         "pie_synchronize": [vp],
@@ -224,6 +226,19 @@ class Pie:
             torch.cuda.synchronize(self.device)
             self._check(self.lib.pie_kv_write(self.ctx, layer, _ptr(p[a:b].copy()), _ptr(s[a:b].copy()), b - a,
                                               C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr())))
+
+    def mask_kvpage(self, page_ids, visible_bits):
+        p = _i32(page_ids)
+        bits = np.ascontiguousarray(visible_bits, dtype=np.uint32)
+        if len(p) != len(bits):
+            raise ValueError("mask_kvpage: one mask per page")
+        self._check(self.lib.pie_mask_kvpage(self.ctx, _ptr(p), _ptr(bits), len(p)))
+
+    def copy_kvpage(self, src_pages, src_slots, dst_pages, dst_slots):
+        a = [_i32(x) for x in (src_pages, src_slots, dst_pages, dst_slots)]
+        if len({len(x) for x in a}) != 1:
+            raise ValueError("copy_kvpage: four arrays of one length")
+        self._check(self.lib.pie_copy_kvpage(self.ctx, *[_ptr(x) for x in a], len(a[0])))
 
     def kv_read(self, layer: int, page_ids, slots):
         p, s = _i32(page_ids), _i32(slots)

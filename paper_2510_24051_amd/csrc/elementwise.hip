@@ -246,3 +246,30 @@ hipError_t launch_kv_copy(bf16_t* kv_layer, const int32_t* pages, const int32_t*
                                                                                to_pool);
   return hipGetLastError();
 }
+
+// copy_kvpage: token k of the call moves from (src page, src slot) to (dst page, dst slot), K and V, in every
+// layer's pool (grid.y = layer); one thread per (token, kv head, element).
+__global__ void kv_token_copy_kernel(bf16_t* __restrict__ kv, size_t layer_elems, const int32_t* __restrict__ sp,
+                                     const int32_t* __restrict__ ss, const int32_t* __restrict__ dp,
+                                     const int32_t* __restrict__ ds, int n, int Hkv, int D) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)n * Hkv * D) return;
+  const int d = (int)(idx % D);
+  const int h = (int)((idx / D) % Hkv);
+  const int i = (int)(idx / ((int64_t)D * Hkv));
+  uint16_t* pool = reinterpret_cast<uint16_t*>(kv + (size_t)blockIdx.y * layer_elems);
+  const uint16_t* src = pool + ((int64_t)sp[i] * Hkv + h) * (2 * PAGE * D);
+  uint16_t* dst = pool + ((int64_t)dp[i] * Hkv + h) * (2 * PAGE * D);
+  dst[k_elem_offset(ds[i], d)] = src[k_elem_offset(ss[i], d)];
+  dst[v_elem_offset(ds[i], d, D)] = src[v_elem_offset(ss[i], d, D)];
+}
+
+hipError_t launch_kv_token_copy(bf16_t* kv, size_t layer_elems, int n_layers, const int32_t* src_pages,
+                                const int32_t* src_slots, const int32_t* dst_pages, const int32_t* dst_slots, int n,
+                                int Hkv, int D, hipStream_t s) {
+  int64_t total = (int64_t)n * Hkv * D;
+  if (total <= 0 || n_layers <= 0) return hipSuccess;
+  kv_token_copy_kernel<<<dim3((unsigned)((total + 255) / 256), (unsigned)n_layers), dim3(256), 0, s>>>(
+      kv, layer_elems, src_pages, src_slots, dst_pages, dst_slots, n, Hkv, D);
+  return hipGetLastError();
+}

@@ -105,6 +105,7 @@ struct pie_ctx {
   double* inv_freq = nullptr;
   bf16_t* table = nullptr;             // embedding table [vocab, H] (embed_txt)
   std::vector<int32_t> embed_pos;      // host: sequence position recorded with each Embed by embed_txt, -1 = none
+  std::vector<uint16_t> page_mask;     // host: token-level visibility bits of every KvPage (mask_kvpage), all layers
   float* x32 = nullptr;                // [T, H] wide layer input of the layers after the first (n_layers > 1)
   // workspace
   bf16_t *xn = nullptr, *qkv = nullptr, *attn = nullptr, *act = nullptr, *en = nullptr;
@@ -132,6 +133,9 @@ hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const 
                               const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, hipStream_t s);
 hipError_t launch_embed_copy(bf16_t* embeds, const int32_t* ids, int n, int H, bf16_t* buf, int to_pool,
                              hipStream_t s);
+hipError_t launch_kv_token_copy(bf16_t* kv, size_t layer_elems, int n_layers, const int32_t* src_pages,
+                                const int32_t* src_slots, const int32_t* dst_pages, const int32_t* dst_slots, int n,
+                                int Hkv, int D, hipStream_t s);
 hipError_t launch_embed_gather(bf16_t* embeds, const int32_t* ids, const int32_t* tok, int n, int H,
                                const bf16_t* table, hipStream_t s);
 hipError_t launch_kv_copy(bf16_t* kv_layer, const int32_t* pages, const int32_t* slots, int n, int Hkv, int D,

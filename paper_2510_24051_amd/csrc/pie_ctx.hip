@@ -89,6 +89,7 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   chk(dev_alloc(&c->h, T * H, false, c->stream));
   if (m->n_layers > 1) chk(dev_alloc(&c->x32, T * H, false, c->stream));
   c->embed_pos.assign((size_t)p->n_embeds, -1);
+  c->page_mask.assign((size_t)p->n_kv_pages, 0xFFFFu);
   chk(dev_alloc(&c->act, T * I, false, c->stream));
   // split-K workspace: only batches of <= 256 rows use it; 8 partial copies of the widest output
   {
@@ -307,6 +308,53 @@ extern "C" pie_status pie_kv_read(pie_ctx* c, int32_t layer, const int32_t* page
   return kv_copy(c, layer, pages, slots, n, k, v, 0);
 }
 
+extern "C" pie_status pie_mask_kvpage(pie_ctx* c, const int32_t* page_ids, const uint32_t* visible_bits, int32_t n) {
+  if (!c) return PIE_EINVAL;
+  if (n < 0 || (n > 0 && (!page_ids || !visible_bits))) return fail(c, PIE_EINVAL, "pie_mask_kvpage: null argument");
+  for (int i = 0; i < n; ++i)
+    if (page_ids[i] < 0 || page_ids[i] >= c->p.n_kv_pages)
+      return fail(c, PIE_ERANGE, "page id %d at %d outside [0, %d)", page_ids[i], i, c->p.n_kv_pages);
+  for (int i = 0; i < n; ++i) c->page_mask[page_ids[i]] = (uint16_t)(visible_bits[i] & 0xFFFFu);
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_copy_kvpage(pie_ctx* c, const int32_t* src_pages, const int32_t* src_slots,
+                                      const int32_t* dst_pages, const int32_t* dst_slots, int32_t n) {
+  if (!c) return PIE_EINVAL;
+  if (n < 0 || (n > 0 && (!src_pages || !src_slots || !dst_pages || !dst_slots)))
+    return fail(c, PIE_EINVAL, "pie_copy_kvpage: null argument");
+  if (n == 0) return PIE_OK;
+  std::unordered_set<int64_t> src, dst;
+  src.reserve((size_t)n * 2);
+  dst.reserve((size_t)n * 2);
+  for (int i = 0; i < n; ++i) {
+    if (src_pages[i] < 0 || src_pages[i] >= c->p.n_kv_pages || dst_pages[i] < 0 || dst_pages[i] >= c->p.n_kv_pages)
+      return fail(c, PIE_ERANGE, "page id at %d outside [0, %d)", i, c->p.n_kv_pages);
+    if (src_slots[i] < 0 || src_slots[i] >= PAGE || dst_slots[i] < 0 || dst_slots[i] >= PAGE)
+      return fail(c, PIE_ERANGE, "slot at %d outside [0, %d)", i, PAGE);
+    src.insert((int64_t)src_pages[i] * PAGE + src_slots[i]);
+    if (!dst.insert((int64_t)dst_pages[i] * PAGE + dst_slots[i]).second)
+      return fail(c, PIE_ECONFLICT, "token (page %d, slot %d) is written twice by one copy", dst_pages[i], dst_slots[i]);
+  }
+  for (int64_t t : dst)
+    if (src.count(t)) return fail(c, PIE_ECONFLICT, "token (page %lld, slot %lld) is both read and written by one copy",
+                                  (long long)(t / PAGE), (long long)(t % PAGE));
+  const int32_t* arrs[4] = {src_pages, src_slots, dst_pages, dst_slots};
+  if ((size_t)n * 4 > c->ids_cap) {
+    (void)hipStreamSynchronize(c->stream);
+    if (c->ids_dev) (void)hipFree(c->ids_dev);
+    c->ids_dev = nullptr;
+    c->ids_cap = (size_t)n * 4;
+    HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&c->ids_dev), c->ids_cap * sizeof(int32_t)));
+  }
+  for (int k = 0; k < 4; ++k)
+    HIP_TRY(c, hipMemcpyAsync(c->ids_dev + (size_t)k * n, arrs[k], (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, launch_kv_token_copy(c->kv, c->kv_layer_elems, c->m.n_layers, c->ids_dev, c->ids_dev + n, c->ids_dev + 2 * (size_t)n,
+                                  c->ids_dev + 3 * (size_t)n, n, c->m.n_kv_heads, c->m.head_dim, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));  // ids_dev is reused by the next call
+  return PIE_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // batch deserialisation
 // ---------------------------------------------------------------------------------------------
@@ -343,6 +391,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   std::vector<int32_t> pos_from_embeds;  // positions recorded by embed_txt, when the batch names none
   if (!b->positions) pos_from_embeds.resize(T);
   std::vector<PrefillItem> pitems;
+  const size_t n_mask_given = b->mask_indptr ? (size_t)b->mask_indptr[R] : 0;
+  std::vector<uint32_t> extra_words;  // masks synthesised for requests that touch pages with token-level masks
   int rows_cap = 0;
   int64_t kv_bytes = 0, kv_bytes_dec = 0, flops = 0;
   const int64_t page_bytes = (int64_t)Hkv * 2 * PAGE * D * 2;
@@ -378,18 +428,44 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
       tok_slot[t] = j % PAGE;
     }
     const bool has_mask = b->mask_indptr && b->mask_indptr[r + 1] > b->mask_indptr[r];
-    if (has_mask) {
-      const int wpr = (L + 31) / 32;
-      if (b->mask_indptr[r + 1] - b->mask_indptr[r] != (int64_t)wpr * n_new)
-        return fail(c, PIE_EINVAL, "request %d: mask has %lld words, expected %lld", r,
-                    (long long)(b->mask_indptr[r + 1] - b->mask_indptr[r]), (long long)wpr * n_new);
+    const int wpr = (L + 31) / 32;
+    if (has_mask && b->mask_indptr[r + 1] - b->mask_indptr[r] != (int64_t)wpr * n_new)
+      return fail(c, PIE_EINVAL, "request %d: mask has %lld words, expected %lld", r,
+                  (long long)(b->mask_indptr[r + 1] - b->mask_indptr[r]), (long long)wpr * n_new);
+    // token-level page masks (mask_kvpage) in force on any page of the request: the request gets an explicit
+    // mask of its own, the call's mask (given or causal) ANDed with the pages' bits
+    bool page_masked = false;
+    for (int pg = 0; pg < n_pages && !page_masked; ++pg) page_masked = c->page_mask[b->page_ids[p0 + pg]] != 0xFFFFu;
+    const uint32_t* w = has_mask ? b->mask_words + b->mask_indptr[r] : nullptr;
+    if (page_masked) {
+      const size_t at = extra_words.size();
+      extra_words.resize(at + (size_t)wpr * n_new);
+      for (int k = 0; k < wpr; ++k) {
+        uint32_t pm = c->page_mask[b->page_ids[p0 + 2 * k]];
+        pm |= (2 * k + 1 < n_pages ? (uint32_t)c->page_mask[b->page_ids[p0 + 2 * k + 1]] : 0xFFFFu) << 16;
+        for (int i = 0; i < n_new; ++i) {
+          uint32_t base;
+          if (has_mask) {
+            base = w[(size_t)i * wpr + k];
+          } else {  // causal on logical order: keys up to index lim
+            const int lim = L - n_new + i, first = 32 * k;
+            base = lim >= first + 31 ? 0xFFFFFFFFu : (lim < first ? 0u : (1u << (lim - first + 1)) - 1u);
+          }
+          extra_words[at + (size_t)i * wpr + k] = base & pm;
+        }
+      }
+      q.wpr = wpr;
+      q.mask_off = (int64_t)n_mask_given + (int64_t)at;
+    } else if (has_mask) {
       q.wpr = wpr;
       q.mask_off = b->mask_indptr[r];
+    }
+    if (q.wpr > 0) {
       // a page is visited when any row has a visible key in it
+      const uint32_t* we = page_masked ? extra_words.data() + (q.mask_off - (int64_t)n_mask_given) : w;
       std::vector<uint32_t> any(wpr, 0u);
-      const uint32_t* w = b->mask_words + b->mask_indptr[r];
       for (int i = 0; i < n_new; ++i)
-        for (int k = 0; k < wpr; ++k) any[k] |= w[(size_t)i * wpr + k];
+        for (int k = 0; k < wpr; ++k) any[k] |= we[(size_t)i * wpr + k];
       for (int pg = 0; pg < n_pages; ++pg) {
         uint32_t bits = (any[pg >> 1] >> ((pg & 1) * 16)) & 0xFFFFu;
         int tail = L - pg * PAGE;
@@ -583,7 +659,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
       if (!ok) return fail(c, PIE_EINVAL, "internal: inconsistent decode plan for wave %zu", w);
     }
     for (const DecodeCol& dc : dcols)
-      if (dc.tok >= T || dc.hg < 0 || dc.hg >= G || (dc.tok >= 0 && dc.wpr > 0 && dc.mask_row + dc.wpr > (int64_t)b->mask_indptr[R]))
+      if (dc.tok >= T || dc.hg < 0 || dc.hg >= G || (dc.tok >= 0 && dc.wpr > 0 && dc.mask_row + dc.wpr > (int64_t)(n_mask_given + extra_words.size())))
         return fail(c, PIE_EINVAL, "internal: inconsistent decode column");
   }
   // partial rows a (decode request, kv head) has to merge: segment * rows_cap + the request's first column
@@ -623,8 +699,13 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   const size_t o_ts = blob.add(tok_slot.data(), (size_t)T * 4);
   const size_t o_vp = blob.add(visit_phys.data(), visit_phys.size() * 4, 8);
   const size_t o_vl = blob.add(visit_logical.data(), visit_logical.size() * 4, 8);
-  const size_t n_mask = b->mask_indptr ? (size_t)b->mask_indptr[R] : 0;
-  const size_t o_mw = blob.add(n_mask ? b->mask_words : nullptr, n_mask * 4, 4);
+  const size_t o_mw = blob.add(n_mask_given ? b->mask_words : nullptr, n_mask_given * 4, 0);
+  if (!extra_words.empty()) {  // directly behind the caller's words: one array for the kernels
+    const size_t at = blob.bytes.size();
+    blob.bytes.resize(at + extra_words.size() * 4);
+    std::memcpy(blob.bytes.data() + at, extra_words.data(), extra_words.size() * 4);
+  }
+  blob.bytes.resize(blob.bytes.size() + 4, 0);
   const size_t o_rq = blob.add(reqs.data(), reqs.size() * sizeof(ReqInfo));
   const size_t o_di = blob.add(dsegs.data(), dsegs.size() * sizeof(DecodeSeg), 16);
   const size_t o_ws = blob.add(dwaves.data(), dwaves.size() * sizeof(DecodeWave), 16);
