@@ -545,8 +545,12 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   if (M <= 0) return hipSuccess;
   if (M <= 32) return run_skinny<1, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   if (M <= 64) return run_skinny<2, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
-  if (M <= 128) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
-  if (M <= 256 && MODE != EPI_SWIGLU) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  // Very wide outputs (the LM head) give the tiled kernel at least one tile per CU even with a single row
+  // block; above 64 rows it beats streaming the weights past 4-8 row blocks per wave (measured at 128256 x 4096:
+  // 0.26 ms for up to 256 rows against 0.30 ms at 128 rows and 0.46 ms at 256 rows).
+  const bool wide = W.K % 128 == 0 && (W.NB + 7) / 8 >= n_cus && M > 64;
+  if (M <= 128 && !wide) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 256 && MODE != EPI_SWIGLU && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   if (W.K % 128 == 0) {
     const int tiles_n = (W.NB + 7) / 8;
     // A ragged last row block that would open one more round of tiles (a round = one tile per CU) costs a whole
