@@ -588,7 +588,7 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
       }
       attn_pv<D>(st, va, vb, pa, pb);
     };
-#define PIE_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+#define PIE_WAIT_VM(n) PIE_S_WAIT_VMCNT(n)
     // Step i: the scores of pair i+1 are issued to the matrix cores first, so they run under the softmax
     // arithmetic of pair i.  A stage is read in two consecutive steps (K, then V), the ring has four stages,
     // two pairs are in flight.
@@ -597,29 +597,29 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
     start_pair(st1, 1, m1);
     start_pair(st2, 2, m2);
     PIE_WAIT_VM(2 * IPW);
-    __syncthreads();
+    wg_barrier();
     f32x16 s_cur = scores(st0), s_next = s_cur;
     for (int p = 0; p < n_pairs; p += 4) {
       PIE_WAIT_VM(IPW);
-      __syncthreads();
+      wg_barrier();
       start_pair(st3, p + 3, m3);
       s_next = scores(st1);
       finish(st0, m0, s_cur);
       if (p + 1 >= n_pairs) break;
       PIE_WAIT_VM(IPW);
-      __syncthreads();
+      wg_barrier();
       start_pair(st0, p + 4, m0);
       s_cur = scores(st2);
       finish(st1, m1, s_next);
       if (p + 2 >= n_pairs) break;
       PIE_WAIT_VM(IPW);
-      __syncthreads();
+      wg_barrier();
       start_pair(st1, p + 5, m1);
       s_next = scores(st3);
       finish(st2, m2, s_cur);
       if (p + 3 >= n_pairs) break;
       PIE_WAIT_VM(IPW);
-      __syncthreads();
+      wg_barrier();
       start_pair(st2, p + 6, m2);
       s_cur = scores(st0);
       finish(st3, m3, s_next);

@@ -50,3 +50,18 @@ __device__ __forceinline__ float wave_max(float v) {
 __host__ __device__ __forceinline__ int64_t packed_tile_offset(int nb, int kb, int kblocks) {
   return ((int64_t)nb * kblocks + kb) * 512;  // in bf16 elements
 }
+
+// Workgroup barrier without the memory fence of __syncthreads().  The fence makes the compiler wait for every
+// outstanding memory operation (s_waitcnt vmcnt(0)) before the barrier, which empties a multi-stage pipeline of
+// direct-to-LDS copies at every step.  Callers wait explicitly (s_waitcnt vmcnt(n)) for the copies whose data
+// the other waves are about to read; LDS contents are otherwise only written by those copies.
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// s_waitcnt vmcnt(n) as a compiler builtin (not inline asm), so that the compiler's own wait-counter
+// bookkeeping knows which copies have landed and does not add a full wait before the next LDS read.
+// gfx9 encoding: vmcnt in bits [3:0] and [15:14]; expcnt [6:4] and lgkmcnt [11:8] left at "no wait".
+#define PIE_S_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | 0x0F70 | ((((n) >> 4) & 3) << 14))
