@@ -108,51 +108,67 @@ hipError_t launch_rmsnorm_f32(const float* x, const bf16_t* gain, bf16_t* out, i
 }
 
 // ---------------------------------------------------------------------------------------------
-// Rotary step + KV append.  qkv is [T, (Hq + 2 Hkv) * D] bf16.  One thread handles, for a query or
-// key head, the 8 pairs (c*8 + e, D/2 + c*8 + e); for a value head, 16 consecutive elements.
-// Angles are pos * theta^(-2i/D) evaluated in double (positions reach tens of thousands).
-// Rotated queries are written back in place; rotated keys and values go to the token's page slot.
+// Rotary step + KV append.  qkv is [T, (Hq + 2 Hkv) * D] bf16.  A rotary thread handles the 8 pairs
+// (c*8 + e, D/2 + c*8 + e) of `hpt` consecutive query/key heads of one token, so the 8 angles
+// pos * theta^(-2i/D), evaluated in double (positions reach tens of thousands), are computed once for all of
+// them; a value thread copies 16 consecutive elements.  Rotated queries are written back in place; rotated
+// keys and values go to the token's page slot.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ qkv, int T, int Hq, int Hkv, int D,
                                                           const int32_t* __restrict__ pos,
                                                           const int32_t* __restrict__ tok_page,
                                                           const int32_t* __restrict__ tok_slot,
                                                           const double* __restrict__ inv_freq,
-                                                          bf16_t* __restrict__ kv_layer) {
+                                                          bf16_t* __restrict__ kv_layer, int hpt) {
   const int cpt = D / 16;  // work pieces per head
-  const int heads = Hq + 2 * Hkv;
+  const int heads = Hq + 2 * Hkv, rot = Hq + Hkv;
+  const int groups = (rot + hpt - 1) / hpt;
+  const int64_t n_rot = (int64_t)T * groups * cpt, n_val = (int64_t)T * Hkv * cpt;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t total = (int64_t)T * heads * cpt;
-  if (idx >= total) return;
-  int c = (int)(idx % cpt);
-  int h = (int)((idx / cpt) % heads);
-  int t = (int)(idx / ((int64_t)cpt * heads));
-  bf16_t* row = qkv + (int64_t)t * heads * D + (int64_t)h * D;
-  const int page = tok_page[t], slot = tok_slot[t];
-  if (h < Hq + Hkv) {
-    Pack16 lo, hi, olo, ohi;
-    lo.u = *reinterpret_cast<const u32x4*>(row + c * 8);
-    hi.u = *reinterpret_cast<const u32x4*>(row + D / 2 + c * 8);
+  if (idx >= n_rot + n_val) return;
+  if (idx < n_rot) {
+    const int c = (int)(idx % cpt);
+    const int g = (int)((idx / cpt) % groups);
+    const int t = (int)(idx / ((int64_t)cpt * groups));
+    const int page = tok_page[t], slot = tok_slot[t];
     const double p = (double)pos[t];
+    float fc[8], fs[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       double sn, cs;
       sincos(p * inv_freq[c * 8 + e], &sn, &cs);
-      float a = bf16_bits_to_f32(lo.s[e]), b = bf16_bits_to_f32(hi.s[e]);
-      float fc = (float)cs, fs = (float)sn;
-      olo.h[e] = f32_to_bf16(a * fc - b * fs);
-      ohi.h[e] = f32_to_bf16(b * fc + a * fs);
+      fc[e] = (float)cs;
+      fs[e] = (float)sn;
     }
-    if (h < Hq) {
-      *reinterpret_cast<u32x4*>(row + c * 8) = olo.u;
-      *reinterpret_cast<u32x4*>(row + D / 2 + c * 8) = ohi.u;
-    } else {
-      bf16_t* blk = kv_layer + ((int64_t)page * Hkv + (h - Hq)) * (2 * PAGE * D);
-      *reinterpret_cast<u32x4*>(blk + k_elem_offset(slot, c * 8)) = olo.u;
-      *reinterpret_cast<u32x4*>(blk + k_elem_offset(slot, D / 2 + c * 8)) = ohi.u;
+    const int h1 = min(rot, (g + 1) * hpt);
+    for (int h = g * hpt; h < h1; ++h) {
+      bf16_t* row = qkv + (int64_t)t * heads * D + (int64_t)h * D;
+      Pack16 lo, hi, olo, ohi;
+      lo.u = *reinterpret_cast<const u32x4*>(row + c * 8);
+      hi.u = *reinterpret_cast<const u32x4*>(row + D / 2 + c * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float a = bf16_bits_to_f32(lo.s[e]), b = bf16_bits_to_f32(hi.s[e]);
+        olo.h[e] = f32_to_bf16(a * fc[e] - b * fs[e]);
+        ohi.h[e] = f32_to_bf16(b * fc[e] + a * fs[e]);
+      }
+      if (h < Hq) {
+        *reinterpret_cast<u32x4*>(row + c * 8) = olo.u;
+        *reinterpret_cast<u32x4*>(row + D / 2 + c * 8) = ohi.u;
+      } else {
+        bf16_t* blk = kv_layer + ((int64_t)page * Hkv + (h - Hq)) * (2 * PAGE * D);
+        *reinterpret_cast<u32x4*>(blk + k_elem_offset(slot, c * 8)) = olo.u;
+        *reinterpret_cast<u32x4*>(blk + k_elem_offset(slot, D / 2 + c * 8)) = ohi.u;
+      }
     }
   } else {
-    bf16_t* blk = kv_layer + ((int64_t)page * Hkv + (h - Hq - Hkv)) * (2 * PAGE * D);
+    idx -= n_rot;
+    const int c = (int)(idx % cpt);
+    const int hv = (int)((idx / cpt) % Hkv);
+    const int t = (int)(idx / ((int64_t)cpt * Hkv));
+    const bf16_t* row = qkv + (int64_t)t * heads * D + (int64_t)(rot + hv) * D;
+    bf16_t* blk = kv_layer + ((int64_t)tok_page[t] * Hkv + hv) * (2 * PAGE * D);
+    const int slot = tok_slot[t];
     Pack16 a, b;
     a.u = *reinterpret_cast<const u32x4*>(row + c * 16);
     b.u = *reinterpret_cast<const u32x4*>(row + c * 16 + 8);
@@ -167,10 +183,14 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
 
 hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const int32_t* pos, const int32_t* tok_page,
                               const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, hipStream_t s) {
-  int64_t total = (int64_t)T * (Hq + 2 * Hkv) * (D / 16);
+  // few tokens: one head per thread keeps enough threads in flight; many tokens: share the angles of a token
+  // across 8 heads (the double-precision sincos dominates the kernel otherwise)
+  const int hpt = T >= 1024 ? 8 : 1;
+  const int groups = (Hq + Hkv + hpt - 1) / hpt;
+  int64_t total = (int64_t)T * (groups + Hkv) * (D / 16);
   if (total <= 0) return hipSuccess;
   rope_append_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(qkv, T, Hq, Hkv, D, pos, tok_page,
-                                                                                   tok_slot, inv_freq, kv_layer);
+                                                                                   tok_slot, inv_freq, kv_layer, hpt);
   return hipGetLastError();
 }
 

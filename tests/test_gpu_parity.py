@@ -128,13 +128,13 @@ def test_ragged_mixed_batch(head_dim, n_q, n_kv):
 
 
 @pytest.mark.parametrize("hidden,mlp,n_q,n_kv,T_prefill", [(256, 320, 6, 2, 290), (192, 512, 4, 2, 600),
-                                                          (256, 512, 4, 4, 513)])
+                                                          (256, 512, 4, 4, 513), (256, 256, 8, 2, 1100)])
 def test_large_batches_on_small_models(hidden, mlp, n_q, n_kv, T_prefill):
     """More than 256 rows: the tiled GEMM kernels (both the asynchronous-copy one and the one for contraction
     lengths that are not a multiple of 128) on ragged row counts and output widths that do not fill a tile."""
     m = small_model(64, n_q, n_kv, hidden=hidden, mlp=mlp, vocab=512)
     reqs = [W.RequestSpec(T_prefill, 21), W.RequestSpec(1, 50), W.RequestSpec(1, 0), W.RequestSpec(3, 10)]
-    w = W.build_workload("large", m, reqs, n_kv_pages=64, seed=300 + hidden + mlp, std=0.05)
+    w = W.build_workload("large", m, reqs, n_kv_pages=128, seed=300 + hidden + mlp, std=0.05)
     compare_layer(w, what=f"T={w.batch.n_tokens} H{hidden} I{mlp} {n_q}/{n_kv}")
 
 
