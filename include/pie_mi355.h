@@ -177,6 +177,15 @@ pie_status pie_forward_all(pie_ctx* ctx, const pie_batch* batch);
 /* Convenience: pie_batch_create + pie_forward + pie_batch_destroy (synchronises the stream). */
 pie_status pie_forward_host(pie_ctx* ctx, int32_t layer, const pie_forward_batch* batch, int32_t validate);
 
+/* forward and sampling in one call (the paper measures the cost of sampling that is not pipelined behind the
+ * forward pass: Evaluation, overhead breakdown): pie_forward_all over the batch, then get_next_dist on the
+ * output Embeds of the batch's token rows rows[0..n) (host int32; each must name an output Embed), all enqueued
+ * back to back on the context's stream without any host synchronisation.  Arguments as for pie_get_next_dist;
+ * all of them are checked before anything is enqueued.  (The two separate calls are stream-ordered in the same
+ * way; this entry point only saves the caller the id bookkeeping.) */
+pie_status pie_forward_dist(pie_ctx* ctx, const pie_batch* batch, const int32_t* rows, int32_t n, int32_t top_k,
+                            float temperature, int32_t* out_ids, float* out_probs);
+
 /* `get_next_dist(q, emb) -> Dist` for n Embeds (Table 1; Sample API): final RMSNorm when the head
  * has a gain, LM head in fp32 logits, softmax(logits / temperature) over the whole vocabulary,
  * truncated to the top_k entries (Sample API: top-K truncation, K configurable, default 256).

@@ -83,6 +83,7 @@ def load_library():
         "pie_copy_kvpage": [vp, vp, vp, vp, vp, i32],
         "pie_forward_host": [vp, i32, C.POINTER(ForwardBatchC), i32],
         "pie_get_next_dist": [vp, vp, i32, i32, f32, vp, vp],
+        "pie_forward_dist": [vp, vp, vp, i32, i32, f32, vp, vp],
         "pie_synchronize": [vp],
         "pie_read_tap": [vp, i32, vp, i64],
         "pie_set_stage_timing": [vp, i32],
@@ -286,6 +287,16 @@ class Pie:
         ids = _i32(embed_ids)
         self._check(self.lib.pie_get_next_dist(self.ctx, _ptr(ids), len(ids), top_k, float(temperature),
                                                C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_probs.data_ptr())))
+
+    def forward_dist(self, batch: PieBatch, rows, top_k: int, temperature: float = 1.0):
+        r = _i32(rows)
+        oi = torch.empty((len(r), top_k), dtype=torch.int32, device=self.device)
+        op = torch.empty((len(r), top_k), dtype=torch.float32, device=self.device)
+        torch.cuda.synchronize(self.device)
+        self._check(self.lib.pie_forward_dist(self.ctx, batch.handle, _ptr(r), len(r), top_k, float(temperature),
+                                              C.c_void_p(oi.data_ptr()), C.c_void_p(op.data_ptr())))
+        self.synchronize()
+        return oi.cpu().numpy(), op.cpu().numpy()
 
     def get_next_dist(self, embed_ids, top_k: int, temperature: float = 1.0):
         n = len(embed_ids)

@@ -70,6 +70,7 @@ struct PrefillItem { int32_t r, qb; };           // query block qb (32 tokens) o
 
 struct pie_batch {
   int32_t R = 0, T = 0;
+  std::vector<int32_t> out_ids_host;  // host copy of the output Embed ids (pie_forward_dist)
   void* dev_blob = nullptr;  // single allocation holding every array below
   int32_t *in_ids = nullptr, *out_ids = nullptr, *pos = nullptr, *tok_page = nullptr, *tok_slot = nullptr;
   int32_t *visit_phys = nullptr, *visit_logical = nullptr;

@@ -679,6 +679,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
 
   pie_batch* pb = new pie_batch();
   pb->R = R; pb->T = T;
+  pb->out_ids_host.assign(b->out_embed_ids, b->out_embed_ids + T);
   pb->n_dsegs = (int32_t)dsegs.size();
   pb->n_dwaves = (int32_t)dwaves.size();
   pb->dslots = dslots;
@@ -880,16 +881,24 @@ extern "C" pie_status pie_forward_host(pie_ctx* c, int32_t layer, const pie_forw
 // ---------------------------------------------------------------------------------------------
 // get_next_dist
 // ---------------------------------------------------------------------------------------------
-extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, int32_t n, int32_t top_k,
-                                        float temperature, int32_t* out_ids, float* out_probs) {
-  if (!c) return PIE_EINVAL;
-  if (!embed_ids || n <= 0) return fail(c, PIE_EINVAL, "pie_get_next_dist: null ids or n <= 0");
+// Argument checks of get_next_dist, everything but the ids themselves.
+static pie_status check_dist_args(pie_ctx* c, const void* ids, int32_t n, int32_t top_k, float temperature,
+                                  const void* out_ids, const void* out_probs) {
+  if (!ids || n <= 0) return fail(c, PIE_EINVAL, "get_next_dist: null ids or n <= 0");
   if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(c, PIE_EINVAL, "temperature must be positive and finite");
-  if (!c->head_loaded) return fail(c, PIE_EINVAL, "pie_get_next_dist: no LM head loaded");
+  if (!c->head_loaded) return fail(c, PIE_EINVAL, "get_next_dist: no LM head loaded");
   if (n > c->p.max_dist_rows) return fail(c, PIE_EBATCH, "%d rows exceed max_dist_rows %d", n, c->p.max_dist_rows);
   if (top_k <= 0 || top_k > c->p.max_top_k || top_k > c->m.vocab)
     return fail(c, PIE_ERANGE, "top_k %d outside [1, min(max_top_k %d, vocab %d)]", top_k, c->p.max_top_k, c->m.vocab);
-  if (!out_ids || !out_probs) return fail(c, PIE_EINVAL, "pie_get_next_dist: null output");
+  if (!out_ids || !out_probs) return fail(c, PIE_EINVAL, "get_next_dist: null output");
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, int32_t n, int32_t top_k,
+                                        float temperature, int32_t* out_ids, float* out_probs) {
+  if (!c) return PIE_EINVAL;
+  pie_status chk = check_dist_args(c, embed_ids, n, top_k, temperature, out_ids, out_probs);
+  if (chk != PIE_OK) return chk;
   for (int i = 0; i < n; ++i)
     if (embed_ids[i] < 0 || embed_ids[i] >= c->p.n_embeds) return fail(c, PIE_ERANGE, "embed id %d at %d outside [0, %d)", embed_ids[i], i, c->p.n_embeds);
   const int H = c->m.hidden, V = c->m.vocab;
@@ -913,6 +922,24 @@ extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, in
   tm.end(PIE_STAGE_TOPK);
   c->last_dist_n = n;
   return PIE_OK;
+}
+
+extern "C" pie_status pie_forward_dist(pie_ctx* c, const pie_batch* b, const int32_t* rows, int32_t n, int32_t top_k,
+                                       float temperature, int32_t* out_ids, float* out_probs) {
+  if (!c) return PIE_EINVAL;
+  if (!b) return fail(c, PIE_EINVAL, "pie_forward_dist: null batch");
+  // every argument is checked before anything is enqueued
+  pie_status st = check_dist_args(c, rows, n, top_k, temperature, out_ids, out_probs);
+  if (st != PIE_OK) return st;
+  std::vector<int32_t> ids(n);
+  for (int i = 0; i < n; ++i) {
+    if (rows[i] < 0 || rows[i] >= b->T) return fail(c, PIE_ERANGE, "row %d at %d outside [0, %d)", rows[i], i, b->T);
+    ids[i] = b->out_ids_host[rows[i]];
+    if (ids[i] < 0) return fail(c, PIE_EINVAL, "row %d stores no output Embed to take a distribution from", rows[i]);
+  }
+  st = pie_forward_all(c, b);
+  if (st != PIE_OK) return st;
+  return pie_get_next_dist(c, ids.data(), n, top_k, temperature, out_ids, out_probs);
 }
 
 extern "C" pie_status pie_synchronize(pie_ctx* c) {

@@ -205,6 +205,32 @@ def test_autoregressive_loop_follows_the_oracle():
         assert_bf16_close(v, ov, f"loop layer {l} V", ulps=4, frac=1.0)
 
 
+def test_forward_dist_equals_forward_then_get_next_dist():
+    from paper_2510_24051_amd import PieError
+    dw = W.deep_tiny(n_layers=2)
+    w, b = dw.base, dw.base.batch
+    rows = w.dist_rows
+    ctx = make_deep_ctx(dw)
+    ctx.embed_txt(dw.token_ids, b.positions, b.in_embed_ids)
+    pb = ctx.batch_create(clone_batch(b, positions=None))
+    ids1, p1 = ctx.forward_dist(pb, rows, w.top_k, 0.7)
+    ctx2 = make_deep_ctx(dw)
+    ctx2.embed_txt(dw.token_ids, b.positions, b.in_embed_ids)
+    pb2 = ctx2.batch_create(clone_batch(b, positions=None))
+    ctx2.forward_all(pb2)
+    ids2, p2 = ctx2.get_next_dist(b.out_embed_ids[rows], w.top_k, 0.7)
+    assert np.array_equal(ids1, ids2) and np.array_equal(p1, p2)
+    # a row that stores no output Embed has nothing to take a distribution from; bad arguments are caught
+    # before anything runs
+    b3 = clone_batch(b, positions=None, out_embed_ids=b.out_embed_ids.copy())
+    b3.out_embed_ids[rows[0]] = -1
+    pb3 = ctx.batch_create(b3)
+    for bad in (lambda: ctx.forward_dist(pb3, rows, w.top_k), lambda: ctx.forward_dist(pb, [b.n_tokens], 4),
+                lambda: ctx.forward_dist(pb, rows, 0), lambda: ctx.forward_dist(pb, rows, 4, temperature=0.0)):
+        with pytest.raises(PieError):
+            bad()
+
+
 def test_model_error_codes():
     from paper_2510_24051_amd import PieError
     dw = W.deep_tiny(n_layers=2)
