@@ -31,6 +31,9 @@ Parity pins (tests/test_oracle_*.py, all CPU):
   whole layer         torch CPU expression of a textbook Llama layer on one contiguous request
   softmax / top-k     torch.softmax + torch.topk, k=V sums to 1, shift invariance
   embed_txt           one-hot matrix product, positions recorded with the Embed
+  adapters            a torch CPU layer with the merged weights W + scale * B A; zero B or scale is a
+                      no-op; a request without adapter equals the plain call; two adapters in one
+                      batch equal each request run alone
   mask_kvpage         equals the same call with the masked tokens cleared in an explicit bitmap;
                       all-ones mask is a no-op; a fully masked page equals an omitted page
   copy_kvpage         a request over token-wise copied pages equals the request over the originals;
@@ -211,9 +214,22 @@ def _maybe_round(x: np.ndarray, on: bool) -> np.ndarray:
     return bf16_round(x) if on else x
 
 
+PROJECTIONS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
+
+
+def _lora_delta(adapter, name: str, x: np.ndarray) -> np.ndarray:
+    """Low-rank update of one projection for the rows x [n, in]: scale * (x A^T) B^T, or 0 when the adapter
+    has no pair for this projection.  `adapter` maps projection names to (A bits [r, in], B bits [out, r],
+    scale)."""
+    if adapter is None or name not in adapter:
+        return 0.0
+    a_bits, b_bits, scale = adapter[name]
+    return float(scale) * ((x @ bf16_decode(a_bits).T) @ bf16_decode(b_bits).T)
+
+
 def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional[Sequence[int]] = None,
             round_intermediates: bool = False, write_embeds: bool = True,
-            x_in: Optional[np.ndarray] = None) -> ForwardResult:
+            x_in: Optional[np.ndarray] = None, adapters=None, adapter_ids=None) -> ForwardResult:
     """One decoder layer over a batch of `forward` commands (Forward API; Table 1 `forward`).
 
     `model`   : hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, page_size, rms_eps, rope_theta
@@ -228,6 +244,11 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
                 the layers after the first, whose input is the previous layer's output).
     `batch.positions` may be None: the positions are then those recorded with the input Embeds by
     `embed_txt` (Forward API: the call works on the sequence positions associated with its resources).
+    `adapters`, `adapter_ids`: `forward_with_adapter` (Forward API): request r uses the LoRA adapter
+                `adapters[adapter_ids[r]]` (a dict projection name -> (A bits [rank, in], B bits [out, rank],
+                scale); -1 = none): every projection that has a pair computes W x + scale * B (A x).  With
+                `round_intermediates` q, k and v are rounded to bf16 once as projected and once more after the
+                update is added; the update itself and the gate/up sums stay wide.
 
     Order of effects inside one call: every input Embed is read first; every K/V append lands
     before any attention read; output Embeds are written last.  New token i of a request sits
@@ -259,8 +280,21 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
         x_all = np.asarray(x_in, dtype=np.float64)
         assert x_all.shape == (T, H)
     xn_all = _maybe_round(rmsnorm(x_all, g1, model.rms_eps), rnd)
-    k_all = _maybe_round(xn_all @ Wk.T, rnd).reshape(T, Hkv, D)
-    v_all = _maybe_round(xn_all @ Wv.T, rnd).reshape(T, Hkv, D)
+    k_all = _maybe_round(xn_all @ Wk.T, rnd)
+    v_all = _maybe_round(xn_all @ Wv.T, rnd)
+
+    def adapter_of(r):
+        if adapters is None or adapter_ids is None or int(adapter_ids[r]) < 0:
+            return None
+        return adapters[int(adapter_ids[r])]
+    for r in range(R):
+        ad = adapter_of(r)
+        if ad is not None:
+            t0, t1 = tok_indptr[r], tok_indptr[r + 1]
+            k_all[t0:t1] = _maybe_round(k_all[t0:t1] + _lora_delta(ad, "wk", xn_all[t0:t1]), rnd)
+            v_all[t0:t1] = _maybe_round(v_all[t0:t1] + _lora_delta(ad, "wv", xn_all[t0:t1]), rnd)
+    k_all = k_all.reshape(T, Hkv, D)
+    v_all = v_all.reshape(T, Hkv, D)
     # 4: rotary step on K with the caller's positions
     k_all = rope(k_all, positions, model.rope_theta)
     # 5: append (bf16 storage) - all appends of the batch precede every attention read
@@ -288,7 +322,10 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
         n_new, L = t1 - t0, int(kv_len[r])
         i_new = t - t0
         # 3-4 for the queries of the selected tokens
-        q = _maybe_round(xn_all[t] @ Wq.T, rnd).reshape(len(t), Hq, D)
+        q = _maybe_round(xn_all[t] @ Wq.T, rnd)
+        if adapter_of(r) is not None:
+            q = _maybe_round(q + _lora_delta(adapter_of(r), "wq", xn_all[t]), rnd)
+        q = q.reshape(len(t), Hq, D)
         q = _maybe_round(rope(q, positions[t], model.rope_theta), rnd)
         # 6: gather logical KV [0, L) through the page table, build the allowed matrix
         pages_r = page_ids[page_indptr[r]:page_indptr[r + 1]]
@@ -313,11 +350,21 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
 
     # 7-8: output projection + residual, second norm, SwiGLU MLP + residual
     Wo = bf16_decode(weights.wo)
-    h = x_all[rows] + o_out.reshape(len(rows), Hq * D) @ Wo.T
+    o_flat = o_out.reshape(len(rows), Hq * D)
+    h = x_all[rows] + o_flat @ Wo.T
+    sel_of = {int(r): np.nonzero(req_of == r)[0] for r in np.unique(req_of) if adapter_of(r) is not None}
+    for r, sel in sel_of.items():
+        h[sel] = h[sel] + _lora_delta(adapter_of(r), "wo", o_flat[sel])
     hn = _maybe_round(rmsnorm(h, g2, model.rms_eps), rnd)
     Wg, Wu, Wd = bf16_decode(weights.wgate), bf16_decode(weights.wup), bf16_decode(weights.wdown)
-    act = _maybe_round(silu(hn @ Wg.T) * (hn @ Wu.T), rnd)
+    gate, up = hn @ Wg.T, hn @ Wu.T
+    for r, sel in sel_of.items():
+        gate[sel] = gate[sel] + _lora_delta(adapter_of(r), "wgate", hn[sel])
+        up[sel] = up[sel] + _lora_delta(adapter_of(r), "wup", hn[sel])
+    act = _maybe_round(silu(gate) * up, rnd)
     y = h + act @ Wd.T
+    for r, sel in sel_of.items():
+        y[sel] = y[sel] + _lora_delta(adapter_of(r), "wdown", act[sel])
 
     # 9: store output Embeds (bf16) for rows that name one
     if write_embeds:
@@ -346,20 +393,23 @@ def embed_txt(table_bits: np.ndarray, token_ids, positions, emb: EmbedPool, embe
 
 
 def forward_model(model, layers, kvs, emb: EmbedPool, batch, *, rows: Optional[Sequence[int]] = None,
-                  round_intermediates: bool = False):
+                  round_intermediates: bool = False, adapters=None, adapter_ids=None):
     """The `forward` call through the whole model (Forward API: the core Transformer forward pass):
     layer l reads and appends to its own KvPage pool `kvs[l]` with the same page table, its input is
     the output of layer l-1 (kept wide: only Embeds, KvPages and weights are bf16 storage), the
     first layer reads the input Embeds and the last one writes the output Embeds.  `rows` restricts
     the last layer's per-token outputs; every earlier layer is computed for all tokens.
+    `adapters[a]` is a list with one projection dict per layer (see `forward`).
     Returns the list of per-layer results."""
     assert len(layers) == len(kvs) and len(layers) >= 1
     results = []
     x = None
     for l, (w, kv) in enumerate(zip(layers, kvs)):
         last = l == len(layers) - 1
+        ad_l = None if adapters is None else {a: per_layer[l] for a, per_layer in adapters.items()}
         res = forward(model, w, kv, emb, batch, rows=rows if last else None,
-                      round_intermediates=round_intermediates, write_embeds=last, x_in=x)
+                      round_intermediates=round_intermediates, write_embeds=last, x_in=x,
+                      adapters=ad_l, adapter_ids=adapter_ids)
         results.append(res)
         x = res.y
     return results

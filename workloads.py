@@ -121,7 +121,7 @@ class Workload:
 # ------------------------------------------------------------------------------------------
 
 STREAM_WEIGHTS, STREAM_EMBEDS, STREAM_KV, STREAM_PAGES, STREAM_CTX, STREAM_MASK, STREAM_HEAD = 1, 2, 3, 4, 5, 6, 7
-STREAM_TABLE, STREAM_TOKENS = 8, 9
+STREAM_TABLE, STREAM_TOKENS, STREAM_ADAPTER = 8, 9, 10
 LAYER_STREAM_STEP = 100  # layer l > 0 draws its weights / prior KV from stream + l * LAYER_STREAM_STEP
 
 
@@ -177,6 +177,28 @@ def make_layer_weights(model: ModelDesc, seed: int, std: float = 0.02, resid_std
         wup=normal_bf16(rng, (I, H), std),
         wdown=normal_bf16(rng, (H, I), rs),
     )
+
+
+PROJ_SHAPES = {  # projection name -> (out, in) as functions of the model
+    "wq": lambda m: (m.n_q_heads * m.head_dim, m.hidden), "wk": lambda m: (m.n_kv_heads * m.head_dim, m.hidden),
+    "wv": lambda m: (m.n_kv_heads * m.head_dim, m.hidden), "wo": lambda m: (m.hidden, m.n_q_heads * m.head_dim),
+    "wgate": lambda m: (m.mlp_dim, m.hidden), "wup": lambda m: (m.mlp_dim, m.hidden),
+    "wdown": lambda m: (m.hidden, m.mlp_dim)}
+
+
+def make_adapter(model: ModelDesc, seed: int, index: int, rank: int, projections=("wq", "wk", "wv", "wo"),
+                 scale: float = 2.0, std: float = 0.02, n_layers: Optional[int] = None):
+    """A LoRA adapter: per layer a dict projection -> (A bits [rank, in] ~N(0, std), B bits [out, rank]
+    ~N(0, std), scale).  (Trained adapters are not available; a zero-initialised B would change nothing.)"""
+    layers = []
+    for l in range(n_layers or model.n_layers):
+        rng = rng_for(seed, STREAM_ADAPTER + 1000 * index + l * LAYER_STREAM_STEP)
+        d = {}
+        for name in projections:
+            out, inn = PROJ_SHAPES[name](model)
+            d[name] = (normal_bf16(rng, (rank, inn), std), normal_bf16(rng, (out, rank), std), float(scale))
+        layers.append(d)
+    return layers
 
 
 def make_head_weights(model: ModelDesc, seed: int, std: float = 0.02, gain_std: float = 0.02,
