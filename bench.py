@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--top-k", type=int, default=256)
+    ap.add_argument("--lora-rank", type=int, default=0,
+                    help="give every request one of two synthetic LoRA adapters of this rank on q, k, v, o "
+                         "(forward_with_adapter); 0 = plain forward")
     ap.add_argument("--layers", type=int, default=1,
                     help="run the batch through this many layers (pie_forward_all; every layer gets the same "
                          "synthetic weights and prior KV values); the default 1 is the per-layer metric")
@@ -74,7 +77,12 @@ def main():
 
     NL = max(1, args.layers)
     ctx = Pie(w.model, w.n_kv_pages, w.n_embeds, max_batch_tokens=T, max_batch_requests=b.n_requests,
-              max_top_k=max(256, w.top_k), max_dist_rows=max(n_dist, 1), n_layers=NL)
+              max_top_k=max(256, w.top_k), max_dist_rows=max(n_dist, 1), n_layers=NL,
+              max_adapters=2 if args.lora_rank > 0 else 0, max_lora_rank=max(args.lora_rank, 0))
+    if args.lora_rank > 0:
+        for a in range(2):
+            ctx.load_adapter(a, W.make_adapter(w.model, 2000, a, rank=args.lora_rank, n_layers=NL))
+        b.adapter_ids = (np.arange(b.n_requests) % 2).astype(np.int32)
     ctx.load_head(w.head)
     ctx.embed_write(b.in_embed_ids, w.embed_bits)
     for l in range(NL):
@@ -229,7 +237,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": desc, "tokens_per_step": T, "requests": int(b.n_requests), "dist_rows": n_dist,
-                   "top_k": int(w.top_k), "layers": NL,
+                   "top_k": int(w.top_k), "layers": NL, "lora_rank": int(args.lora_rank),
                    "step": ("pie_forward (1 layer)" if NL == 1 else f"pie_forward_all ({NL} layers)") + " + pie_get_next_dist"},
         "forward_only": {"tokens_per_s": round(T / (fwd_ms * 1e-3), 1), "ms": round(fwd_ms, 5)},
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},

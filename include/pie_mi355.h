@@ -54,6 +54,7 @@ typedef struct {
  * Embed and KvPage resources physically located in the inference layer). */
 typedef struct {
   int32_t n_kv_pages, n_embeds, max_batch_tokens, max_batch_requests, max_top_k, max_dist_rows;
+  int32_t max_adapters, max_lora_rank; /* LoRA adapters (pie_load_adapter); both 0 = none */
 } pie_pool_desc;
 
 /* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (NULL = default
@@ -72,6 +73,17 @@ pie_status pie_load_layer(pie_ctx* ctx, int32_t layer, const void* g1, const voi
                           const void* wdown);
 /* g_final may be NULL: get_next_dist then applies no final norm. */
 pie_status pie_load_head(pie_ctx* ctx, const void* g_final, const void* w_lm /* [vocab, hidden] */);
+
+/* `forward_with_adapter` (Forward API: a call may name LoRA adapters to serve fine-tuned models).  An adapter is,
+ * per layer and per projection, an optional pair A [rank, in], B [out, rank] (dev bf16, row-major, copied by the
+ * call) and a scale: requests of a batch that name the adapter (pie_forward_batch.adapter_ids) compute
+ * W x + scale * B (A x) for that projection.  rank = 0 or A = B = NULL removes the pair.  Projections: the seven
+ * linear maps of the layer.  Errors: PIE_EINVAL (null with rank > 0, context created without adapters),
+ * PIE_ERANGE (adapter, layer, projection or rank out of range), PIE_ENOMEM, PIE_EHIP.  Synchronises the stream. */
+enum { PIE_PROJ_Q = 0, PIE_PROJ_K = 1, PIE_PROJ_V = 2, PIE_PROJ_O = 3, PIE_PROJ_GATE = 4, PIE_PROJ_UP = 5,
+       PIE_PROJ_DOWN = 6, PIE_N_PROJ = 7 };
+pie_status pie_load_adapter(pie_ctx* ctx, int32_t adapter, int32_t layer, int32_t projection, int32_t rank,
+                            float scale, const void* A, const void* B);
 
 /* Embedding table for `embed_txt`: dev bf16 [vocab, hidden], copied into library storage (the caller may
  * free its tensor afterwards).  Errors: PIE_EINVAL (null, context without vocab), PIE_ENOMEM, PIE_EHIP. */
@@ -136,6 +148,8 @@ pie_status pie_copy_kvpage(pie_ctx* ctx, const int32_t* src_pages, const int32_t
  *     NULL, and a request with an empty word range has its mask inferred: causal on logical
  *     order (token i sees j <= kv_len - n_new + i).  A row with no visible key outputs zeros.
  *
+ *   adapter_ids[r]: the LoRA adapter request r runs with (`forward_with_adapter`), see pie_load_adapter
+ *
  * Effects of a call, in order: read all input Embeds; append every new K/V; attend; write output
  * Embeds.  Two tokens of one batch must not write the same (page, slot) (vertical batching is
  * only done when calls do not conflict); checked when validate != 0.
@@ -151,6 +165,7 @@ typedef struct {
   const int32_t* kv_len;        /* [R] */
   const int64_t* mask_indptr;   /* [R+1] or NULL */
   const uint32_t* mask_words;   /* [mask_indptr[R]] or NULL */
+  const int32_t* adapter_ids;   /* [R] LoRA adapter of each request, -1 = none; NULL = no request has one */
 } pie_forward_batch;
 
 /* Deserialise a batch: check shapes and id ranges on the host (validate != 0 adds the

@@ -36,14 +36,14 @@ class ModelDescC(C.Structure):
 
 class PoolDescC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_kv_pages", "n_embeds", "max_batch_tokens", "max_batch_requests",
-                                          "max_top_k", "max_dist_rows")]
+                                          "max_top_k", "max_dist_rows", "max_adapters", "max_lora_rank")]
 
 
 class ForwardBatchC(C.Structure):
     _fields_ = [("n_requests", C.c_int32), ("n_tokens", C.c_int32), ("tok_indptr", C.c_void_p),
                 ("in_embed_ids", C.c_void_p), ("out_embed_ids", C.c_void_p), ("positions", C.c_void_p),
                 ("page_indptr", C.c_void_p), ("page_ids", C.c_void_p), ("kv_len", C.c_void_p),
-                ("mask_indptr", C.c_void_p), ("mask_words", C.c_void_p)]
+                ("mask_indptr", C.c_void_p), ("mask_words", C.c_void_p), ("adapter_ids", C.c_void_p)]
 
 
 def lib_path() -> str:
@@ -78,6 +78,7 @@ def load_library():
         "pie_forward": [vp, i32, vp],
         "pie_forward_all": [vp, vp],
         "pie_load_embedding": [vp, vp],
+        "pie_load_adapter": [vp, i32, i32, i32, i32, f32, vp, vp],
         "pie_embed_txt": [vp, vp, vp, i32, vp],
         "pie_mask_kvpage": [vp, vp, vp, i32],
         "pie_copy_kvpage": [vp, vp, vp, vp, vp, i32],
@@ -136,7 +137,7 @@ class Pie:
 
     def __init__(self, model, n_kv_pages: int, n_embeds: int, max_batch_tokens: int, max_batch_requests: int,
                  max_top_k: int = 256, max_dist_rows: int = 0, n_layers: int = 1, device: str = "cuda:0",
-                 stream: Optional[torch.cuda.Stream] = None):
+                 stream: Optional[torch.cuda.Stream] = None, max_adapters: int = 0, max_lora_rank: int = 0):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
@@ -146,7 +147,8 @@ class Pie:
         self.model = model
         md = ModelDescC(model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.mlp_dim, model.vocab,
                         model.page_size, model.rms_eps, model.rope_theta, n_layers)
-        pd = PoolDescC(n_kv_pages, n_embeds, max_batch_tokens, max_batch_requests, max_top_k, max_dist_rows)
+        pd = PoolDescC(n_kv_pages, n_embeds, max_batch_tokens, max_batch_requests, max_top_k, max_dist_rows,
+                       max_adapters, max_lora_rank)
         h = C.c_void_p()
         st = self.lib.pie_create(C.byref(md), C.byref(pd), C.c_void_p(self.stream.cuda_stream), C.byref(h))
         if st != 0:
@@ -196,6 +198,17 @@ class Pie:
         t = self._dev_bf16(table_bits)
         torch.cuda.synchronize(self.device)
         self._check(self.lib.pie_load_embedding(self.ctx, C.c_void_p(t.data_ptr())))
+
+    PROJECTIONS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
+
+    def load_adapter(self, adapter: int, layers):
+        """`layers[l]` maps projection names to (A bits [rank, in], B bits [out, rank], scale)."""
+        for l, d in enumerate(layers):
+            for name, (a_bits, b_bits, scale) in d.items():
+                a, b = self._dev_bf16(a_bits), self._dev_bf16(b_bits)
+                torch.cuda.synchronize(self.device)
+                self._check(self.lib.pie_load_adapter(self.ctx, adapter, l, self.PROJECTIONS.index(name), a.shape[0],
+                                                      float(scale), C.c_void_p(a.data_ptr()), C.c_void_p(b.data_ptr())))
 
     # ---- resources ----
     def embed_txt(self, token_ids, positions, embed_ids):
@@ -260,10 +273,12 @@ class Pie:
                     page_indptr=_i32(b.page_indptr), page_ids=_i32(b.page_ids), kv_len=_i32(b.kv_len))
         mi = None if b.mask_indptr is None else np.ascontiguousarray(b.mask_indptr, dtype=np.int64)
         mw = None if b.mask_words is None else np.ascontiguousarray(b.mask_words, dtype=np.uint32)
+        ad = getattr(b, "adapter_ids", None)
+        ad = None if ad is None else _i32(ad)
         fb = ForwardBatchC(int(b.n_requests), int(b.n_tokens), _ptr(arrs["tok_indptr"]), _ptr(arrs["in_embed_ids"]),
                            _ptr(arrs["out_embed_ids"]), _ptr(arrs["positions"]), _ptr(arrs["page_indptr"]),
-                           _ptr(arrs["page_ids"]), _ptr(arrs["kv_len"]), _ptr(mi), _ptr(mw))
-        return fb, (arrs, mi, mw)
+                           _ptr(arrs["page_ids"]), _ptr(arrs["kv_len"]), _ptr(mi), _ptr(mw), _ptr(ad))
+        return fb, (arrs, mi, mw, ad)
 
     def batch_create(self, batch, validate: bool = True) -> PieBatch:
         fb, keep = self._batch_struct(batch)

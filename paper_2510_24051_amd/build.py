@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpie_mi355.so")
-SOURCES = ["pie_ctx.hip", "gemm.hip", "attention.hip", "elementwise.hip", "dist.hip"]
+SOURCES = ["pie_ctx.hip", "gemm.hip", "attention.hip", "elementwise.hip", "dist.hip", "lora.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

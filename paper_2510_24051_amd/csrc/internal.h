@@ -39,6 +39,14 @@ __host__ __device__ __forceinline__ int v_elem_offset(int t, int d, int D) {
   return PAGE * D + (d >> 5) * 512 + (t >> 3) * 256 + (d & 31) * 8 + (t & 7);
 }
 
+// ---- LoRA adapters ---------------------------------------------------------------------------
+struct LoraPair {  // one projection of one layer of one adapter; device copies owned by the context
+  bf16_t* A = nullptr;  // [rank, in]
+  bf16_t* B = nullptr;  // [out, rank]
+  int32_t rank = 0;
+  float scale = 0.f;
+};
+
 // ---- batch plan ------------------------------------------------------------------------------
 struct ReqInfo {       // one per request, device + host
   int32_t tok0;        // first token
@@ -73,6 +81,8 @@ struct pie_batch {
   std::vector<int32_t> out_ids_host;  // host copy of the output Embed ids (pie_forward_dist)
   void* dev_blob = nullptr;  // single allocation holding every array below
   int32_t *in_ids = nullptr, *out_ids = nullptr, *pos = nullptr, *tok_page = nullptr, *tok_slot = nullptr;
+  int32_t* tok_adapter = nullptr;      // [T] adapter of each token's request, -1 = none (null: no adapters)
+  std::vector<int32_t> used_adapters;  // host: distinct adapters named by the batch
   int32_t *visit_phys = nullptr, *visit_logical = nullptr;
   uint32_t* mask_words = nullptr;
   ReqInfo* reqs = nullptr;
@@ -107,6 +117,10 @@ struct pie_ctx {
   bf16_t* table = nullptr;             // embedding table [vocab, H] (embed_txt)
   std::vector<int32_t> embed_pos;      // host: sequence position recorded with each Embed by embed_txt, -1 = none
   std::vector<uint16_t> page_mask;     // host: token-level visibility bits of every KvPage (mask_kvpage), all layers
+  std::vector<LoraPair> lora;          // host mirror of the adapter table [max_adapters][n_layers][PIE_N_PROJ]
+  LoraPair* lora_dev = nullptr;        // the same table on the device
+  float* lora_z = nullptr;             // [T, 3, max_lora_rank] fp32: A x of up to three projections sharing an input
+  float* gu32 = nullptr;               // [T, 2 I] fp32 gate/up sums (packed column order) for adapted gate/up
   float* x32 = nullptr;                // [T, H] wide layer input of the layers after the first (n_layers > 1)
   // workspace
   bf16_t *xn = nullptr, *qkv = nullptr, *attn = nullptr, *act = nullptr, *en = nullptr;
@@ -182,6 +196,14 @@ hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_d
                              const int32_t* mrefs, int rows_cap, const float* part_o, const float* part_ml,
                              hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s);
+
+hipError_t launch_lora_down(const bf16_t* x, int ldx, int in, int T, int n_slots, const int32_t* tok_adapter,
+                            const LoraPair* table, int layer, int n_layers, int proj0, float* z, int rmax,
+                            hipStream_t s);
+hipError_t launch_lora_up(void* dst, int ld, int out, int kind, int col0, int T, const int32_t* tok_adapter,
+                          const LoraPair* table, int layer, int n_layers, int proj, int slot, const float* z, int rmax,
+                          hipStream_t s);
+hipError_t launch_swiglu_f32(const float* gu, int I, bf16_t* act, int T, hipStream_t s);
 
 int topk_chunks(int V, int k);  // chunks per row used by launch_topk (<= 16), 0 if unsupported
 // cand_ws: [n, chunks, k] 64-bit candidates; stats_ws: [n, chunks, 2] floats

@@ -60,6 +60,9 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   if (p->n_kv_pages <= 0 || p->n_embeds <= 0 || p->max_batch_tokens <= 0 || p->max_batch_requests <= 0 ||
       p->max_top_k < 0 || p->max_dist_rows < 0 || p->max_top_k > 1024)
     return fail(nullptr, PIE_EINVAL, "pool sizes must be positive (max_top_k <= 1024)");
+  if (p->max_adapters < 0 || p->max_lora_rank < 0 || (p->max_adapters > 0) != (p->max_lora_rank > 0) ||
+      p->max_lora_rank > 1024)
+    return fail(nullptr, PIE_EINVAL, "max_adapters and max_lora_rank (<= 1024) must both be 0 or both be positive");
   if ((int64_t)p->n_kv_pages * m->n_kv_heads > INT32_MAX)
     return fail(nullptr, PIE_EUNSUPPORTED, "n_kv_pages * n_kv_heads must fit 31 bits (page-head block indices are int32)");
 
@@ -88,6 +91,11 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   chk(dev_alloc(&c->attn, T * QD, false, c->stream));
   chk(dev_alloc(&c->h, T * H, false, c->stream));
   if (m->n_layers > 1) chk(dev_alloc(&c->x32, T * H, false, c->stream));
+  if (p->max_adapters > 0) {
+    c->lora.assign((size_t)p->max_adapters * m->n_layers * PIE_N_PROJ, LoraPair());
+    chk(dev_alloc(&c->lora_dev, c->lora.size(), true, c->stream));
+    chk(dev_alloc(&c->lora_z, T * 3 * p->max_lora_rank, false, c->stream));
+  }
   c->embed_pos.assign((size_t)p->n_embeds, -1);
   c->page_mask.assign((size_t)p->n_kv_pages, 0xFFFFu);
   chk(dev_alloc(&c->act, T * I, false, c->stream));
@@ -138,7 +146,11 @@ extern "C" pie_status pie_destroy(pie_ctx* c) {
   }
   free_packed(c->wlm);
   void* bufs[] = {c->embeds, c->kv, c->xn, c->qkv, c->attn, c->h, c->act, c->splitk, c->logits, c->en,
-                  c->ids_dev, c->inv_freq, c->g_final, c->topk_cand, c->topk_stats, c->table, c->x32};
+                  c->ids_dev, c->inv_freq, c->g_final, c->topk_cand, c->topk_stats, c->table, c->x32, c->lora_dev, c->lora_z, c->gu32};
+  for (LoraPair& lp : c->lora) {
+    if (lp.A) (void)hipFree(lp.A);
+    if (lp.B) (void)hipFree(lp.B);
+  }
   for (void* b : bufs) if (b) (void)hipFree(b);
   for (int i = 0; i < 2 * PIE_N_STAGES; ++i) if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
   delete c;
@@ -215,6 +227,53 @@ extern "C" pie_status pie_load_embedding(pie_ctx* c, const void* table) {
     if (e != hipSuccess) return fail(c, e == hipErrorOutOfMemory ? PIE_ENOMEM : PIE_EHIP, "pie_load_embedding: %s", hipGetErrorString(e));
   }
   HIP_TRY(c, hipMemcpyAsync(c->table, table, bytes, hipMemcpyDeviceToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_load_adapter(pie_ctx* c, int32_t adapter, int32_t layer, int32_t proj, int32_t rank,
+                                       float scale, const void* A, const void* B) {
+  if (!c) return PIE_EINVAL;
+  if (c->p.max_adapters <= 0) return fail(c, PIE_EINVAL, "pie_load_adapter: context created without adapters");
+  if (adapter < 0 || adapter >= c->p.max_adapters) return fail(c, PIE_ERANGE, "adapter %d outside [0, %d)", adapter, c->p.max_adapters);
+  if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "layer %d of %d", layer, c->m.n_layers);
+  if (proj < 0 || proj >= PIE_N_PROJ) return fail(c, PIE_ERANGE, "projection %d outside [0, %d)", proj, PIE_N_PROJ);
+  if (rank < 0 || rank > c->p.max_lora_rank) return fail(c, PIE_ERANGE, "rank %d outside [0, %d]", rank, c->p.max_lora_rank);
+  if (rank > 0 && (!A || !B)) return fail(c, PIE_EINVAL, "pie_load_adapter: null pair with rank %d", rank);
+  if (!std::isfinite(scale)) return fail(c, PIE_EINVAL, "pie_load_adapter: scale must be finite");
+  const pie_model_desc& m = c->m;
+  const int QD = m.n_q_heads * m.head_dim, KD = m.n_kv_heads * m.head_dim;
+  const int outs[PIE_N_PROJ] = {QD, KD, KD, m.hidden, m.mlp_dim, m.mlp_dim, m.hidden};
+  const int ins[PIE_N_PROJ] = {m.hidden, m.hidden, m.hidden, QD, m.hidden, m.hidden, m.mlp_dim};
+  HIP_TRY(c, hipStreamSynchronize(c->stream));  // no kernel may still read the pair that is replaced
+  LoraPair& lp = c->lora[((size_t)adapter * m.n_layers + layer) * PIE_N_PROJ + proj];
+  if (lp.A) (void)hipFree(lp.A);
+  if (lp.B) (void)hipFree(lp.B);
+  lp = LoraPair();
+  if (rank > 0 && A && B) {
+    const size_t a_bytes = (size_t)rank * ins[proj] * sizeof(bf16_t), b_bytes = (size_t)outs[proj] * rank * sizeof(bf16_t);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&lp.A), a_bytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&lp.B), b_bytes);
+    if (e != hipSuccess) {
+      if (lp.A) (void)hipFree(lp.A);
+      lp = LoraPair();
+      return fail(c, e == hipErrorOutOfMemory ? PIE_ENOMEM : PIE_EHIP, "pie_load_adapter: %s", hipGetErrorString(e));
+    }
+    HIP_TRY(c, hipMemcpyAsync(lp.A, A, a_bytes, hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(lp.B, B, b_bytes, hipMemcpyDeviceToDevice, c->stream));
+    lp.rank = rank;
+    lp.scale = scale;
+    if ((proj == PIE_PROJ_GATE || proj == PIE_PROJ_UP) && !c->gu32) {
+      // adapted gate/up: the SwiGLU product is taken from fp32 sums instead of the GEMM epilogue
+      hipError_t e2 = hipMalloc(reinterpret_cast<void**>(&c->gu32), (size_t)c->p.max_batch_tokens * 2 * m.mlp_dim * sizeof(float));
+      if (e2 != hipSuccess) {
+        (void)hipFree(lp.A); (void)hipFree(lp.B);
+        lp = LoraPair();
+        return fail(c, e2 == hipErrorOutOfMemory ? PIE_ENOMEM : PIE_EHIP, "pie_load_adapter: %s", hipGetErrorString(e2));
+      }
+    }
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->lora_dev, c->lora.data(), c->lora.size() * sizeof(LoraPair), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   return PIE_OK;
 }
@@ -386,6 +445,18 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   if (b->tok_indptr[0] != 0 || b->tok_indptr[R] != T) return fail(c, PIE_EINVAL, "tok_indptr must run from 0 to n_tokens");
   if (b->page_indptr[0] != 0) return fail(c, PIE_EINVAL, "page_indptr must start at 0");
 
+  std::vector<int32_t> tok_adapter;
+  std::vector<int32_t> used_adapters;
+  if (b->adapter_ids) {
+    bool any = false;
+    for (int r = 0; r < R; ++r) {
+      const int ad = b->adapter_ids[r];
+      if (ad < -1 || ad >= c->p.max_adapters)
+        return fail(c, PIE_ERANGE, "request %d: adapter %d outside [-1, %d)", r, ad, c->p.max_adapters);
+      any = any || ad >= 0;
+    }
+    if (any) tok_adapter.assign(T, -1);  // filled once the token ranges have been checked
+  }
   std::vector<ReqInfo> reqs(R);
   std::vector<int32_t> tok_page(T), tok_slot(T), visit_phys, visit_logical, dec_reqs;
   std::vector<int32_t> pos_from_embeds;  // positions recorded by embed_txt, when the batch names none
@@ -494,6 +565,12 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
     }
     kv_bytes += visited_pages * page_bytes;
   }
+  if (!tok_adapter.empty())
+    for (int r = 0; r < R; ++r) {
+      const int ad = b->adapter_ids[r];
+      for (int i = 0; i < reqs[r].n_new; ++i) tok_adapter[reqs[r].tok0 + i] = ad;
+      if (ad >= 0 && std::find(used_adapters.begin(), used_adapters.end(), ad) == used_adapters.end()) used_adapters.push_back(ad);
+    }
   if (b->page_indptr[R] < 0) return fail(c, PIE_EINVAL, "bad page_indptr");
   if (validate) {
     std::unordered_set<int64_t> seen;
@@ -698,6 +775,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   const size_t o_in = blob.add(b->in_embed_ids, (size_t)T * 4), o_out = blob.add(b->out_embed_ids, (size_t)T * 4);
   const size_t o_pos = blob.add(b->positions ? b->positions : pos_from_embeds.data(), (size_t)T * 4), o_tp = blob.add(tok_page.data(), (size_t)T * 4);
   const size_t o_ts = blob.add(tok_slot.data(), (size_t)T * 4);
+  const size_t o_ta = blob.add(tok_adapter.empty() ? nullptr : tok_adapter.data(), tok_adapter.size() * 4, 4);
   const size_t o_vp = blob.add(visit_phys.data(), visit_phys.size() * 4, 8);
   const size_t o_vl = blob.add(visit_logical.data(), visit_logical.size() * 4, 8);
   const size_t o_mw = blob.add(n_mask_given ? b->mask_words : nullptr, n_mask_given * 4, 0);
@@ -736,6 +814,8 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   unsigned char* d = reinterpret_cast<unsigned char*>(pb->dev_blob);
   pb->in_ids = (int32_t*)(d + o_in); pb->out_ids = (int32_t*)(d + o_out); pb->pos = (int32_t*)(d + o_pos);
   pb->tok_page = (int32_t*)(d + o_tp); pb->tok_slot = (int32_t*)(d + o_ts);
+  pb->tok_adapter = tok_adapter.empty() ? nullptr : (int32_t*)(d + o_ta);
+  pb->used_adapters = used_adapters;
   pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl);
   pb->mask_words = (uint32_t*)(d + o_mw); pb->reqs = (ReqInfo*)(d + o_rq);
   pb->dsegs = (DecodeSeg*)(d + o_di); pb->dwaves = (DecodeWave*)(d + o_ws); pb->wave_pg = (int2*)(d + o_wp);
@@ -800,6 +880,22 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
   HIP_TRY(c, launch_gemm(c->xn, H, T, L.wqkv, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_QKV);
 
+  // LoRA pairs the batch's adapters carry in this layer, per projection
+  bool lora[PIE_N_PROJ] = {false, false, false, false, false, false, false};
+  bool any_lora = false;
+  if (b->tok_adapter)
+    for (int ad : b->used_adapters)
+      for (int pj = 0; pj < PIE_N_PROJ; ++pj)
+        if (c->lora[((size_t)ad * m.n_layers + layer) * PIE_N_PROJ + pj].rank > 0) lora[pj] = any_lora = true;
+  const int RM = c->p.max_lora_rank, NL = m.n_layers;
+  if (lora[PIE_PROJ_Q] || lora[PIE_PROJ_K] || lora[PIE_PROJ_V]) {  // q, k, v share the normalised input
+    const int KD = Hkv * D;
+    HIP_TRY(c, launch_lora_down(c->xn, H, H, T, 3, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_Q, c->lora_z, RM, s));
+    HIP_TRY(c, launch_lora_up(c->qkv, QKV, Hq * D, 0, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_Q, 0, c->lora_z, RM, s));
+    HIP_TRY(c, launch_lora_up(c->qkv, QKV, KD, 0, Hq * D, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_K, 1, c->lora_z, RM, s));
+    HIP_TRY(c, launch_lora_up(c->qkv, QKV, KD, 0, Hq * D + KD, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_V, 2, c->lora_z, RM, s));
+  }
+
   tm.begin(PIE_STAGE_ROPE_APPEND);
   HIP_TRY(c, launch_rope_append(c->qkv, T, Hq, Hkv, D, b->pos, b->tok_page, b->tok_slot, c->inv_freq, kv_layer, s));
   tm.end(PIE_STAGE_ROPE_APPEND);
@@ -827,14 +923,35 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
   HIP_TRY(c, launch_gemm(c->attn, Hq * D, T, L.wo, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
   tm.end(PIE_STAGE_OPROJ);
 
+  if (lora[PIE_PROJ_O]) {  // h += scale * B (A attn), before the second norm reads h
+    HIP_TRY(c, launch_lora_down(c->attn, Hq * D, Hq * D, T, 1, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_O, c->lora_z, RM, s));
+    HIP_TRY(c, launch_lora_up(c->h, H, H, 1, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_O, 0, c->lora_z, RM, s));
+  }
+
   tm.begin(PIE_STAGE_NORM2);
   HIP_TRY(c, launch_rmsnorm_f32(c->h, L.g2, c->xn, T, H, m.rms_eps, s));
   tm.end(PIE_STAGE_NORM2);
 
   tm.begin(PIE_STAGE_GATEUP);
-  e = EpiArgs{EPI_SWIGLU, c->act, I, nullptr, nullptr, nullptr, 0};
-  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wgu, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
+  if (lora[PIE_PROJ_GATE] || lora[PIE_PROJ_UP]) {
+    // the update sits inside the nonlinearity: fp32 gate/up sums, update, then the SwiGLU product
+    e = EpiArgs{EPI_STORE_F32, c->gu32, 2 * I, nullptr, nullptr, nullptr, 0};
+    HIP_TRY(c, launch_gemm(c->xn, H, T, L.wgu, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
+    HIP_TRY(c, launch_lora_down(c->xn, H, H, T, 2, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_GATE, c->lora_z, RM, s));
+    HIP_TRY(c, launch_lora_up(c->gu32, 2 * I, I, 2, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_GATE, 0, c->lora_z, RM, s));
+    HIP_TRY(c, launch_lora_up(c->gu32, 2 * I, I, 2, 32, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_UP, 1, c->lora_z, RM, s));
+    HIP_TRY(c, launch_swiglu_f32(c->gu32, I, c->act, T, s));
+  } else {
+    e = EpiArgs{EPI_SWIGLU, c->act, I, nullptr, nullptr, nullptr, 0};
+    HIP_TRY(c, launch_gemm(c->xn, H, T, L.wgu, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
+  }
   tm.end(PIE_STAGE_GATEUP);
+
+  if (lora[PIE_PROJ_DOWN]) {  // added to the residual the down projection's epilogue reads
+    HIP_TRY(c, launch_lora_down(c->act, I, I, T, 1, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_DOWN, c->lora_z, RM, s));
+    HIP_TRY(c, launch_lora_up(c->h, H, H, 1, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_DOWN, 0, c->lora_z, RM, s));
+  }
+  (void)any_lora;
 
   tm.begin(PIE_STAGE_DOWN);
   e = EpiArgs{EPI_RESID_OUT, y_out, y_out ? H : 0, c->embeds, b->out_ids, c->h, H};

@@ -69,6 +69,7 @@ class Batch:  # mirrors the C-ABI batch descriptor, host arrays
     kv_len: np.ndarray         # int32 [R], length after append
     mask_indptr: Optional[np.ndarray] = None  # int64 [R+1] word offsets, None = all inferred causal
     mask_words: Optional[np.ndarray] = None   # uint32
+    adapter_ids: Optional[np.ndarray] = None  # int32 [R] LoRA adapter per request, -1 = none
 
 
 @dataclass
