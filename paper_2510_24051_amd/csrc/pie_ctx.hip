@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <new>
 #include <unordered_set>
 
 #include "internal.h"
@@ -28,6 +29,18 @@ static pie_status fail(pie_ctx* ctx, pie_status code, const char* fmt, ...) {
 
 extern "C" const char* pie_last_error(const pie_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
 
+// No C++ exception may cross the C boundary: entry points that build host containers run through this.
+template <typename F>
+static pie_status guarded(pie_ctx* ctx, const char* what, F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, PIE_ENOMEM, "%s: out of host memory", what);
+  } catch (...) {
+    return fail(ctx, PIE_EINVAL, "%s: unexpected exception", what);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // create / destroy
 // ---------------------------------------------------------------------------------------------
@@ -43,7 +56,7 @@ static hipError_t dev_alloc(T** p, size_t elems, bool zero, hipStream_t s) {
 
 static int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
-extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p, void* hip_stream, pie_ctx** out) {
+static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* p, void* hip_stream, pie_ctx** out) {
   if (!m || !p || !out) return fail(nullptr, PIE_EINVAL, "pie_create: null argument");
   *out = nullptr;
   if (m->page_size != PAGE) return fail(nullptr, PIE_EUNSUPPORTED, "page_size %d: kernels are built for %d", m->page_size, PAGE);
@@ -129,6 +142,10 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   }
   *out = c;
   return PIE_OK;
+}
+
+extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p, void* hip_stream, pie_ctx** out) {
+  return guarded(nullptr, "pie_create", [&]() { return pie_create_impl(m, p, hip_stream, out); });
 }
 
 static void free_packed(PackedWeight& w) {
@@ -313,7 +330,7 @@ extern "C" pie_status pie_embed_write(pie_ctx* c, const int32_t* ids, int32_t n,
   return st;
 }
 
-extern "C" pie_status pie_embed_txt(pie_ctx* c, const int32_t* token_ids, const int32_t* positions, int32_t n,
+static pie_status pie_embed_txt_impl(pie_ctx* c, const int32_t* token_ids, const int32_t* positions, int32_t n,
                                     const int32_t* embed_ids) {
   if (!c) return PIE_EINVAL;
   if (n < 0 || (n > 0 && (!token_ids || !positions || !embed_ids))) return fail(c, PIE_EINVAL, "pie_embed_txt: null argument");
@@ -336,6 +353,11 @@ extern "C" pie_status pie_embed_txt(pie_ctx* c, const int32_t* token_ids, const 
   HIP_TRY(c, hipStreamSynchronize(c->stream));  // ids_dev is reused by the next call
   for (int i = 0; i < n; ++i) c->embed_pos[embed_ids[i]] = positions[i];
   return PIE_OK;
+}
+
+extern "C" pie_status pie_embed_txt(pie_ctx* c, const int32_t* token_ids, const int32_t* positions, int32_t n,
+                                    const int32_t* embed_ids) {
+  return guarded(c, "pie_embed_txt", [&]() { return pie_embed_txt_impl(c, token_ids, positions, n, embed_ids); });
 }
 extern "C" pie_status pie_embed_read(pie_ctx* c, const int32_t* ids, int32_t n, void* dst) {
   return embed_copy(c, ids, n, dst, 0);
@@ -377,7 +399,7 @@ extern "C" pie_status pie_mask_kvpage(pie_ctx* c, const int32_t* page_ids, const
   return PIE_OK;
 }
 
-extern "C" pie_status pie_copy_kvpage(pie_ctx* c, const int32_t* src_pages, const int32_t* src_slots,
+static pie_status pie_copy_kvpage_impl(pie_ctx* c, const int32_t* src_pages, const int32_t* src_slots,
                                       const int32_t* dst_pages, const int32_t* dst_slots, int32_t n) {
   if (!c) return PIE_EINVAL;
   if (n < 0 || (n > 0 && (!src_pages || !src_slots || !dst_pages || !dst_slots)))
@@ -414,6 +436,11 @@ extern "C" pie_status pie_copy_kvpage(pie_ctx* c, const int32_t* src_pages, cons
   return PIE_OK;
 }
 
+extern "C" pie_status pie_copy_kvpage(pie_ctx* c, const int32_t* src_pages, const int32_t* src_slots,
+                                      const int32_t* dst_pages, const int32_t* dst_slots, int32_t n) {
+  return guarded(c, "pie_copy_kvpage", [&]() { return pie_copy_kvpage_impl(c, src_pages, src_slots, dst_pages, dst_slots, n); });
+}
+
 // ---------------------------------------------------------------------------------------------
 // batch deserialisation
 // ---------------------------------------------------------------------------------------------
@@ -429,7 +456,7 @@ struct Blob {  // host image of the device allocation
 };
 }  // namespace
 
-extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, int32_t validate, pie_batch** out) {
+static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, int32_t validate, pie_batch** out) {
   if (!c) return PIE_EINVAL;
   if (!b || !out) return fail(c, PIE_EINVAL, "pie_batch_create: null argument");
   *out = nullptr;
@@ -826,6 +853,10 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
   return PIE_OK;
 }
 
+extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, int32_t validate, pie_batch** out) {
+  return guarded(c, "pie_batch_create", [&]() { return pie_batch_create_impl(c, b, validate, out); });
+}
+
 extern "C" pie_status pie_batch_destroy(pie_ctx* c, pie_batch* b) {
   if (!b) return PIE_OK;
   if (c) (void)hipStreamSynchronize(c->stream);
@@ -1041,7 +1072,7 @@ extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, in
   return PIE_OK;
 }
 
-extern "C" pie_status pie_forward_dist(pie_ctx* c, const pie_batch* b, const int32_t* rows, int32_t n, int32_t top_k,
+static pie_status pie_forward_dist_impl(pie_ctx* c, const pie_batch* b, const int32_t* rows, int32_t n, int32_t top_k,
                                        float temperature, int32_t* out_ids, float* out_probs) {
   if (!c) return PIE_EINVAL;
   if (!b) return fail(c, PIE_EINVAL, "pie_forward_dist: null batch");
@@ -1057,6 +1088,11 @@ extern "C" pie_status pie_forward_dist(pie_ctx* c, const pie_batch* b, const int
   st = pie_forward_all(c, b);
   if (st != PIE_OK) return st;
   return pie_get_next_dist(c, ids.data(), n, top_k, temperature, out_ids, out_probs);
+}
+
+extern "C" pie_status pie_forward_dist(pie_ctx* c, const pie_batch* b, const int32_t* rows, int32_t n, int32_t top_k,
+                                       float temperature, int32_t* out_ids, float* out_probs) {
+  return guarded(c, "pie_forward_dist", [&]() { return pie_forward_dist_impl(c, b, rows, n, top_k, temperature, out_ids, out_probs); });
 }
 
 extern "C" pie_status pie_synchronize(pie_ctx* c) {
