@@ -210,35 +210,55 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
   }
 }
 
-// Sum split-K partials and apply the epilogue.  One thread per output element (SWIGLU: per gate/up pair).
+// Sum split-K partials and apply the epilogue.  One thread per four consecutive output columns (SWIGLU: four
+// gate/up pairs); all column counts are multiples of 32, so the four never straddle a 32-column block.
 template <int MODE>
 __global__ void splitk_epilogue_kernel(const float* __restrict__ part, int splits, int M, int N, int NP, EpiArgs e) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int cols = (MODE == EPI_SWIGLU) ? NP / 2 : N;
-  if (idx >= (int64_t)M * cols) return;
-  int m = (int)(idx / cols), c = (int)(idx % cols);
+  const int cols4 = cols / 4;
+  if (idx >= (int64_t)M * cols4) return;
+  const int m = (int)(idx / cols4), c = (int)(idx % cols4) * 4;
   auto total = [&](int n) {
-    float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += part[((int64_t)k * M + m) * NP + n];
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < splits; ++k) s += *reinterpret_cast<const f32x4*>(part + ((int64_t)k * M + m) * NP + n);
     return s;
   };
+  auto store_bf16x4 = [](bf16_t* dst, const f32x4& v) {
+    bf16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = f32_to_bf16(v[i]);
+    *reinterpret_cast<bf16x4*>(dst) = o;
+  };
   if (MODE == EPI_SWIGLU) {
-    int ng = (c >> 5) * 64 + (c & 31);  // gate column in packed order; up column is 32 further
-    reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + c] = f32_to_bf16(silu_f(total(ng)) * total(ng + 32));
+    const int ng = (c >> 5) * 64 + (c & 31);  // gate columns in packed order; the up columns are 32 further
+    const f32x4 g = total(ng), u = total(ng + 32);
+    f32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = silu_f(g[i]) * u[i];
+    store_bf16x4(reinterpret_cast<bf16_t*>(e.out) + (int64_t)m * e.ldo + c, r);
   } else {
-    float x = total(c);
-    if (MODE == EPI_STORE_BF16) reinterpret_cast<bf16_t*>(e.out)[(int64_t)m * e.ldo + c] = f32_to_bf16(x);
-    else if (MODE == EPI_STORE_F32) reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = x;
-    else if (MODE == EPI_RESID_EMBED) {
-      const float r = e.resid != nullptr ? e.resid[(int64_t)m * e.H + c]
-                                         : bf16_to_f32(e.embeds[(int64_t)e.ids[m] * e.H + c]);
-      reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = r + x;
-    } else if (MODE == EPI_RESID_OUT) {
-      if (e.out != nullptr) {
-        reinterpret_cast<float*>(e.out)[(int64_t)m * e.ldo + c] = e.resid[(int64_t)m * e.H + c] + x;
+    f32x4 x = total(c);
+    if (MODE == EPI_STORE_BF16) {
+      store_bf16x4(reinterpret_cast<bf16_t*>(e.out) + (int64_t)m * e.ldo + c, x);
+    } else if (MODE == EPI_STORE_F32) {
+      *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(e.out) + (int64_t)m * e.ldo + c) = x;
+    } else if (MODE == EPI_RESID_EMBED) {
+      if (e.resid != nullptr) {
+        x += *reinterpret_cast<const f32x4*>(e.resid + (int64_t)m * e.H + c);
       } else {
-        int id = e.ids[m];
-        if (id >= 0) e.embeds[(int64_t)id * e.H + c] = f32_to_bf16(e.resid[(int64_t)m * e.H + c] + x);
+        const bf16x4 r = *reinterpret_cast<const bf16x4*>(e.embeds + (int64_t)e.ids[m] * e.H + c);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] += bf16_to_f32(r[i]);
+      }
+      *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(e.out) + (int64_t)m * e.ldo + c) = x;
+    } else if (MODE == EPI_RESID_OUT) {
+      const f32x4 y = x + *reinterpret_cast<const f32x4*>(e.resid + (int64_t)m * e.H + c);
+      if (e.out != nullptr) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(e.out) + (int64_t)m * e.ldo + c) = y;
+      } else {
+        const int id = e.ids[m];
+        if (id >= 0) store_bf16x4(e.embeds + (int64_t)id * e.H + c, y);
       }
     }
   }
@@ -509,7 +529,7 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int cols = (MODE == EPI_SWIGLU) ? NP / 2 : W.N;
-  int64_t total = (int64_t)M * cols;
+  int64_t total = (int64_t)M * (cols / 4);
   splitk_epilogue_kernel<MODE><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(ws, splits, M, W.N, NP, epi);
   return hipGetLastError();
 }

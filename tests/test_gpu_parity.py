@@ -115,7 +115,7 @@ def test_c1_literal_unstored_rows_and_in_place():
 
 
 # ---------------------------------------------------------------- ragged shapes, masks, head dims, group sizes
-@pytest.mark.parametrize("head_dim,n_q,n_kv", [(64, 4, 2), (128, 8, 2), (128, 8, 1), (64, 2, 2)])
+@pytest.mark.parametrize("head_dim,n_q,n_kv", [(64, 4, 2), (128, 8, 2), (128, 8, 1), (64, 2, 2), (64, 8, 1)])
 def test_ragged_mixed_batch(head_dim, n_q, n_kv):
     m = small_model(head_dim, n_q, n_kv)
     sparse = random_mask(0.3)
@@ -286,6 +286,21 @@ def test_get_next_dist_top_k(k, temp):
     ctx = make_ctx(w, max_top_k=512)
     gpu_forward(ctx, w)
     compare_dist(ctx, w, f"k={k} T={temp}")
+
+
+@pytest.mark.parametrize("vocab,k", [(131072, 1024), (131072, 1), (32, 32), (8192, 1000), (8224, 7)])
+def test_get_next_dist_size_limits(vocab, k):
+    """Largest vocabulary and K the kernels take, K equal to the vocabulary, a vocabulary of exactly one chunk and
+    one that spills 32 entries into a second chunk."""
+    m = small_model(vocab=vocab)
+    w = W.build_workload("dist_lim", m, [W.RequestSpec(1, 5) for _ in range(3)], n_kv_pages=8, seed=42, std=0.05,
+                         top_k=k)
+    ctx = make_ctx(w, max_top_k=1024)
+    gpu_forward(ctx, w)
+    compare_dist(ctx, w, f"V={vocab} k={k}")
+    if k == vocab:
+        _, gp = ctx.get_next_dist(w.batch.out_embed_ids[w.dist_rows], k, 1.0)
+        np.testing.assert_allclose(gp.sum(axis=1), 1.0, rtol=1e-5)
 
 
 def test_top_k_ties_pick_lower_ids():
