@@ -65,3 +65,5 @@ __device__ __forceinline__ void wg_barrier() {
 // bookkeeping knows which copies have landed and does not add a full wait before the next LDS read.
 // gfx9 encoding: vmcnt in bits [3:0] and [15:14]; expcnt [6:4] and lgkmcnt [11:8] left at "no wait".
 #define PIE_S_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | 0x0F70 | ((((n) >> 4) & 3) << 14))
+// s_waitcnt lgkmcnt(0) alone (LDS and scalar-memory operations done; vector-memory loads stay in flight)
+#define PIE_S_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xC07F)

@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
       if (c < A_CHUNKS) *reinterpret_cast<u32x4*>(As + buf * A_ELEMS + r * SK_BK + ((kc ^ (r & 15)) << 3)) = areg[j];
     }
   };
-  bf16x8 breg[2][NBW][8];
+  bf16x8 breg[3][NBW][8];  // ring of three register sets: the weights of the next two iterations are in flight
   auto load_b = [&](int it, const int slot) {
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
@@ -148,16 +148,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
       }
   };
 
-  // one main-loop iteration; SLOT is the register set holding this iteration's W operands (compile-time so
-  // the operand arrays stay in registers)
+  // One main-loop iteration; SLOT is the register set holding this iteration's W operands (compile-time so
+  // the operand arrays stay in registers).  The barrier carries no memory fence (a fence would make the compiler
+  // drain every outstanding load, i.e. the weights requested two iterations ahead): only the LDS stores of the
+  // next activation tile have to be visible to the other waves, hence the explicit wait for LDS operations.
   auto step = [&](auto slot_c, int it) {
     constexpr int SLOT = decltype(slot_c)::value;
     const int cur = (it - it0) & 1;
     const bool more = it + 1 < it1;
-    if (more) {
-      load_a(it + 1);
-      load_b(it + 1, SLOT ^ 1);
-    }
+    if (more) load_a(it + 1);
+    if (it + 2 < it1) load_b(it + 2, (SLOT + 2) % 3);
     const bf16_t* Ab = As + cur * A_ELEMS;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -171,17 +171,21 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
       }
     }
     if (more) store_a(cur ^ 1);
-    __syncthreads();
+    PIE_S_WAIT_LGKMCNT0();
+    wg_barrier();
   };
   if (it0 < it1) {
     load_a(it0);
     load_b(it0, 0);
+    if (it0 + 1 < it1) load_b(it0 + 1, 1);
     store_a(0);
   }
-  __syncthreads();
-  for (int it = it0; it < it1; it += 2) {
+  PIE_S_WAIT_LGKMCNT0();
+  wg_barrier();
+  for (int it = it0; it < it1; it += 3) {
     step(std::integral_constant<int, 0>{}, it);
     if (it + 1 < it1) step(std::integral_constant<int, 1>{}, it + 1);
+    if (it + 2 < it1) step(std::integral_constant<int, 2>{}, it + 2);
   }
   if (!wave_active) return;
   if (PARTIAL) {
