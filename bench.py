@@ -36,6 +36,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--top-k", type=int, default=256)
+    ap.add_argument("--requests", type=int, default=64, help="c2 only: number of decode requests (default: the config's 64)")
     ap.add_argument("--lora-rank", type=int, default=0,
                     help="give every request one of two synthetic LoRA adapters of this rank on q, k, v, o "
                          "(forward_with_adapter); 0 = plain forward")
@@ -54,8 +55,9 @@ def main():
 
     t_setup = time.time()
     if args.workload == "c2":
-        w = W.c2_decode(top_k=args.top_k)
-        desc = "configs[1]: Llama-3-8B-shaped layer, 64 decode requests, prior ctx U[512,4096], 40k-page pool, page 16"
+        w = W.c2_decode(top_k=args.top_k, n_requests=args.requests)
+        desc = (f"configs[1]: Llama-3-8B-shaped layer, {args.requests} decode requests, prior ctx U[512,4096], "
+                "40k-page pool, page 16")
     elif args.workload == "c3":
         w = W.c3_mixed()
         desc = "configs[2]: 8B-shaped layer, 8 prefill x 1024 (prior U[0,2048]) + 128 decode @2048"

@@ -116,23 +116,26 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
   constexpr int A_CHUNKS = BM * 16;
   constexpr int A_PER_THREAD = (A_CHUNKS + 255) / 256;
   u32x4 areg[A_PER_THREAD];
+  // Loads always read an in-bounds address (row and k clamped); chunks outside the matrix are zeroed when the
+  // registers are stored to LDS, so no register is written while an earlier load into it could be pending.
   auto load_a = [&](int it) {
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
-      int c = tid + j * 256;
-      int r = c >> 4, kc = c & 15;
-      int k = it * SK_BK + kc * 8;
-      u32x4 v = {0, 0, 0, 0};
-      if (c < A_CHUNKS && r < M && k < K) v = *reinterpret_cast<const u32x4*>(A + (int64_t)r * lda + k);
-      areg[j] = v;
+      const int c = min(tid + j * 256, A_CHUNKS - 1);
+      const int r = min(c >> 4, M - 1), kc = c & 15;
+      const int k = min(it * SK_BK + kc * 8, K - 8);
+      areg[j] = *reinterpret_cast<const u32x4*>(A + (int64_t)r * lda + k);
     }
   };
-  auto store_a = [&](int buf) {
+  auto store_a = [&](int buf, int it) {
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
-      int c = tid + j * 256;
-      int r = c >> 4, kc = c & 15;
-      if (c < A_CHUNKS) *reinterpret_cast<u32x4*>(As + buf * A_ELEMS + r * SK_BK + ((kc ^ (r & 15)) << 3)) = areg[j];
+      const int c = tid + j * 256;
+      const int r = c >> 4, kc = c & 15;
+      const bool inside = r < M && it * SK_BK + kc * 8 < K;
+      if (c < A_CHUNKS)
+        *reinterpret_cast<u32x4*>(As + buf * A_ELEMS + r * SK_BK + ((kc ^ (r & 15)) << 3)) =
+            inside ? areg[j] : u32x4{0, 0, 0, 0};
     }
   };
   bf16x8 breg[3][NBW][8];  // ring of three register sets: the weights of the next two iterations are in flight
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
         for (int j = 0; j < NBW; ++j) acc[j][i] = mfma32(af, breg[SLOT][j][s], acc[j][i]);
       }
     }
-    if (more) store_a(cur ^ 1);
+    if (more) store_a(cur ^ 1, it + 1);
     PIE_S_WAIT_LGKMCNT0();
     wg_barrier();
   };
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
     load_a(it0);
     load_b(it0, 0);
     if (it0 + 1 < it1) load_b(it0 + 1, 1);
-    store_a(0);
+    store_a(0, it0);
   }
   PIE_S_WAIT_LGKMCNT0();
   wg_barrier();
