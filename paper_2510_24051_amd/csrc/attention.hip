@@ -455,12 +455,21 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, const int32_
         den += w * part_ml[prow * 2 + 1];
       }
       const int cnt = min(64, count - c0);
-      for (int j = 0; j < cnt; ++j) {
-        const float wj = __shfl(w, j);
-        const int64_t pj = __shfl((int)prow, j);
-        const float* po = part_o + pj * D + lane * E;
+      // eight partial rows per round: their loads are independent and go out together
+      for (int j0 = 0; j0 < cnt; j0 += 8) {
+        float wj[8], v[8][E];
 #pragma unroll
-        for (int e = 0; e < E; ++e) num[e] += wj * po[e];
+        for (int u = 0; u < 8; ++u) {
+          const int j = min(j0 + u, cnt - 1);
+          wj[u] = j0 + u < cnt ? __shfl(w, j) : 0.f;
+          const float* po = part_o + (int64_t)__shfl((int)prow, j) * D + lane * E;
+#pragma unroll
+          for (int e = 0; e < E; ++e) v[u][e] = po[e];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int e = 0; e < E; ++e) num[e] += wj[u] * v[u][e];
       }
     }
     den = wave_sum(den);

@@ -707,7 +707,10 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
         }
       }
     }
-    int64_t per_wave = (total_pairs + c->wave_slots - 1) / c->wave_slots;
+    // whole rounds of resident waves: when one round of 64-pair shares does not cover the list, the shares
+    // shrink so that every round is full instead of leaving a nearly empty last one
+    const int64_t rounds = std::max<int64_t>(1, (total_pairs + (int64_t)c->wave_slots * 64 - 1) / ((int64_t)c->wave_slots * 64));
+    int64_t per_wave = (total_pairs + rounds * c->wave_slots - 1) / (rounds * c->wave_slots);
     per_wave = std::min<int64_t>(std::max<int64_t>(per_wave, 2), 64);
     dslots = (int)(2 * per_wave);
     wave_pg.reserve((size_t)((total_pairs + per_wave - 1) / per_wave + 1) * dslots);
