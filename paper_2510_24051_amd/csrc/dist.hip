@@ -17,7 +17,8 @@
 #include "internal.h"
 
 #define TC_THREADS 512
-#define TC_PER 16  // keys per thread: chunks hold at most TC_THREADS * TC_PER = 8192 logits
+// keys per thread of the chunk kernel: 16 (chunks of at most 8192 logits) or, when there are enough rows to fill
+// the chip with half as many workgroups, 32 (16384 logits): half the block-wide synchronisation per logit
 #define TM_THREADS 1024
 #define TM_PER 16  // composites per thread: at most 16384 candidates per row
 
@@ -112,6 +113,7 @@ __device__ __forceinline__ void select_kth(const KeyT (&keys)[PER], uint32_t nee
   *out_eq = eq;
 }
 
+template <int TC_PER>
 __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __restrict__ logits, int V, int chunk_len,
                                                                 int k, float inv_temp,
                                                                 unsigned long long* __restrict__ cand,
@@ -307,14 +309,21 @@ int topk_chunks(int V, int k) {
 hipError_t launch_topk(const float* logits, int n, int V, int k, float inv_temp, int32_t* out_ids, float* out_probs,
                        unsigned long long* cand_ws, float* stats_ws, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  const int n_chunks = topk_chunks(V, k);
+  int n_chunks = topk_chunks(V, k);
   if (n_chunks == 0 || k > 1024 || k > V || k <= 0 || (V & 3)) return hipErrorInvalidValue;
+  // with many rows, chunks twice as long still give every CU several workgroups
+  const bool wide = n_chunks > 1 && (int64_t)n * n_chunks >= 1024;
+  if (wide) n_chunks = (n_chunks + 1) / 2;
+  const int per = wide ? 32 : 16;
   int chunk_len = ((V + n_chunks - 1) / n_chunks + 3) / 4 * 4;
-  if (chunk_len > TC_THREADS * TC_PER || n_chunks * k > TM_THREADS * TM_PER) return hipErrorInvalidValue;
+  if (chunk_len > TC_THREADS * per || n_chunks * k > TM_THREADS * TM_PER) return hipErrorInvalidValue;
   int n2 = 1;
   while (n2 < k) n2 <<= 1;
   size_t smem_b = (size_t)n2 * 8;
-  topk_chunk_kernel<<<dim3(n, n_chunks), dim3(TC_THREADS), 0, s>>>(logits, V, chunk_len, k, inv_temp, cand_ws, stats_ws);
+  if (wide)
+    topk_chunk_kernel<32><<<dim3(n, n_chunks), dim3(TC_THREADS), 0, s>>>(logits, V, chunk_len, k, inv_temp, cand_ws, stats_ws);
+  else
+    topk_chunk_kernel<16><<<dim3(n, n_chunks), dim3(TC_THREADS), 0, s>>>(logits, V, chunk_len, k, inv_temp, cand_ws, stats_ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   topk_merge_kernel<<<dim3(n), dim3(TM_THREADS), smem_b, s>>>(n_chunks, k, inv_temp, cand_ws, stats_ws, n2, out_ids,

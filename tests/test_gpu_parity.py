@@ -303,6 +303,17 @@ def test_get_next_dist_size_limits(vocab, k):
         np.testing.assert_allclose(gp.sum(axis=1), 1.0, rtol=1e-5)
 
 
+def test_get_next_dist_many_rows_long_chunks():
+    """Enough rows that the chunk kernel takes 16384-logit chunks (two of them for 16416 logits, the second with
+    32 entries), K larger than the short chunk."""
+    m = small_model(vocab=16416)
+    w = W.build_workload("dist_rows", m, [W.RequestSpec(1, 3) for _ in range(360)], n_kv_pages=400, seed=43, std=0.05,
+                         top_k=40)
+    ctx = make_ctx(w, max_top_k=64)
+    gpu_forward(ctx, w)
+    compare_dist(ctx, w, "360 rows, V=16416, k=40")
+
+
 def test_top_k_ties_pick_lower_ids():
     m = small_model(vocab=512)
     w = W.build_workload("ties", m, [W.RequestSpec(1, 3)], n_kv_pages=4, seed=41, std=0.05, top_k=40)
