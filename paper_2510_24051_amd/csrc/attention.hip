@@ -111,6 +111,8 @@ __device__ __forceinline__ void attn_step(AttnState<D>& st, const bf16x8 (&kf)[D
   }
 }
 
+constexpr float RESCALE_SLACK = 8.0f;
+
 // The three phases of attn_step as separate functions, for kernels that overlap the QK^T MFMAs of the next
 // pair with the softmax arithmetic of the current one.
 template <int D>
@@ -134,10 +136,15 @@ __device__ __forceinline__ void attn_softmax(AttnState<D>& st, f32x16 s, uint32_
   float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
   mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
   mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+  // The reference point st.m of the exponentials only has to stay within RESCALE_SLACK (in log2 units) of the
+  // running maximum: weights up to 2^RESCALE_SLACK are harmless in fp32 sums and keep their relative precision
+  // in bf16, and the final division by the sum of the same weights cancels the reference.  So the accumulators
+  // are rescaled only when some row's maximum has moved by more than the slack, which after the first pairs of a
+  // row almost never happens.
   const float m_new = fmaxf(st.m, mx);
-  const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-  if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0ull) {
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+  if (__builtin_amdgcn_ballot_w64(m_new > st.m + RESCALE_SLACK) != 0ull) {  // -inf + slack = -inf: first visible key
+    const float m_to = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_to);  // 0 while nothing was visible before
     st.l *= alpha;
 #pragma unroll
     for (int b = 0; b < D / 32; ++b)
@@ -145,6 +152,7 @@ __device__ __forceinline__ void attn_softmax(AttnState<D>& st, f32x16 s, uint32_
       for (int v = 0; v < 16; ++v) st.o[b][v] *= alpha;
     st.m = m_new;
   }
+  const float m_safe = (st.m == -INFINITY) ? 0.f : st.m;
   float lsum = 0.f;
   Pack16 pa, pb;
 #pragma unroll
@@ -538,8 +546,12 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
     const bf16_t* kvh = a.kv + (int64_t)hk * BLK + lane * 8;
     const int64_t page_stride = (int64_t)a.Hkv * BLK;
     const uint32_t* mrow = a.mask_words + rq.mask_off + (int64_t)i_ld * rq.wpr;
-    struct Meta { int pl_a, pl_b; bool has_b; uint32_t mw_a, mw_b; };
+    struct Meta { int pl_a, pl_b; bool has_b, full; uint32_t mw_a, mw_b; };
     Meta m0{}, m1{}, m2{}, m3{};
+    // Inferred-causal blocks of 32 real rows: a pair whose last key is at or below the first row's limit is
+    // visible to every row, which the whole workgroup knows without any per-lane arithmetic.
+    const bool rows_full = !has_bitmap && it.qb * 32 + 31 < rq.n_new;
+    const int first_lim = rq.kv_len - rq.n_new + it.qb * 32;
     auto start_pair = [&](bf16_t* stage, int pair, Meta& md) {
       const int pc = pair < n_pairs ? pair : n_pairs - 1;
       const int v = pc * 2;
@@ -549,6 +561,7 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
       md.has_b = v + 1 < v_end;
       if (md.has_b) page_of(v + 1, pp_b, md.pl_b);
       else { pp_b = pp_a; md.pl_b = md.pl_a; }
+      md.full = rows_full && md.has_b && max(md.pl_a, md.pl_b) * PAGE + PAGE - 1 <= first_lim;
       if (has_bitmap && valid) { md.mw_a = mrow[md.pl_a >> 1]; md.mw_b = mrow[md.pl_b >> 1]; }
       const bf16_t* sa = kvh + (int64_t)pp_a * page_stride;
       const bf16_t* sb = kvh + (int64_t)pp_b * page_stride;
@@ -585,8 +598,11 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
       return attn_qk<D>(kf, qf);
     };
     auto finish = [&](const bf16_t* stage, const Meta& md, const f32x16& sc) {
-      const uint32_t bits_a = bits_of(md.mw_a, md.pl_a);
-      const uint32_t bits_b = md.has_b ? bits_of(md.mw_b, md.pl_b) : 0u;
+      uint32_t bits_a = 0xFFu, bits_b = 0xFFu;
+      if (!md.full) {
+        bits_a = bits_of(md.mw_a, md.pl_a);
+        bits_b = md.has_b ? bits_of(md.mw_b, md.pl_b) : 0u;
+      }
       bf16x8 pa, pb;
       attn_softmax<D>(st, sc, bits_a, bits_b, a.scale_log2, pa, pb);
       bf16x8 va[D / 32], vb[D / 32];
