@@ -7,6 +7,7 @@
 //                 few workgroups; partial sums go to a workspace and a second kernel applies the epilogue.
 //   gemm_large  : M > 256 (prefill).  MFMA-bound: 256x256x64 workgroup tile, 8 waves of 128x64, LDS double
 //                 buffering, swizzled A tile, W tile kept in operand order.
+#include <algorithm>
 #include <type_traits>
 
 #include "internal.h"
@@ -277,6 +278,7 @@ __global__ void splitk_epilogue_kernel(const float* __restrict__ part, int split
 #define LG_BM 256
 #define LG_BN 256
 #define LG_BK 64
+#define TILED_MIN_KTS 8  // fewest k tiles a split of the tiled kernel takes
 
 template <int MODE>
 __global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restrict__ A, int lda, int M,
@@ -394,15 +396,19 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restric
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),           \
                                    (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
 
-template <int MODE>
+template <int MODE, bool PARTIAL>
 __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                                const bf16_t* __restrict__ Wp, int N, int NB, int K,
-                                                               EpiArgs epi, int tiles_m, int tiles_n) {
+                                                               EpiArgs epi, int tiles_m, int tiles_n,
+                                                               int kts_per_split, float* __restrict__ part) {
   __shared__ __align__(16) bf16_t As0[LG_BM * LG_BK], As1[LG_BM * LG_BK], Bs0[LG_BN * LG_BK], Bs1[LG_BN * LG_BK];
   constexpr int GROUP_M = 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
   const int KB = K / 16, KT = K / LG_BK;  // KT is even
+  // split K: workgroup row blockIdx.y takes k tiles [kt0, kt1), an even count
+  const int kt0 = PARTIAL ? blockIdx.y * kts_per_split : 0;
+  const int kt1 = PARTIAL ? min(KT, kt0 + kts_per_split) : KT;
   int pid = blockIdx.x;
   const int ntiles = tiles_m * tiles_n;
   if (ntiles % 8 == 0) pid = (pid & 7) * (ntiles / 8) + (pid >> 3);
@@ -442,7 +448,7 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
     bp[jj] = Wp + packed_tile_offset(nb, j & 3, KB) + lane * 8;
   }
   auto issue = [&](bf16_t* As, bf16_t* Bs, int kt) {
-    const int k = kt < KT ? kt : KT - 1;
+    const int k = kt < kt1 ? kt : kt1 - 1;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) LDS_DMA16(ap[jj] + (int64_t)k * LG_BK, As + (wave * 4 + jj) * 512);
 #pragma unroll
@@ -472,10 +478,10 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  issue(As0, Bs0, 0);
+  issue(As0, Bs0, kt0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  for (int kt = 0; kt < KT; kt += 2) {
+  for (int kt = kt0; kt < kt1; kt += 2) {
     issue(As1, Bs1, kt + 1);
     compute(As0, Bs0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -484,6 +490,23 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
     compute(As1, Bs1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+  }
+  if (PARTIAL) {
+    // raw partial sums: part[split][m][n_packed]
+    const int NP = NB * 32;
+    float* P = part + (int64_t)blockIdx.y * M * NP;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int nb = nb0 + wn * 2 + j;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * 128 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          if (m < M && nb < NB) P[(int64_t)m * NP + nb * 32 + (lane & 31)] = acc[i][j][v];
+        }
+      }
+    return;
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -577,6 +600,26 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   // 0.26 ms for up to 256 rows against 0.30 ms at 128 rows and 0.46 ms at 256 rows).
   const bool wide = W.K % 128 == 0 && (W.NB + 7) / 8 >= n_cus && M > 64;
   if (M <= 128 && !wide) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 256 && !wide && W.K % 128 == 0) {
+    // One row of 256x256 tiles with K split so that the tiles fill the chip once; each split keeps at least
+    // TILED_MIN_KTS k tiles, or the pipeline fill and the partial sums outweigh the work.
+    const int tiles_n = (W.NB + 7) / 8, KT = W.K / LG_BK, NP = W.NB * 32;
+    int splits = std::max(1, n_cus / tiles_n);
+    int kts = (KT + splits - 1) / splits;
+    kts += kts & 1;
+    kts = std::max(kts, TILED_MIN_KTS);
+    splits = (KT + kts - 1) / kts;
+    if (splits > 1 && (size_t)splits * M * NP <= ws_elems) {
+      gemm_large_async_kernel<MODE, true><<<dim3(tiles_n, splits), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB, W.K,
+                                                                                     epi, 1, tiles_n, kts, ws);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      const int cols = (MODE == EPI_SWIGLU) ? NP / 2 : W.N;
+      const int64_t total = (int64_t)M * (cols / 4);
+      splitk_epilogue_kernel<MODE><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(ws, splits, M, W.N, NP, epi);
+      return hipGetLastError();
+    }
+  }
   if (M <= 256 && MODE != EPI_SWIGLU && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
   if (W.K % 128 == 0) {
     const int tiles_n = (W.NB + 7) / 8;
@@ -586,15 +629,15 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
     auto rounds = [&](int tm) { return (tm * tiles_n + n_cus - 1) / n_cus; };
     if (ragged > 0 && full > 0 && (ragged <= 128 || MODE != EPI_SWIGLU) && rounds(full + 1) > rounds(full)) {
       const int M0 = full * LG_BM;
-      gemm_large_async_kernel<MODE><<<dim3(full * tiles_n), dim3(512), 0, s>>>(A, lda, M0, W.data, W.N, W.NB, W.K, epi,
-                                                                              full, tiles_n);
+      gemm_large_async_kernel<MODE, false><<<dim3(full * tiles_n), dim3(512), 0, s>>>(A, lda, M0, W.data, W.N, W.NB,
+                                                                                     W.K, epi, full, tiles_n, 0, nullptr);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       return run_mode<MODE>(A + (int64_t)M0 * lda, lda, ragged, W, offset_rows<MODE>(epi, M0), ws, ws_elems, n_cus, s);
     }
     const int tiles_m = (M + LG_BM - 1) / LG_BM;
-    gemm_large_async_kernel<MODE><<<dim3(tiles_m * tiles_n), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, epi,
-                                                                                tiles_m, tiles_n);
+    gemm_large_async_kernel<MODE, false><<<dim3(tiles_m * tiles_n), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB,
+                                                                                       W.K, epi, tiles_m, tiles_n, 0, nullptr);
     return hipGetLastError();
   }
   auto kern = gemm_large_kernel<MODE>;
