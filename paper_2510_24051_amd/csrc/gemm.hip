@@ -227,9 +227,21 @@ __global__ void splitk_epilogue_kernel(const float* __restrict__ part, int split
   const int cols4 = cols / 4;
   if (idx >= (int64_t)M * cols4) return;
   const int m = (int)(idx / cols4), c = (int)(idx % cols4) * 4;
+  // partial sums are added in split order; eight loads are requested together so that the few threads of a
+  // small batch still keep enough bytes in flight
   auto total = [&](int n) {
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int k = 0; k < splits; ++k) s += *reinterpret_cast<const f32x4*>(part + ((int64_t)k * M + m) * NP + n);
+    const float* p = part + (int64_t)m * NP + n;
+    const int64_t stride = (int64_t)M * NP;
+    int k = 0;
+    for (; k + 8 <= splits; k += 8) {
+      f32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(p + (k + u) * stride);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; k < splits; ++k) s += *reinterpret_cast<const f32x4*>(p + k * stride);
     return s;
   };
   auto store_bf16x4 = [](bf16_t* dst, const f32x4& v) {
