@@ -44,10 +44,21 @@ hipError_t launch_pack_weight(const bf16_t* s0, int r0, const bf16_t* s1, int r1
 // ---------------------------------------------------------------------------------------------
 // RMSNorm: one workgroup per row, values kept in registers between the two passes.
 // ---------------------------------------------------------------------------------------------
-template <bool FROM_EMBED>
+// The row comes from an Embed (NORM_EMBED), from a wide fp32 row (NORM_F32), or is first formed as residual +
+// split-K partial sums of the projection before it (NORM_PARTIAL: partials added in split order, then the
+// residual, exactly as the stand-alone split-K epilogue does, and the wide row is stored as well).
+enum { NORM_EMBED = 0, NORM_F32 = 1, NORM_PARTIAL = 2 };
+struct NormPartial {
+  const float* part;    // [splits][rows][NP]
+  int splits, NP, rows;
+  const float* resid;   // [rows, H] fp32, or null: the residual is Embed ids[row]
+  float* wide;          // [rows, H] fp32 destination of residual + sum
+};
+
+template <int SRC>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ xin, const int32_t* __restrict__ ids,
                                                       const bf16_t* __restrict__ gain, bf16_t* __restrict__ out,
-                                                      int H, float eps) {
+                                                      int H, float eps, NormPartial np) {
   __shared__ float red[4];
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
@@ -59,12 +70,44 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
   for (int p = 0; p < 4; ++p) {
     int c = p * 2048 + tid * 8;
     if (p < npass && c < H) {
-      if (FROM_EMBED) {
+      if (SRC == NORM_EMBED) {
         const bf16_t* x = reinterpret_cast<const bf16_t*>(xin) + (int64_t)ids[row] * H + c;
         Pack16 pk;
         pk.u = *reinterpret_cast<const u32x4*>(x);
 #pragma unroll
         for (int e = 0; e < 8; ++e) vals[p][e] = bf16_bits_to_f32(pk.s[e]);
+      } else if (SRC == NORM_PARTIAL) {
+        f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+        const float* pp = np.part + (int64_t)row * np.NP + c;
+        const int64_t stride = (int64_t)np.rows * np.NP;
+        int k = 0;
+        for (; k + 8 <= np.splits; k += 8) {  // eight splits requested together, added in order
+          f32x4 va[8], vb[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            va[u] = *reinterpret_cast<const f32x4*>(pp + (k + u) * stride);
+            vb[u] = *reinterpret_cast<const f32x4*>(pp + (k + u) * stride + 4);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) { a += va[u]; b += vb[u]; }
+        }
+        for (; k < np.splits; ++k) {
+          a += *reinterpret_cast<const f32x4*>(pp + k * stride);
+          b += *reinterpret_cast<const f32x4*>(pp + k * stride + 4);
+        }
+        if (np.resid != nullptr) {
+          a += *reinterpret_cast<const f32x4*>(np.resid + (int64_t)row * H + c);
+          b += *reinterpret_cast<const f32x4*>(np.resid + (int64_t)row * H + c + 4);
+        } else {
+          Pack16 pk;
+          pk.u = *reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16_t*>(xin) + (int64_t)ids[row] * H + c);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { a[e] += bf16_bits_to_f32(pk.s[e]); b[e] += bf16_bits_to_f32(pk.s[4 + e]); }
+        }
+        *reinterpret_cast<f32x4*>(np.wide + (int64_t)row * H + c) = a;
+        *reinterpret_cast<f32x4*>(np.wide + (int64_t)row * H + c + 4) = b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { vals[p][e] = a[e]; vals[p][4 + e] = b[e]; }
       } else {
         const float* x = reinterpret_cast<const float*>(xin) + (int64_t)row * H + c;
         f32x4 a = *reinterpret_cast<const f32x4*>(x);
@@ -97,13 +140,22 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
 hipError_t launch_rmsnorm_embed(const bf16_t* embeds, const int32_t* ids, const bf16_t* gain, bf16_t* out, int rows,
                                 int H, float eps, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  rmsnorm_kernel<true><<<dim3(rows), dim3(256), 0, s>>>(embeds, ids, gain, out, H, eps);
+  rmsnorm_kernel<NORM_EMBED><<<dim3(rows), dim3(256), 0, s>>>(embeds, ids, gain, out, H, eps, NormPartial{});
   return hipGetLastError();
 }
 hipError_t launch_rmsnorm_f32(const float* x, const bf16_t* gain, bf16_t* out, int rows, int H, float eps,
                               hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  rmsnorm_kernel<false><<<dim3(rows), dim3(256), 0, s>>>(x, nullptr, gain, out, H, eps);
+  rmsnorm_kernel<NORM_F32><<<dim3(rows), dim3(256), 0, s>>>(x, nullptr, gain, out, H, eps, NormPartial{});
+  return hipGetLastError();
+}
+hipError_t launch_splitk_resid_norm(const float* part, int splits, int NP, const float* resid, const bf16_t* embeds,
+                                    const int32_t* ids, float* wide, const bf16_t* gain, bf16_t* out, int rows, int H,
+                                    float eps, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (splits <= 0 || NP < H || (resid == nullptr && (embeds == nullptr || ids == nullptr))) return hipErrorInvalidValue;
+  rmsnorm_kernel<NORM_PARTIAL><<<dim3(rows), dim3(256), 0, s>>>(embeds, ids, gain, out, H, eps,
+                                                              NormPartial{part, splits, NP, rows, resid, wide});
   return hipGetLastError();
 }
 
@@ -119,7 +171,38 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
                                                           const int32_t* __restrict__ tok_page,
                                                           const int32_t* __restrict__ tok_slot,
                                                           const double* __restrict__ inv_freq,
-                                                          bf16_t* __restrict__ kv_layer, int hpt) {
+                                                          bf16_t* __restrict__ kv_layer, int hpt,
+                                                          const float* __restrict__ part, int splits, int NP) {
+  // Eight consecutive values of token t from column `col` of its qkv row: read as stored, or (splits > 0) summed
+  // in split order from the partials of the QKV product and rounded to bf16 like the stored row would be.
+  auto load8 = [&](int t, int col) -> Pack16 {
+    Pack16 r;
+    if (splits > 0) {
+      f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+      const float* pp = part + (int64_t)t * NP + col;
+      const int64_t stride = (int64_t)T * NP;
+      int k = 0;
+      for (; k + 4 <= splits; k += 4) {
+        f32x4 va[4], vb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          va[u] = *reinterpret_cast<const f32x4*>(pp + (k + u) * stride);
+          vb[u] = *reinterpret_cast<const f32x4*>(pp + (k + u) * stride + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { a += va[u]; b += vb[u]; }
+      }
+      for (; k < splits; ++k) {
+        a += *reinterpret_cast<const f32x4*>(pp + k * stride);
+        b += *reinterpret_cast<const f32x4*>(pp + k * stride + 4);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { r.h[e] = f32_to_bf16(a[e]); r.h[4 + e] = f32_to_bf16(b[e]); }
+    } else {
+      r.u = *reinterpret_cast<const u32x4*>(qkv + (int64_t)t * NP + col);
+    }
+    return r;
+  };
   const int cpt = D / 16;  // work pieces per head
   const int heads = Hq + 2 * Hkv, rot = Hq + Hkv;
   const int groups = (rot + hpt - 1) / hpt;
@@ -143,9 +226,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
     const int h1 = min(rot, (g + 1) * hpt);
     for (int h = g * hpt; h < h1; ++h) {
       bf16_t* row = qkv + (int64_t)t * heads * D + (int64_t)h * D;
-      Pack16 lo, hi, olo, ohi;
-      lo.u = *reinterpret_cast<const u32x4*>(row + c * 8);
-      hi.u = *reinterpret_cast<const u32x4*>(row + D / 2 + c * 8);
+      Pack16 olo, ohi;
+      const Pack16 lo = load8(t, h * D + c * 8), hi = load8(t, h * D + D / 2 + c * 8);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float a = bf16_bits_to_f32(lo.s[e]), b = bf16_bits_to_f32(hi.s[e]);
@@ -166,12 +248,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
     const int c = (int)(idx % cpt);
     const int hv = (int)((idx / cpt) % Hkv);
     const int t = (int)(idx / ((int64_t)cpt * Hkv));
-    const bf16_t* row = qkv + (int64_t)t * heads * D + (int64_t)(rot + hv) * D;
     bf16_t* blk = kv_layer + ((int64_t)tok_page[t] * Hkv + hv) * (2 * PAGE * D);
     const int slot = tok_slot[t];
-    Pack16 a, b;
-    a.u = *reinterpret_cast<const u32x4*>(row + c * 16);
-    b.u = *reinterpret_cast<const u32x4*>(row + c * 16 + 8);
+    const Pack16 a = load8(t, (rot + hv) * D + c * 16), b = load8(t, (rot + hv) * D + c * 16 + 8);
     uint16_t* dst = reinterpret_cast<uint16_t*>(blk);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -182,7 +261,10 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
 }
 
 hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const int32_t* pos, const int32_t* tok_page,
-                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, hipStream_t s) {
+                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, const float* part,
+                              int splits, int NP, hipStream_t s) {
+  if (splits > 0 && (part == nullptr || NP < (Hq + 2 * Hkv) * D)) return hipErrorInvalidValue;
+  if (splits <= 0) NP = (Hq + 2 * Hkv) * D;  // row length of the stored qkv
   // few tokens: one head per thread keeps enough threads in flight; many tokens: share the angles of a token
   // across 8 heads (the double-precision sincos dominates the kernel otherwise)
   const int hpt = T >= 1024 ? 8 : 1;
@@ -190,7 +272,8 @@ hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const 
   int64_t total = (int64_t)T * (groups + Hkv) * (D / 16);
   if (total <= 0) return hipSuccess;
   rope_append_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(qkv, T, Hq, Hkv, D, pos, tok_page,
-                                                                                   tok_slot, inv_freq, kv_layer, hpt);
+                                                                                   tok_slot, inv_freq, kv_layer, hpt,
+                                                                                   part, splits, NP);
   return hipGetLastError();
 }
 

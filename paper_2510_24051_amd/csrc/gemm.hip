@@ -541,7 +541,7 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
 // ------------------------------------------------------------------------------------------------
 template <int MB, int MODE, int NBW>
 static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
-                               size_t ws_elems, int n_cus, hipStream_t s) {
+                               size_t ws_elems, int n_cus, hipStream_t s, int* defer) {
   const int wg_n = (W.NB + 4 * NBW - 1) / (4 * NBW);
   const int total_iters = (W.K + SK_BK - 1) / SK_BK;
   // Split K so that one round of workgroups fills the chip without spilling into a second, mostly empty round:
@@ -570,6 +570,7 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
   kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, ws);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (defer) { *defer = splits; return hipSuccess; }  // the caller's next kernel sums the partials
   const int cols = (MODE == EPI_SWIGLU) ? NP / 2 : W.N;
   int64_t total = (int64_t)M * (cols / 4);
   splitk_epilogue_kernel<MODE><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(ws, splits, M, W.N, NP, epi);
@@ -578,15 +579,15 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
 
 template <int MB, int MODE>
 static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
-                             size_t ws_elems, int n_cus, hipStream_t s) {
+                             size_t ws_elems, int n_cus, hipStream_t s, int* defer) {
   if constexpr (MODE == EPI_SWIGLU) {
-    return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+    return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   } else {
     // wide outputs (LM head): two blocks per wave halve the workgroup count and the activation reads from LDS
     if constexpr (MB <= 2)
       if ((W.NB + 3) / 4 > n_cus * (MB == 1 ? 3 : 2))
-        return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
-    return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+        return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
+    return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   }
 }
 
@@ -603,15 +604,15 @@ static EpiArgs offset_rows(EpiArgs e, int m0) {
 
 template <int MODE>
 static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
-                           size_t ws_elems, int n_cus, hipStream_t s) {
+                           size_t ws_elems, int n_cus, hipStream_t s, int* defer) {
   if (M <= 0) return hipSuccess;
-  if (M <= 32) return run_skinny<1, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
-  if (M <= 64) return run_skinny<2, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 32) return run_skinny<1, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
+  if (M <= 64) return run_skinny<2, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   // Very wide outputs (the LM head) give the tiled kernel at least one tile per CU even with a single row
   // block; above 64 rows it beats streaming the weights past 4-8 row blocks per wave (measured at 128256 x 4096:
   // 0.26 ms for up to 256 rows against 0.30 ms at 128 rows and 0.46 ms at 256 rows).
   const bool wide = W.K % 128 == 0 && (W.NB + 7) / 8 >= n_cus && M > 64;
-  if (M <= 128 && !wide) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 128 && !wide) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   if (M <= 256 && !wide && W.K % 128 == 0) {
     // One row of 256x256 tiles with K split so that the tiles fill the chip once; each split keeps at least
     // TILED_MIN_KTS k tiles, or the pipeline fill and the partial sums outweigh the work.
@@ -626,13 +627,14 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
                                                                                      epi, 1, tiles_n, kts, ws);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
+      if (defer) { *defer = splits; return hipSuccess; }
       const int cols = (MODE == EPI_SWIGLU) ? NP / 2 : W.N;
       const int64_t total = (int64_t)M * (cols / 4);
       splitk_epilogue_kernel<MODE><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(ws, splits, M, W.N, NP, epi);
       return hipGetLastError();
     }
   }
-  if (M <= 256 && MODE != EPI_SWIGLU && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s);
+  if (M <= 256 && MODE != EPI_SWIGLU && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   if (W.K % 128 == 0) {
     const int tiles_n = (W.NB + 7) / 8;
     // A ragged last row block that would open one more round of tiles (a round = one tile per CU) costs a whole
@@ -645,7 +647,8 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
                                                                                      W.K, epi, full, tiles_n, 0, nullptr);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
-      return run_mode<MODE>(A + (int64_t)M0 * lda, lda, ragged, W, offset_rows<MODE>(epi, M0), ws, ws_elems, n_cus, s);
+      return run_mode<MODE>(A + (int64_t)M0 * lda, lda, ragged, W, offset_rows<MODE>(epi, M0), ws, ws_elems, n_cus, s,
+                            nullptr);
     }
     const int tiles_m = (M + LG_BM - 1) / LG_BM;
     gemm_large_async_kernel<MODE, false><<<dim3(tiles_m * tiles_n), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB,
@@ -662,13 +665,16 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
 }
 
 hipError_t launch_gemm(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* splitk_ws,
-                       size_t splitk_elems, int n_cus, hipStream_t s) {
+                       size_t splitk_elems, int n_cus, hipStream_t s, int* deferred_splits) {
+  // Deferral is only offered where the whole product goes through one split-K launch (at most 256 rows).
+  int* defer = (deferred_splits && M <= 256) ? deferred_splits : nullptr;
+  if (deferred_splits) *deferred_splits = 0;
   switch (epi.mode) {
-    case EPI_STORE_BF16: return run_mode<EPI_STORE_BF16>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
-    case EPI_RESID_EMBED: return run_mode<EPI_RESID_EMBED>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
-    case EPI_SWIGLU: return run_mode<EPI_SWIGLU>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
-    case EPI_RESID_OUT: return run_mode<EPI_RESID_OUT>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
-    case EPI_STORE_F32: return run_mode<EPI_STORE_F32>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s);
+    case EPI_STORE_BF16: return run_mode<EPI_STORE_BF16>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s, defer);
+    case EPI_RESID_EMBED: return run_mode<EPI_RESID_EMBED>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s, defer);
+    case EPI_SWIGLU: return run_mode<EPI_SWIGLU>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s, defer);
+    case EPI_RESID_OUT: return run_mode<EPI_RESID_OUT>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s, defer);
+    case EPI_STORE_F32: return run_mode<EPI_STORE_F32>(A, lda, M, W, epi, splitk_ws, splitk_elems, n_cus, s, defer);
   }
   return hipErrorInvalidValue;
 }

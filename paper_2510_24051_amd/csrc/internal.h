@@ -144,8 +144,17 @@ hipError_t launch_rmsnorm_embed(const bf16_t* embeds, const int32_t* ids, const 
                                 int H, float eps, hipStream_t s);
 hipError_t launch_rmsnorm_f32(const float* x, const bf16_t* gain, bf16_t* out, int rows, int H, float eps,
                               hipStream_t s);
+// part/splits: when splits > 0 the q, k, v values are not read from qkv but summed from the split-K partials
+// [split][T][NP] of the QKV product (then rounded to bf16 as the epilogue would have stored them).
 hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const int32_t* pos, const int32_t* tok_page,
-                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, hipStream_t s);
+                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, const float* part,
+                              int splits, int NP, hipStream_t s);
+// Split-K epilogue of a residual projection fused with the RMSNorm that follows it: wide[m] = residual[m] + sum of
+// the partials [split][rows][NP] (residual: resid fp32 [rows, H], or Embed ids[m] when resid is null), and
+// out[m] = bf16(rmsnorm(wide[m]) * gain).
+hipError_t launch_splitk_resid_norm(const float* part, int splits, int NP, const float* resid, const bf16_t* embeds,
+                                    const int32_t* ids, float* wide, const bf16_t* gain, bf16_t* out, int rows, int H,
+                                    float eps, hipStream_t s);
 hipError_t launch_embed_copy(bf16_t* embeds, const int32_t* ids, int n, int H, bf16_t* buf, int to_pool,
                              hipStream_t s);
 hipError_t launch_kv_token_copy(bf16_t* kv, size_t layer_elems, int n_layers, const int32_t* src_pages,
@@ -174,8 +183,11 @@ struct EpiArgs {
   int H;
 };
 // C[M, N] = A[M, K] (bf16 row-major, leading dimension lda) x W^T with the epilogue above.
+// deferred_splits (optional): when the product was split along K, the epilogue kernel is not launched and
+// *deferred_splits receives the number of partial copies [split][M][round_up(N, 32)] left in splitk_ws, for a
+// following kernel of the caller to sum (in split order) together with its own work; 0 = the epilogue has run.
 hipError_t launch_gemm(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* splitk_ws,
-                       size_t splitk_elems, int n_cus, hipStream_t s);
+                       size_t splitk_elems, int n_cus, hipStream_t s, int* deferred_splits = nullptr);
 
 struct AttnArgs {
   const bf16_t* q;   // [T, q_stride] rotated queries

@@ -890,8 +890,11 @@ struct StageTimer {
 
 // One decoder layer.  x_in: wide [T, H] layer input, or null to read the batch's input Embeds; y_out: wide
 // [T, H] destination of the layer output, or null to store it as bf16 into the batch's output Embeds.
-static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const float* x_in, float* y_out,
-                            bool timed) {
+// carry (optional): on entry, the number of split-K partial copies of the previous layer's down projection
+// still waiting in the workspace (x_in = previous residual c->h + their sum has not been formed yet: the first
+// norm does it); on return, the same for this layer's down projection (only when y_out is given).
+static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float* x_in, float* y_out, bool timed,
+                            int* carry = nullptr) {
   const LayerWeights& L = c->layers[layer];
   const pie_model_desc& m = c->m;
   const int T = b->T, H = m.hidden, Hq = m.n_q_heads, Hkv = m.n_kv_heads, D = m.head_dim, I = m.mlp_dim;
@@ -904,25 +907,36 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
   struct Restore { pie_ctx* c; bool v; ~Restore() { c->timing = v; } } restore{c, was_timing};
   EpiArgs e{};
 
+  // LoRA pairs the batch's adapters carry in this layer, per projection
+  bool lora[PIE_N_PROJ] = {false, false, false, false, false, false, false};
+  if (b->tok_adapter)
+    for (int ad : b->used_adapters)
+      for (int pj = 0; pj < PIE_N_PROJ; ++pj)
+        if (c->lora[((size_t)ad * m.n_layers + layer) * PIE_N_PROJ + pj].rank > 0) lora[pj] = true;
+  const int RM = c->p.max_lora_rank, NL = m.n_layers;
+  const bool lora_qkv = lora[PIE_PROJ_Q] || lora[PIE_PROJ_K] || lora[PIE_PROJ_V];
+  // Small batches split their projections along K.  Where the next kernel reads the projection's output row by
+  // row anyway, it sums the partial copies itself and the separate epilogue launch is saved: the rotary step
+  // after QKV, the second norm after the output projection, the next layer's first norm after the down
+  // projection.  An adapter update that sits between the two kernels rules this out.
+  const int carried = (carry && x_in) ? *carry : 0;
+  if (carry) *carry = 0;
+
   tm.begin(PIE_STAGE_NORM1);
-  if (x_in) HIP_TRY(c, launch_rmsnorm_f32(x_in, L.g1, c->xn, T, H, m.rms_eps, s));
+  if (x_in && carried > 0)
+    HIP_TRY(c, launch_splitk_resid_norm(c->splitk, carried, L.wdown.NB * 32, c->h, nullptr, nullptr, x_in, L.g1, c->xn, T, H, m.rms_eps, s));
+  else if (x_in) HIP_TRY(c, launch_rmsnorm_f32(x_in, L.g1, c->xn, T, H, m.rms_eps, s));
   else HIP_TRY(c, launch_rmsnorm_embed(c->embeds, b->in_ids, L.g1, c->xn, T, H, m.rms_eps, s));
   tm.end(PIE_STAGE_NORM1);
 
   tm.begin(PIE_STAGE_QKV);
+  int qkv_splits = 0;
   e = EpiArgs{EPI_STORE_BF16, c->qkv, QKV, nullptr, nullptr, nullptr, 0};
-  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wqkv, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
+  HIP_TRY(c, launch_gemm(c->xn, H, T, L.wqkv, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s,
+                         lora_qkv ? nullptr : &qkv_splits));
   tm.end(PIE_STAGE_QKV);
 
-  // LoRA pairs the batch's adapters carry in this layer, per projection
-  bool lora[PIE_N_PROJ] = {false, false, false, false, false, false, false};
-  bool any_lora = false;
-  if (b->tok_adapter)
-    for (int ad : b->used_adapters)
-      for (int pj = 0; pj < PIE_N_PROJ; ++pj)
-        if (c->lora[((size_t)ad * m.n_layers + layer) * PIE_N_PROJ + pj].rank > 0) lora[pj] = any_lora = true;
-  const int RM = c->p.max_lora_rank, NL = m.n_layers;
-  if (lora[PIE_PROJ_Q] || lora[PIE_PROJ_K] || lora[PIE_PROJ_V]) {  // q, k, v share the normalised input
+  if (lora_qkv) {  // q, k, v share the normalised input
     const int KD = Hkv * D;
     HIP_TRY(c, launch_lora_down(c->xn, H, H, T, 3, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_Q, c->lora_z, RM, s));
     HIP_TRY(c, launch_lora_up(c->qkv, QKV, Hq * D, 0, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_Q, 0, c->lora_z, RM, s));
@@ -931,7 +945,8 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
   }
 
   tm.begin(PIE_STAGE_ROPE_APPEND);
-  HIP_TRY(c, launch_rope_append(c->qkv, T, Hq, Hkv, D, b->pos, b->tok_page, b->tok_slot, c->inv_freq, kv_layer, s));
+  HIP_TRY(c, launch_rope_append(c->qkv, T, Hq, Hkv, D, b->pos, b->tok_page, b->tok_slot, c->inv_freq, kv_layer,
+                                c->splitk, qkv_splits, L.wqkv.NB * 32, s));
   tm.end(PIE_STAGE_ROPE_APPEND);
 
   AttnArgs a{};
@@ -953,8 +968,10 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
   }
 
   tm.begin(PIE_STAGE_OPROJ);
+  int o_splits = 0;
   e = EpiArgs{EPI_RESID_EMBED, c->h, H, c->embeds, b->in_ids, x_in, H};
-  HIP_TRY(c, launch_gemm(c->attn, Hq * D, T, L.wo, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
+  HIP_TRY(c, launch_gemm(c->attn, Hq * D, T, L.wo, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s,
+                         lora[PIE_PROJ_O] ? nullptr : &o_splits));
   tm.end(PIE_STAGE_OPROJ);
 
   if (lora[PIE_PROJ_O]) {  // h += scale * B (A attn), before the second norm reads h
@@ -963,7 +980,9 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
   }
 
   tm.begin(PIE_STAGE_NORM2);
-  HIP_TRY(c, launch_rmsnorm_f32(c->h, L.g2, c->xn, T, H, m.rms_eps, s));
+  if (o_splits > 0)
+    HIP_TRY(c, launch_splitk_resid_norm(c->splitk, o_splits, L.wo.NB * 32, x_in, c->embeds, b->in_ids, c->h, L.g2, c->xn, T, H, m.rms_eps, s));
+  else HIP_TRY(c, launch_rmsnorm_f32(c->h, L.g2, c->xn, T, H, m.rms_eps, s));
   tm.end(PIE_STAGE_NORM2);
 
   tm.begin(PIE_STAGE_GATEUP);
@@ -985,11 +1004,11 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, const
     HIP_TRY(c, launch_lora_down(c->act, I, I, T, 1, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_DOWN, c->lora_z, RM, s));
     HIP_TRY(c, launch_lora_up(c->h, H, H, 1, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_DOWN, 0, c->lora_z, RM, s));
   }
-  (void)any_lora;
 
   tm.begin(PIE_STAGE_DOWN);
   e = EpiArgs{EPI_RESID_OUT, y_out, y_out ? H : 0, c->embeds, b->out_ids, c->h, H};
-  HIP_TRY(c, launch_gemm(c->act, I, T, L.wdown, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
+  HIP_TRY(c, launch_gemm(c->act, I, T, L.wdown, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s,
+                         (carry && y_out) ? carry : nullptr));
   tm.end(PIE_STAGE_DOWN);
   c->last_T = T;
   return PIE_OK;
@@ -1011,9 +1030,10 @@ extern "C" pie_status pie_forward_all(pie_ctx* c, const pie_batch* b) {
   for (int l = 0; l < NL; ++l)
     if (!c->layers[l].loaded) return fail(c, PIE_EINVAL, "pie_forward_all: layer %d has no weights", l);
   if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "batch larger than the context");
+  int carry = 0;
   for (int l = 0; l < NL; ++l) {
     // the layer output stays wide between layers; only the last layer stores bf16 Embeds
-    pie_status st = run_layer(c, l, b, l == 0 ? nullptr : c->x32, l == NL - 1 ? nullptr : c->x32, NL == 1);
+    pie_status st = run_layer(c, l, b, l == 0 ? nullptr : c->x32, l == NL - 1 ? nullptr : c->x32, NL == 1, &carry);
     if (st != PIE_OK) return st;
   }
   return PIE_OK;
