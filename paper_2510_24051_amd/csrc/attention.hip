@@ -82,7 +82,7 @@ __device__ __forceinline__ void attn_step(AttnState<D>& st, const bf16x8 (&kf)[D
   }
   float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
   mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
-  mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;  // scale > 0; -inf stays -inf
+  mx = max_xor32(mx) * scale_log2;  // scale > 0; -inf stays -inf
   const float m_new = fmaxf(st.m, mx);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
   if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0ull) {
@@ -135,7 +135,7 @@ __device__ __forceinline__ void attn_softmax(AttnState<D>& st, f32x16 s, uint32_
   }
   float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
   mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
-  mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+  mx = max_xor32(mx) * scale_log2;
   // The reference point st.m of the exponentials only has to stay within RESCALE_SLACK (in log2 units) of the
   // running maximum: weights up to 2^RESCALE_SLACK are harmless in fp32 sums and keep their relative precision
   // in bf16, and the final division by the sum of the same weights cancels the reference.  So the accumulators
@@ -329,8 +329,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
     }
   };
   auto end_segment = [&]() {
-    float l_tot = st_l + __shfl_xor(st_l, 16);
-    l_tot += __shfl_xor(l_tot, 32);
+    const float l_tot = sum_xor32(sum_xor16(st_l));
     if (valid) {
       const int64_t prow = (int64_t)cur_sg * rows_cap + qcol;
       if (g4 == 0) {
@@ -390,8 +389,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
       sv[4 + e] = ((bits_b >> e) & 1u) ? sb[e] * a.scale_log2 : -INFINITY;
       mx = fmaxf(mx, fmaxf(sv[e], sv[4 + e]));
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_xor32(max_xor16(mx));
     const float m_new = fmaxf(st_m, mx);
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(st_m - m_safe);
@@ -652,7 +650,7 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
     PIE_WAIT_VM(0);
 #undef PIE_WAIT_VM
   }
-  const float l_tot = st.l + __shfl_xor(st.l, 32);
+  const float l_tot = sum_xor32(st.l);
   if (!valid) return;
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   bf16_t* orow = a.out + (int64_t)(rq.tok0 + i_tok) * a.Hq * D + (hk * G + hg) * D;
@@ -702,7 +700,7 @@ __global__ __launch_bounds__(512) void attn_prefill_direct_kernel(AttnArgs a, co
     const uint32_t bits_b = has_b ? key_bits(rq, a.mask_words, i_ld, pl_b, g, valid) : 0u;
     attn_step<D>(st, kf, qf, va, vb, bits_a, bits_b, a.scale_log2);
   }
-  const float l_tot = st.l + __shfl_xor(st.l, 32);
+  const float l_tot = sum_xor32(st.l);
   if (!valid) return;
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   bf16_t* orow = a.out + (int64_t)(rq.tok0 + i_tok) * a.Hq * D + (hk * G + hg) * D;
