@@ -496,8 +496,8 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, const int32_
 // instruction; the page block is already in operand order) into a ring of four stages, so the copies of the
 // next three pairs are in flight while a pair is computed.  Every step issues exactly one copy batch (past the
 // end it re-reads the last pair into a stage nobody consumes), which keeps the wait-counter arithmetic
-// uniform: a pair has landed when at most two younger batches are outstanding.  Page ids sit across the lanes
-// of two registers (refilled every 64 pairs); mask words are fetched with the copy, a stage ahead of their use.
+// uniform: a pair has landed when at most two younger batches are outstanding.  Page ids are read with scalar
+// loads one pair ahead; mask words are fetched with the copy, three steps ahead of their use.
 template <int D, int G>
 __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
   constexpr int BLK = 2 * PAGE * D;            // elements of one (page, head) block: K part then V part
@@ -527,19 +527,20 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
   }
   const int n_pairs = (v_end + 1) / 2;
   if (n_pairs > 0) {
-    int win0 = 0, vphys_lo = 0, vphys_hi = 0, vlog_lo = 0, vlog_hi = 0;
-    auto load_window = [&](int w0) {
-      win0 = w0;
-      const int base = rq.visit0 + w0;
-      vphys_lo = w0 + lane < v_end ? a.visit_phys[base + lane] : 0;
-      vphys_hi = w0 + lane + 64 < v_end ? a.visit_phys[base + lane + 64] : 0;
-      vlog_lo = w0 + lane < v_end ? a.visit_logical[base + lane] : 0;
-      vlog_hi = w0 + lane + 64 < v_end ? a.visit_logical[base + lane + 64] : 0;
-    };
-    auto page_of = [&](int v, int& phys, int& logical) {  // v is workgroup-uniform, inside the window
-      const int i = v - win0, src = i & 63;
-      phys = __builtin_amdgcn_readlane(i < 64 ? vphys_lo : vphys_hi, src);
-      logical = __builtin_amdgcn_readlane(i < 64 ? vlog_lo : vlog_hi, src);
+    // Page ids are workgroup-uniform: they are read through the constant address space (scalar loads, which do
+    // not count as vector memory operations, so waiting for them never drains the copies in flight), one pair
+    // ahead of the pair that is started.
+    typedef const __attribute__((address_space(4))) int32_t* const_i32;
+    const const_i32 vis_phys = (const_i32)(a.visit_phys + rq.visit0);
+    const const_i32 vis_log = (const_i32)(a.visit_logical + rq.visit0);
+    int nx_pa = 0, nx_la = 0, nx_pb = 0, nx_lb = 0;
+    auto fetch_ids = [&](int pair) {  // ids of pair min(pair, n_pairs - 1); a missing second page repeats the first
+      const int v = (pair < n_pairs ? pair : n_pairs - 1) * 2;
+      const int v2 = v + 1 < v_end ? v + 1 : v;
+      nx_pa = vis_phys[v];
+      nx_la = vis_log[v];
+      nx_pb = vis_phys[v2];
+      nx_lb = vis_log[v2];
     };
     const bf16_t* kvh = a.kv + (int64_t)hk * BLK + lane * 8;
     const int64_t page_stride = (int64_t)a.Hkv * BLK;
@@ -552,13 +553,11 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
     const int first_lim = rq.kv_len - rq.n_new + it.qb * 32;
     auto start_pair = [&](bf16_t* stage, int pair, Meta& md) {
       const int pc = pair < n_pairs ? pair : n_pairs - 1;
-      const int v = pc * 2;
-      if (v - win0 >= 128) load_window(v);
-      int pp_a, pp_b;
-      page_of(v, pp_a, md.pl_a);
-      md.has_b = v + 1 < v_end;
-      if (md.has_b) page_of(v + 1, pp_b, md.pl_b);
-      else { pp_b = pp_a; md.pl_b = md.pl_a; }
+      const int pp_a = nx_pa, pp_b = nx_pb;  // fetched by the previous call (pairs are started in order)
+      md.pl_a = nx_la;
+      md.pl_b = nx_lb;
+      md.has_b = pc * 2 + 1 < v_end;
+      fetch_ids(pair + 1);
       md.full = rows_full && md.has_b && max(md.pl_a, md.pl_b) * PAGE + PAGE - 1 <= first_lim;
       if (has_bitmap && valid) { md.mw_a = mrow[md.pl_a >> 1]; md.mw_b = mrow[md.pl_b >> 1]; }
       const bf16_t* sa = kvh + (int64_t)pp_a * page_stride;
@@ -601,21 +600,23 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
         bits_a = bits_of(md.mw_a, md.pl_a);
         bits_b = md.has_b ? bits_of(md.mw_b, md.pl_b) : 0u;
       }
-      bf16x8 pa, pb;
-      attn_softmax<D>(st, sc, bits_a, bits_b, a.scale_log2, pa, pb);
+      // the V operands are requested before the softmax arithmetic, which hides their LDS latency
       bf16x8 va[D / 32], vb[D / 32];
 #pragma unroll
       for (int bb = 0; bb < D / 32; ++bb) {
         va[bb] = *reinterpret_cast<const bf16x8*>(stage + voff + bb * 512);
         vb[bb] = *reinterpret_cast<const bf16x8*>(stage + BLK + voff + bb * 512);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      bf16x8 pa, pb;
+      attn_softmax<D>(st, sc, bits_a, bits_b, a.scale_log2, pa, pb);
       attn_pv<D>(st, va, vb, pa, pb);
     };
 #define PIE_WAIT_VM(n) PIE_S_WAIT_VMCNT(n)
     // Step i: the scores of pair i+1 are issued to the matrix cores first, so they run under the softmax
     // arithmetic of pair i.  A stage is read in two consecutive steps (K, then V), the ring has four stages,
     // two pairs are in flight.
-    load_window(0);
+    fetch_ids(0);
     start_pair(st0, 0, m0);
     start_pair(st1, 1, m1);
     start_pair(st2, 2, m2);
