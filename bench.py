@@ -143,9 +143,9 @@ def main():
         for k, v in ctx.stage_times().items():
             acc[k] = acc.get(k, 0.0) + v
     stages = {k: v / n_prof for k, v in acc.items() if v > 0}
-    # Decode attention again with forward calls back to back.  The kernel that follows get_next_dist pays for
-    # the write-back of the logits that call left dirty in the caches (about 10 us here); in a model of several
-    # layers only the first layer is in that position, so both figures are reported.
+    # Decode attention again with forward calls back to back, for comparison: a kernel that leaves many dirty
+    # cache lines behind (get_next_dist once did) slows the next kernel that streams from HBM, and in a model of
+    # several layers only the first layer follows get_next_dist.
     attn_b2b_ms = 0.0
     for _ in range(n_prof):
         ctx.forward(0, pb)

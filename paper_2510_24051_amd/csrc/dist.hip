@@ -195,7 +195,9 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
   if (split_tie) {
     // ids ascend with (j, thread, e): walk j outermost; within a j the workgroup's ids are tid*4 + e
     uint32_t eq_seen = 0u;
-    for (int j = 0; j < TC_PER / 4 && eq_seen < need_eq; ++j) {  // eq_seen is uniform across the workgroup
+#pragma unroll  // keys[] must only be indexed by constants, or the array is placed in scratch memory
+    for (int j = 0; j < TC_PER / 4; ++j) {
+      if (eq_seen >= need_eq) break;  // eq_seen is uniform across the workgroup
       uint32_t mine = 0u;
 #pragma unroll
       for (int e = 0; e < 4; ++e) mine += (keys[j * 4 + e] == kth && keys[j * 4 + e] != 0u) ? 1u : 0u;

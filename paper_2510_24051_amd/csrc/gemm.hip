@@ -634,7 +634,9 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
       return hipGetLastError();
     }
   }
-  if (M <= 256 && MODE != EPI_SWIGLU && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
+  if constexpr (MODE != EPI_SWIGLU) {  // (eight row blocks of gate/up pairs would not fit the register file)
+    if (M <= 256 && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
+  }
   if (W.K % 128 == 0) {
     const int tiles_n = (W.NB + 7) / 8;
     // A ragged last row block that would open one more round of tiles (a round = one tile per CU) costs a whole
