@@ -41,9 +41,10 @@ __host__ __device__ __forceinline__ int v_elem_offset(int t, int d, int D) {
 
 // ---- LoRA adapters ---------------------------------------------------------------------------
 struct LoraPair {  // one projection of one layer of one adapter; device copies owned by the context
-  bf16_t* A = nullptr;  // [rank, in]
-  bf16_t* B = nullptr;  // [out, rank]
+  bf16_t* A = nullptr;  // [rank_p, in], rows past the rank are zero
+  bf16_t* B = nullptr;  // [out, rank_p], columns past the rank are zero
   int32_t rank = 0;
+  int32_t rank_p = 0;   // rank rounded up to a multiple of 16 (one MFMA contraction step)
   float scale = 0.f;
 };
 
@@ -81,7 +82,10 @@ struct pie_batch {
   std::vector<int32_t> out_ids_host;  // host copy of the output Embed ids (pie_forward_dist)
   void* dev_blob = nullptr;  // single allocation holding every array below
   int32_t *in_ids = nullptr, *out_ids = nullptr, *pos = nullptr, *tok_page = nullptr, *tok_slot = nullptr;
-  int32_t* tok_adapter = nullptr;      // [T] adapter of each token's request, -1 = none (null: no adapters)
+  // tokens of requests that name an adapter, grouped by adapter in tiles of 32 rows (null / 0: no adapters)
+  int32_t* lora_rows = nullptr;        // [n_lora_tiles * 32] token index, -1 = padding
+  int32_t* lora_tile_ad = nullptr;     // [n_lora_tiles] adapter of the tile
+  int n_lora_tiles = 0;
   std::vector<int32_t> used_adapters;  // host: distinct adapters named by the batch
   int32_t *visit_phys = nullptr, *visit_logical = nullptr;
   uint32_t* mask_words = nullptr;
@@ -119,7 +123,8 @@ struct pie_ctx {
   std::vector<uint16_t> page_mask;     // host: token-level visibility bits of every KvPage (mask_kvpage), all layers
   std::vector<LoraPair> lora;          // host mirror of the adapter table [max_adapters][n_layers][PIE_N_PROJ]
   LoraPair* lora_dev = nullptr;        // the same table on the device
-  float* lora_z = nullptr;             // [T, 3, max_lora_rank] fp32: A x of up to three projections sharing an input
+  float* lora_z = nullptr;             // [lora_z_rows, 3, padded max rank] fp32: A x of up to three projections sharing an input
+  size_t lora_z_rows = 0;
   float* gu32 = nullptr;               // [T, 2 I] fp32 gate/up sums (packed column order) for adapted gate/up
   float* x32 = nullptr;                // [T, H] wide layer input of the layers after the first (n_layers > 1)
   // workspace
@@ -209,12 +214,16 @@ hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_d
                              hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s);
 
-hipError_t launch_lora_down(const bf16_t* x, int ldx, int in, int T, int n_slots, const int32_t* tok_adapter,
-                            const LoraPair* table, int layer, int n_layers, int proj0, float* z, int rmax,
-                            hipStream_t s);
-hipError_t launch_lora_up(void* dst, int ld, int out, int kind, int col0, int T, const int32_t* tok_adapter,
-                          const LoraPair* table, int layer, int n_layers, int proj, int slot, const float* z, int rmax,
-                          hipStream_t s);
+// rows / tile_ad: the batch's adapter tiles (32 rows each); z: [ksplits][n_tiles * 32, 3, rmax_p] fp32, where
+// ksplits (from lora_ksplits, the same for the down and the up launch of a projection group) splits the input
+// dimension over workgroups when the batch has few tiles; z_rows = rows of 3 * rmax_p floats the buffer holds
+int lora_ksplits(int n_tiles, int n_slots, int in, int rmax_p, size_t z_rows);
+hipError_t launch_lora_down(const bf16_t* x, int ldx, int in, int n_tiles, int n_slots, const int32_t* rows,
+                            const int32_t* tile_ad, const LoraPair* table, int layer, int n_layers, int proj0, float* z,
+                            int rmax_p, int ksplits, hipStream_t s);
+hipError_t launch_lora_up(void* dst, int ld, int out, int kind, int col0, int kd, int n_tiles, const int32_t* rows,
+                          const int32_t* tile_ad, const LoraPair* table, int layer, int n_layers, int proj, int slot,
+                          const float* z, int rmax_p, int ksplits, hipStream_t s);
 hipError_t launch_swiglu_f32(const float* gu, int I, bf16_t* act, int T, hipStream_t s);
 
 int topk_chunks(int V, int k);  // chunks per row used by launch_topk (<= 16), 0 if unsupported

@@ -107,7 +107,10 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
   if (p->max_adapters > 0) {
     c->lora.assign((size_t)p->max_adapters * m->n_layers * PIE_N_PROJ, LoraPair());
     chk(dev_alloc(&c->lora_dev, c->lora.size(), true, c->stream));
-    chk(dev_alloc(&c->lora_z, T * 3 * p->max_lora_rank, false, c->stream));
+    // rows: every token once, each adapter's group padded to whole tiles of 32; at least 2048 so that small
+    // batches can split the input dimension over workgroups (partial copies)
+    c->lora_z_rows = std::max<size_t>(T + 32 * (size_t)p->max_adapters, 2048);
+    chk(dev_alloc(&c->lora_z, c->lora_z_rows * 3 * round_up(p->max_lora_rank, 16), false, c->stream));
   }
   c->embed_pos.assign((size_t)p->n_embeds, -1);
   c->page_mask.assign((size_t)p->n_kv_pages, 0xFFFFu);
@@ -268,7 +271,8 @@ extern "C" pie_status pie_load_adapter(pie_ctx* c, int32_t adapter, int32_t laye
   if (lp.B) (void)hipFree(lp.B);
   lp = LoraPair();
   if (rank > 0 && A && B) {
-    const size_t a_bytes = (size_t)rank * ins[proj] * sizeof(bf16_t), b_bytes = (size_t)outs[proj] * rank * sizeof(bf16_t);
+    const int rank_p = round_up(rank, 16);
+    const size_t a_bytes = (size_t)rank_p * ins[proj] * sizeof(bf16_t), b_bytes = (size_t)outs[proj] * rank_p * sizeof(bf16_t);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&lp.A), a_bytes);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&lp.B), b_bytes);
     if (e != hipSuccess) {
@@ -276,8 +280,13 @@ extern "C" pie_status pie_load_adapter(pie_ctx* c, int32_t adapter, int32_t laye
       lp = LoraPair();
       return fail(c, e == hipErrorOutOfMemory ? PIE_ENOMEM : PIE_EHIP, "pie_load_adapter: %s", hipGetErrorString(e));
     }
-    HIP_TRY(c, hipMemcpyAsync(lp.A, A, a_bytes, hipMemcpyDeviceToDevice, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(lp.B, B, b_bytes, hipMemcpyDeviceToDevice, c->stream));
+    // zero padding: rows rank .. rank_p of A, columns rank .. rank_p of every row of B
+    HIP_TRY(c, hipMemsetAsync(lp.A, 0, a_bytes, c->stream));
+    HIP_TRY(c, hipMemsetAsync(lp.B, 0, b_bytes, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(lp.A, A, (size_t)rank * ins[proj] * sizeof(bf16_t), hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(c, hipMemcpy2DAsync(lp.B, (size_t)rank_p * sizeof(bf16_t), B, (size_t)rank * sizeof(bf16_t),
+                                (size_t)rank * sizeof(bf16_t), (size_t)outs[proj], hipMemcpyDeviceToDevice, c->stream));
+    lp.rank_p = rank_p;
     lp.rank = rank;
     lp.scale = scale;
     if ((proj == PIE_PROJ_GATE || proj == PIE_PROJ_UP) && !c->gu32) {
@@ -472,8 +481,8 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   if (b->tok_indptr[0] != 0 || b->tok_indptr[R] != T) return fail(c, PIE_EINVAL, "tok_indptr must run from 0 to n_tokens");
   if (b->page_indptr[0] != 0) return fail(c, PIE_EINVAL, "page_indptr must start at 0");
 
-  std::vector<int32_t> tok_adapter;
-  std::vector<int32_t> used_adapters;
+  std::vector<int32_t> tok_adapter;  // host only: adapter of each token's request
+  std::vector<int32_t> used_adapters, lora_rows, lora_tile_ad;
   if (b->adapter_ids) {
     bool any = false;
     for (int r = 0; r < R; ++r) {
@@ -598,6 +607,13 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
       for (int i = 0; i < reqs[r].n_new; ++i) tok_adapter[reqs[r].tok0 + i] = ad;
       if (ad >= 0 && std::find(used_adapters.begin(), used_adapters.end(), ad) == used_adapters.end()) used_adapters.push_back(ad);
     }
+  // the adapted tokens grouped by adapter, each group padded to whole tiles of 32 rows
+  for (int ad : used_adapters) {
+    for (int t = 0; t < T; ++t)
+      if (tok_adapter[t] == ad) lora_rows.push_back(t);
+    while (lora_rows.size() % 32 != 0) lora_rows.push_back(-1);
+    lora_tile_ad.resize(lora_rows.size() / 32, ad);
+  }
   if (b->page_indptr[R] < 0) return fail(c, PIE_EINVAL, "bad page_indptr");
   if (validate) {
     std::unordered_set<int64_t> seen;
@@ -805,7 +821,8 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t o_in = blob.add(b->in_embed_ids, (size_t)T * 4), o_out = blob.add(b->out_embed_ids, (size_t)T * 4);
   const size_t o_pos = blob.add(b->positions ? b->positions : pos_from_embeds.data(), (size_t)T * 4), o_tp = blob.add(tok_page.data(), (size_t)T * 4);
   const size_t o_ts = blob.add(tok_slot.data(), (size_t)T * 4);
-  const size_t o_ta = blob.add(tok_adapter.empty() ? nullptr : tok_adapter.data(), tok_adapter.size() * 4, 4);
+  const size_t o_lr = blob.add(lora_rows.empty() ? nullptr : lora_rows.data(), lora_rows.size() * 4, 4);
+  const size_t o_lt = blob.add(lora_tile_ad.empty() ? nullptr : lora_tile_ad.data(), lora_tile_ad.size() * 4, 4);
   const size_t o_vp = blob.add(visit_phys.data(), visit_phys.size() * 4, 8);
   const size_t o_vl = blob.add(visit_logical.data(), visit_logical.size() * 4, 8);
   const size_t o_mw = blob.add(n_mask_given ? b->mask_words : nullptr, n_mask_given * 4, 0);
@@ -844,7 +861,9 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   unsigned char* d = reinterpret_cast<unsigned char*>(pb->dev_blob);
   pb->in_ids = (int32_t*)(d + o_in); pb->out_ids = (int32_t*)(d + o_out); pb->pos = (int32_t*)(d + o_pos);
   pb->tok_page = (int32_t*)(d + o_tp); pb->tok_slot = (int32_t*)(d + o_ts);
-  pb->tok_adapter = tok_adapter.empty() ? nullptr : (int32_t*)(d + o_ta);
+  pb->n_lora_tiles = (int)lora_tile_ad.size();
+  pb->lora_rows = lora_rows.empty() ? nullptr : (int32_t*)(d + o_lr);
+  pb->lora_tile_ad = lora_tile_ad.empty() ? nullptr : (int32_t*)(d + o_lt);
   pb->used_adapters = used_adapters;
   pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl);
   pb->mask_words = (uint32_t*)(d + o_mw); pb->reqs = (ReqInfo*)(d + o_rq);
@@ -909,11 +928,11 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
 
   // LoRA pairs the batch's adapters carry in this layer, per projection
   bool lora[PIE_N_PROJ] = {false, false, false, false, false, false, false};
-  if (b->tok_adapter)
+  if (b->n_lora_tiles > 0)
     for (int ad : b->used_adapters)
       for (int pj = 0; pj < PIE_N_PROJ; ++pj)
         if (c->lora[((size_t)ad * m.n_layers + layer) * PIE_N_PROJ + pj].rank > 0) lora[pj] = true;
-  const int RM = c->p.max_lora_rank, NL = m.n_layers;
+  const int RM = round_up(c->p.max_lora_rank, 16), NL = m.n_layers, LT = b->n_lora_tiles;
   const bool lora_qkv = lora[PIE_PROJ_Q] || lora[PIE_PROJ_K] || lora[PIE_PROJ_V];
   // Small batches split their projections along K.  Where the next kernel reads the projection's output row by
   // row anyway, it sums the partial copies itself and the separate epilogue launch is saved: the rotary step
@@ -938,10 +957,9 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
 
   if (lora_qkv) {  // q, k, v share the normalised input
     const int KD = Hkv * D;
-    HIP_TRY(c, launch_lora_down(c->xn, H, H, T, 3, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_Q, c->lora_z, RM, s));
-    HIP_TRY(c, launch_lora_up(c->qkv, QKV, Hq * D, 0, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_Q, 0, c->lora_z, RM, s));
-    HIP_TRY(c, launch_lora_up(c->qkv, QKV, KD, 0, Hq * D, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_K, 1, c->lora_z, RM, s));
-    HIP_TRY(c, launch_lora_up(c->qkv, QKV, KD, 0, Hq * D + KD, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_V, 2, c->lora_z, RM, s));
+    const int ks = lora_ksplits(LT, 3, H, RM, c->lora_z_rows);
+    HIP_TRY(c, launch_lora_down(c->xn, H, H, LT, 3, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_Q, c->lora_z, RM, ks, s));
+    HIP_TRY(c, launch_lora_up(c->qkv, QKV, QKV, 3, Hq * D, KD, LT, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_Q, 0, c->lora_z, RM, ks, s));
   }
 
   tm.begin(PIE_STAGE_ROPE_APPEND);
@@ -975,8 +993,9 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
   tm.end(PIE_STAGE_OPROJ);
 
   if (lora[PIE_PROJ_O]) {  // h += scale * B (A attn), before the second norm reads h
-    HIP_TRY(c, launch_lora_down(c->attn, Hq * D, Hq * D, T, 1, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_O, c->lora_z, RM, s));
-    HIP_TRY(c, launch_lora_up(c->h, H, H, 1, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_O, 0, c->lora_z, RM, s));
+    const int ks = lora_ksplits(LT, 1, Hq * D, RM, c->lora_z_rows);
+    HIP_TRY(c, launch_lora_down(c->attn, Hq * D, Hq * D, LT, 1, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_O, c->lora_z, RM, ks, s));
+    HIP_TRY(c, launch_lora_up(c->h, H, H, 1, 0, 0, LT, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_O, 0, c->lora_z, RM, ks, s));
   }
 
   tm.begin(PIE_STAGE_NORM2);
@@ -990,9 +1009,10 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
     // the update sits inside the nonlinearity: fp32 gate/up sums, update, then the SwiGLU product
     e = EpiArgs{EPI_STORE_F32, c->gu32, 2 * I, nullptr, nullptr, nullptr, 0};
     HIP_TRY(c, launch_gemm(c->xn, H, T, L.wgu, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
-    HIP_TRY(c, launch_lora_down(c->xn, H, H, T, 2, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_GATE, c->lora_z, RM, s));
-    HIP_TRY(c, launch_lora_up(c->gu32, 2 * I, I, 2, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_GATE, 0, c->lora_z, RM, s));
-    HIP_TRY(c, launch_lora_up(c->gu32, 2 * I, I, 2, 32, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_UP, 1, c->lora_z, RM, s));
+    const int ks = lora_ksplits(LT, 2, H, RM, c->lora_z_rows);
+    HIP_TRY(c, launch_lora_down(c->xn, H, H, LT, 2, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_GATE, c->lora_z, RM, ks, s));
+    HIP_TRY(c, launch_lora_up(c->gu32, 2 * I, I, 2, 0, 0, LT, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_GATE, 0, c->lora_z, RM, ks, s));
+    HIP_TRY(c, launch_lora_up(c->gu32, 2 * I, I, 2, 32, 0, LT, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_UP, 1, c->lora_z, RM, ks, s));
     HIP_TRY(c, launch_swiglu_f32(c->gu32, I, c->act, T, s));
   } else {
     e = EpiArgs{EPI_SWIGLU, c->act, I, nullptr, nullptr, nullptr, 0};
@@ -1001,8 +1021,9 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
   tm.end(PIE_STAGE_GATEUP);
 
   if (lora[PIE_PROJ_DOWN]) {  // added to the residual the down projection's epilogue reads
-    HIP_TRY(c, launch_lora_down(c->act, I, I, T, 1, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_DOWN, c->lora_z, RM, s));
-    HIP_TRY(c, launch_lora_up(c->h, H, H, 1, 0, T, b->tok_adapter, c->lora_dev, layer, NL, PIE_PROJ_DOWN, 0, c->lora_z, RM, s));
+    const int ks = lora_ksplits(LT, 1, I, RM, c->lora_z_rows);
+    HIP_TRY(c, launch_lora_down(c->act, I, I, LT, 1, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_DOWN, c->lora_z, RM, ks, s));
+    HIP_TRY(c, launch_lora_up(c->h, H, H, 1, 0, 0, LT, b->lora_rows, b->lora_tile_ad, c->lora_dev, layer, NL, PIE_PROJ_DOWN, 0, c->lora_z, RM, ks, s));
   }
 
   tm.begin(PIE_STAGE_DOWN);

@@ -84,6 +84,20 @@ def test_adapter_head_dim_128_ragged():
     compare(dw, adapters, [1, 3, 1, -1], "D128 ragged, odd ranks", max_rank=8)
 
 
+def test_adapter_many_rows_and_rank_blocks():
+    """Adapter groups longer than one 32-row tile (prefill requests of 70 and 45 tokens, one adapter shared by a
+    prefill and several decode requests), a rank above 32 (two blocks of rank columns) and one that is no
+    multiple of 16, on every projection."""
+    m = W.ModelDesc(hidden=256, n_q_heads=8, n_kv_heads=2, head_dim=64, mlp_dim=512, vocab=512, page_size=16,
+                    rms_eps=1e-5, rope_theta=1e4, n_layers=2)
+    reqs = [W.RequestSpec(70, 19), W.RequestSpec(1, 90, in_place=True), W.RequestSpec(45, 0), W.RequestSpec(1, 33),
+            W.RequestSpec(2, 64), W.RequestSpec(1, 17), W.RequestSpec(33, 5)]
+    dw = W.build_deep_workload("ad_rows", m, reqs, n_kv_pages=96, seed=6700, std=0.05, resid_std=0.05 / np.sqrt(4.0))
+    adapters = {0: W.make_adapter(m, 6700, 0, rank=40, projections=ALL, scale=0.5, std=0.05),
+                1: W.make_adapter(m, 6700, 1, rank=21, projections=ALL, scale=1.0, std=0.05)}
+    compare(dw, adapters, [0, 0, 1, 1, 0, -1, -1], "tiles and rank blocks", max_rank=40)
+
+
 def test_adapter_8b_shape_decode():
     """Rank-16 adapters on q, k, v, o (the usual targets) at the 8B widths, 16 decode requests, one layer."""
     m = W.model_8b()
