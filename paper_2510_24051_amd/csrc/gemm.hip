@@ -408,12 +408,15 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restric
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),           \
                                    (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
 
-template <int MODE, bool PARTIAL>
+// BM = 256, or 128 for products of at most 128 rows (half the accumulators and half the activation copies per wave).
+template <int MODE, bool PARTIAL, int BM>
 __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                                const bf16_t* __restrict__ Wp, int N, int NB, int K,
                                                                EpiArgs epi, int tiles_m, int tiles_n,
                                                                int kts_per_split, float* __restrict__ part) {
-  __shared__ __align__(16) bf16_t As0[LG_BM * LG_BK], As1[LG_BM * LG_BK], Bs0[LG_BN * LG_BK], Bs1[LG_BN * LG_BK];
+  static_assert(BM == 256 || BM == 128, "tile height");
+  constexpr int MI = BM / 64;  // 32-row accumulator blocks per wave, and activation copy instructions per wave
+  __shared__ __align__(16) bf16_t As0[BM * LG_BK], As1[BM * LG_BK], Bs0[LG_BN * LG_BK], Bs1[LG_BN * LG_BK];
   constexpr int GROUP_M = 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
@@ -432,29 +435,33 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
     tm = first_m + (pid % width) % gsz;
     tn = (pid % width) / gsz;
   }
-  const int m0 = tm * LG_BM, nb0 = tn * (LG_BN / 32);
+  const int m0 = tm * BM, nb0 = tn * (LG_BN / 32);
 
-  f32x16 acc[4][2];
+  f32x16 acc[MI][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // copy instruction j = wave * 4 + jj of an operand covers LDS bytes [j KiB, (j + 1) KiB)
-  //   A: rows j*8 .. j*8+7, lane -> row j*8 + lane/8, stored chunk lane%8
-  //   W: block j/4, k-step j%4 (1 KiB contiguous in the tiled weight)
-  const bf16_t* ap[4];
+  // copy instruction j of an operand covers LDS bytes [j KiB, (j + 1) KiB)
+  //   A (j = wave * MI + jj): rows j*8 .. j*8+7, lane -> row j*8 + lane/8, stored chunk lane%8
+  //   W (j = wave * 4 + jj): block j/4, k-step j%4 (1 KiB contiguous in the tiled weight)
+  const bf16_t* ap[MI];
   const bf16_t* bp[4];
 #pragma unroll
-  for (int jj = 0; jj < 4; ++jj) {
-    const int j = wave * 4 + jj;
+  for (int jj = 0; jj < MI; ++jj) {
+    const int j = wave * MI + jj;
     const int r = j * 8 + (lane >> 3);
     const int kc = (lane & 7) ^ ((r >> 1) & 7);
     int gr = m0 + r;
     gr = gr < M ? gr : M - 1;  // rows past M re-read a valid row; their results are never stored
     ap[jj] = A + (int64_t)gr * lda + kc * 8;
+  }
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const int j = wave * 4 + jj;
     int nb = nb0 + (j >> 2);
     nb = nb < NB ? nb : NB - 1;
     bp[jj] = Wp + packed_tile_offset(nb, j & 3, KB) + lane * 8;
@@ -462,15 +469,15 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
   auto issue = [&](bf16_t* As, bf16_t* Bs, int kt) {
     const int k = kt < kt1 ? kt : kt1 - 1;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) LDS_DMA16(ap[jj] + (int64_t)k * LG_BK, As + (wave * 4 + jj) * 512);
+    for (int jj = 0; jj < MI; ++jj) LDS_DMA16(ap[jj] + (int64_t)k * LG_BK, As + (wave * MI + jj) * 512);
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) LDS_DMA16(bp[jj] + (int64_t)k * 2048, Bs + (wave * 4 + jj) * 512);
   };
-  auto load_frags = [&](const bf16_t* As, const bf16_t* Bs, int s, bf16x8 (&af)[4], bf16x8 (&bfr)[2]) {
+  auto load_frags = [&](const bf16_t* As, const bf16_t* Bs, int s, bf16x8 (&af)[MI], bf16x8 (&bfr)[2]) {
     const int kc = s * 2 + (lane >> 5);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = wm * 128 + i * 32 + (lane & 31);
+    for (int i = 0; i < MI; ++i) {
+      const int r = wm * (BM / 2) + i * 32 + (lane & 31);
       af[i] = *reinterpret_cast<const bf16x8*>(As + r * LG_BK + ((kc ^ ((r >> 1) & 7)) << 3));
     }
 #pragma unroll
@@ -478,13 +485,13 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
       bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + ((wn * 2 + j) * 4 + s) * 512 + lane * 8);
   };
   auto compute = [&](const bf16_t* As, const bf16_t* Bs) {
-    bf16x8 af[2][4], bfr[2][2];
+    bf16x8 af[2][MI], bfr[2][2];
     load_frags(As, Bs, 0, af[0], bfr[0]);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       if (s + 1 < 4) load_frags(As, Bs, s + 1, af[(s + 1) & 1], bfr[(s + 1) & 1]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(af[s & 1][i], bfr[s & 1][j], acc[i][j]);
       __builtin_amdgcn_sched_barrier(0);
@@ -508,21 +515,21 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
     const int NP = NB * 32;
     float* P = part + (int64_t)blockIdx.y * M * NP;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int nb = nb0 + wn * 2 + j;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * 128 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          const int m = m0 + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
           if (m < M && nb < NB) P[(int64_t)m * NP + nb * 32 + (lane & 31)] = acc[i][j][v];
         }
       }
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int mt = m0 + wm * 128 + i * 32;
+  for (int i = 0; i < MI; ++i) {
+    const int mt = m0 + wm * (BM / 2) + i * 32;
     if (MODE == EPI_SWIGLU) {
       int nb = nb0 + wn * 2;
       if (nb < NB) epi_tile<MODE>(epi, acc[i][0], acc[i][1], mt, nb * 32, M, NB * 32, lane);
@@ -612,10 +619,10 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   // block; above 64 rows it beats streaming the weights past 4-8 row blocks per wave (measured at 128256 x 4096:
   // 0.26 ms for up to 256 rows against 0.30 ms at 128 rows and 0.46 ms at 256 rows).
   const bool wide = W.K % 128 == 0 && (W.NB + 7) / 8 >= n_cus && M > 64;
-  if (M <= 128 && !wide) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   if (M <= 256 && !wide && W.K % 128 == 0) {
-    // One row of 256x256 tiles with K split so that the tiles fill the chip once; each split keeps at least
-    // TILED_MIN_KTS k tiles, or the pipeline fill and the partial sums outweigh the work.
+    // One row of 256-column tiles (128 rows high up to 128 rows, else 256) with K split so that the tiles fill the
+    // chip once; each split keeps at least TILED_MIN_KTS k tiles, or the pipeline fill and the partial sums
+    // outweigh the work.
     const int tiles_n = (W.NB + 7) / 8, KT = W.K / LG_BK, NP = W.NB * 32;
     int splits = std::max(1, n_cus / tiles_n);
     int kts = (KT + splits - 1) / splits;
@@ -623,8 +630,12 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
     kts = std::max(kts, TILED_MIN_KTS);
     splits = (KT + kts - 1) / kts;
     if (splits > 1 && (size_t)splits * M * NP <= ws_elems) {
-      gemm_large_async_kernel<MODE, true><<<dim3(tiles_n, splits), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB, W.K,
-                                                                                     epi, 1, tiles_n, kts, ws);
+      if (M <= 128)
+        gemm_large_async_kernel<MODE, true, 128><<<dim3(tiles_n, splits), dim3(512), 0, s>>>(
+            A, lda, M, W.data, W.N, W.NB, W.K, epi, 1, tiles_n, kts, ws);
+      else
+        gemm_large_async_kernel<MODE, true, 256><<<dim3(tiles_n, splits), dim3(512), 0, s>>>(
+            A, lda, M, W.data, W.N, W.NB, W.K, epi, 1, tiles_n, kts, ws);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       if (defer) { *defer = splits; return hipSuccess; }
@@ -634,6 +645,7 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
       return hipGetLastError();
     }
   }
+  if (M <= 128 && !wide) return run_skinny<4, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   if constexpr (MODE != EPI_SWIGLU) {  // (eight row blocks of gate/up pairs would not fit the register file)
     if (M <= 256 && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   }
@@ -645,16 +657,20 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
     auto rounds = [&](int tm) { return (tm * tiles_n + n_cus - 1) / n_cus; };
     if (ragged > 0 && full > 0 && (ragged <= 128 || MODE != EPI_SWIGLU) && rounds(full + 1) > rounds(full)) {
       const int M0 = full * LG_BM;
-      gemm_large_async_kernel<MODE, false><<<dim3(full * tiles_n), dim3(512), 0, s>>>(A, lda, M0, W.data, W.N, W.NB,
-                                                                                     W.K, epi, full, tiles_n, 0, nullptr);
+      gemm_large_async_kernel<MODE, false, 256><<<dim3(full * tiles_n), dim3(512), 0, s>>>(
+          A, lda, M0, W.data, W.N, W.NB, W.K, epi, full, tiles_n, 0, nullptr);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       return run_mode<MODE>(A + (int64_t)M0 * lda, lda, ragged, W, offset_rows<MODE>(epi, M0), ws, ws_elems, n_cus, s,
                             nullptr);
     }
     const int tiles_m = (M + LG_BM - 1) / LG_BM;
-    gemm_large_async_kernel<MODE, false><<<dim3(tiles_m * tiles_n), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB,
-                                                                                       W.K, epi, tiles_m, tiles_n, 0, nullptr);
+    if (M <= 128)
+      gemm_large_async_kernel<MODE, false, 128><<<dim3(tiles_n), dim3(512), 0, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, epi,
+                                                                                   1, tiles_n, 0, nullptr);
+    else
+      gemm_large_async_kernel<MODE, false, 256><<<dim3(tiles_m * tiles_n), dim3(512), 0, s>>>(
+          A, lda, M, W.data, W.N, W.NB, W.K, epi, tiles_m, tiles_n, 0, nullptr);
     return hipGetLastError();
   }
   auto kern = gemm_large_kernel<MODE>;
