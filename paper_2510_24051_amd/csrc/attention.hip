@@ -80,8 +80,9 @@ __device__ __forceinline__ void attn_step(AttnState<D>& st, const bf16x8 (&kf)[D
 #pragma unroll
     for (int v = 0; v < 16; ++v) s[v] = ((bits >> v) & 1u) ? s[v] : -INFINITY;
   }
-  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-  mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
+  const float mx_lo = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8]));
+  const float mx_hi = max3(max3(s[9], s[10], s[11]), max3(s[12], s[13], s[14]), s[15]);
+  float mx = max3(mx_lo, mx_hi, mx_hi);
   mx = max_xor32(mx) * scale_log2;  // scale > 0; -inf stays -inf
   const float m_new = fmaxf(st.m, mx);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
@@ -133,8 +134,9 @@ __device__ __forceinline__ void attn_softmax(AttnState<D>& st, f32x16 s, uint32_
 #pragma unroll
     for (int v = 0; v < 16; ++v) s[v] = ((bits >> v) & 1u) ? s[v] : -INFINITY;
   }
-  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-  mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
+  const float mx_lo = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[8]));
+  const float mx_hi = max3(max3(s[9], s[10], s[11]), max3(s[12], s[13], s[14]), s[15]);
+  float mx = max3(mx_lo, mx_hi, mx_hi);
   mx = max_xor32(mx) * scale_log2;
   // The reference point st.m of the exponentials only has to stay within RESCALE_SLACK (in log2 units) of the
   // running maximum: weights up to 2^RESCALE_SLACK are harmless in fp32 sums and keep their relative precision

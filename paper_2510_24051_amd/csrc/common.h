@@ -33,6 +33,14 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// max(a, b, c) in one instruction.  (fmaxf chains compile to v_max_f32 pairs preceded by a canonicalising
+// v_max_f32 x, x per input, because the inputs might be signalling NaNs; MFMA results never are.)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Exchanges between the two halves of a wave (lane l and l ^ 32) and between neighbouring rows of 16 lanes
 // (l and l ^ 16) on the gfx950 swap instructions: v_permlane32_swap with the same register as both operands leaves
 // the lower half's value in one result and the upper half's in the other, for every lane; v_permlane16_swap does
