@@ -138,6 +138,20 @@ def test_large_batches_on_small_models(hidden, mlp, n_q, n_kv, T_prefill):
     compare_layer(w, what=f"T={w.batch.n_tokens} H{hidden} I{mlp} {n_q}/{n_kv}")
 
 
+@pytest.mark.parametrize("n_decode,n_prefill", [(40, 60), (100, 0), (57, 143), (129, 0), (64, 192), (1, 64)])
+def test_mid_size_batches_split_k_tiles(n_decode, n_prefill):
+    """65 to 256 rows on a model whose contraction lengths (1024, 2048) are long enough for the tiled GEMM to split
+    them across workgroups: 128-row tiles up to 128 rows, 256-row tiles above, ragged row counts in both, the
+    partial sums taken by the split-K epilogue, the rotary step and the second norm."""
+    m = small_model(64, 16, 4, hidden=1024, mlp=2048, vocab=512)
+    rng = np.random.default_rng(n_decode * 1000 + n_prefill)
+    reqs = [W.RequestSpec(1, int(c)) for c in rng.integers(0, 60, size=n_decode)]
+    if n_prefill:
+        reqs.append(W.RequestSpec(n_prefill, 7))
+    w = W.build_workload("mid", m, reqs, n_kv_pages=n_decode * 4 + 32, seed=900 + n_decode + n_prefill, std=0.012)
+    compare_layer(w, what=f"T={w.batch.n_tokens} H1024 I2048")
+
+
 # ---------------------------------------------------------------- shared prefixes (requests aliasing pages)
 def hide_span(a0, a1):
     def f(n_new, L, rng):
