@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/pie_mi355.h"
@@ -81,6 +82,7 @@ struct pie_batch {
   int32_t R = 0, T = 0;
   std::vector<int32_t> out_ids_host;  // host copy of the output Embed ids (pie_forward_dist)
   void* dev_blob = nullptr;  // single allocation holding every array below
+  size_t dev_blob_bytes = 0;
   int32_t *in_ids = nullptr, *out_ids = nullptr, *pos = nullptr, *tok_page = nullptr, *tok_slot = nullptr;
   // tokens of requests that name an adapter, grouped by adapter in tiles of 32 rows (null / 0: no adapters)
   int32_t* lora_rows = nullptr;        // [n_lora_tiles * 32] token index, -1 = padding
@@ -132,6 +134,9 @@ struct pie_ctx {
   float *h = nullptr, *splitk = nullptr, *logits = nullptr, *topk_stats = nullptr;
   unsigned long long* topk_cand = nullptr;
   size_t splitk_elems = 0;
+  // device blocks of destroyed batches, kept for the next pie_batch_create (a serving loop creates and destroys a
+  // batch per step; hipMalloc + hipFree cost more than the deserialisation itself)
+  std::vector<std::pair<void*, size_t>> blob_pool;
   int32_t* ids_dev = nullptr;  // staging for id lists of the small resource calls
   size_t ids_cap = 0;
   int last_T = 0, last_dist_n = 0;

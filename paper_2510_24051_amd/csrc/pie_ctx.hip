@@ -172,6 +172,7 @@ extern "C" pie_status pie_destroy(pie_ctx* c) {
     if (lp.B) (void)hipFree(lp.B);
   }
   for (void* b : bufs) if (b) (void)hipFree(b);
+  for (auto& blk : c->blob_pool) (void)hipFree(blk.first);
   for (int i = 0; i < 2 * PIE_N_STAGES; ++i) if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
   delete c;
   return PIE_OK;
@@ -845,7 +846,20 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t o_po = blob.add(nullptr, 0, 0);  // metadata ends here; the partial buffers are device-only
   const size_t o_pm = (o_po + part_rows * D * 4 + 255) / 256 * 256;
   const size_t total_bytes = o_pm + part_rows * 2 * 4 + 256;
-  hipError_t e = hipMalloc(&pb->dev_blob, total_bytes);
+  hipError_t e = hipSuccess;
+  {  // the smallest kept block that is large enough, else a new one (sizes in 1 MiB steps so that blocks get reused)
+    int best = -1;
+    for (int i = 0; i < (int)c->blob_pool.size(); ++i)
+      if (c->blob_pool[i].second >= total_bytes && (best < 0 || c->blob_pool[i].second < c->blob_pool[best].second)) best = i;
+    if (best >= 0) {
+      pb->dev_blob = c->blob_pool[best].first;
+      pb->dev_blob_bytes = c->blob_pool[best].second;
+      c->blob_pool.erase(c->blob_pool.begin() + best);
+    } else {
+      pb->dev_blob_bytes = (total_bytes + (1u << 20) - 1) >> 20 << 20;
+      e = hipMalloc(&pb->dev_blob, pb->dev_blob_bytes);
+    }
+  }
   if (e != hipSuccess) {
     delete pb;
     return fail(c, PIE_ENOMEM, "pie_batch_create: %s (%zu bytes)", hipGetErrorString(e), total_bytes);
@@ -881,8 +895,12 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
 
 extern "C" pie_status pie_batch_destroy(pie_ctx* c, pie_batch* b) {
   if (!b) return PIE_OK;
-  if (c) (void)hipStreamSynchronize(c->stream);
-  if (b->dev_blob) (void)hipFree(b->dev_blob);
+  if (c) (void)hipStreamSynchronize(c->stream);  // no kernel may still read the batch
+  if (b->dev_blob) {
+    constexpr size_t POOL_BLOCKS = 8;
+    if (c && c->blob_pool.size() < POOL_BLOCKS) c->blob_pool.emplace_back(b->dev_blob, b->dev_blob_bytes);
+    else (void)hipFree(b->dev_blob);
+  }
   delete b;
   return PIE_OK;
 }
