@@ -625,31 +625,35 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
     PIE_WAIT_VM(2 * IPW);
     wg_barrier();
     f32x16 s_cur = scores(st0), s_next = s_cur;
-    for (int p = 0; p < n_pairs; p += 4) {
-      PIE_WAIT_VM(IPW);
-      wg_barrier();
-      start_pair(st3, p + 3, m3);
-      s_next = scores(st1);
-      finish(st0, m0, s_cur);
-      if (p + 1 >= n_pairs) break;
-      PIE_WAIT_VM(IPW);
-      wg_barrier();
-      start_pair(st0, p + 4, m0);
-      s_cur = scores(st2);
-      finish(st1, m1, s_next);
-      if (p + 2 >= n_pairs) break;
-      PIE_WAIT_VM(IPW);
-      wg_barrier();
-      start_pair(st1, p + 5, m1);
-      s_next = scores(st3);
-      finish(st2, m2, s_cur);
-      if (p + 3 >= n_pairs) break;
-      PIE_WAIT_VM(IPW);
-      wg_barrier();
-      start_pair(st2, p + 6, m2);
-      s_cur = scores(st0);
-      finish(st3, m3, s_next);
+    // One step: wait for the pair the scores need, start the copy three pairs ahead, scores of the next pair,
+    // softmax and PV of the current one.  The loop body is four ring revolutions: at the loop header the compiler
+    // waits for every copy in flight before the first LDS read (it cannot tell across the back edge which copies
+    // may alias it), which empties the pipeline once per iteration.
+#define PIE_STEP(SA, MA, SCUR, SB, SNEXT, SC, MC, AHEAD)   \
+    PIE_WAIT_VM(IPW);                                      \
+    wg_barrier();                                          \
+    start_pair(SC, p + (AHEAD), MC);                       \
+    SNEXT = scores(SB);                                    \
+    finish(SA, MA, SCUR);
+#define PIE_REVOLUTION(BASE)                                         \
+    PIE_STEP(st0, m0, s_cur, st1, s_next, st3, m3, (BASE) + 3)       \
+    if (p + (BASE) + 1 >= n_pairs) break;                            \
+    PIE_STEP(st1, m1, s_next, st2, s_cur, st0, m0, (BASE) + 4)       \
+    if (p + (BASE) + 2 >= n_pairs) break;                            \
+    PIE_STEP(st2, m2, s_cur, st3, s_next, st1, m1, (BASE) + 5)       \
+    if (p + (BASE) + 3 >= n_pairs) break;                            \
+    PIE_STEP(st3, m3, s_next, st0, s_cur, st2, m2, (BASE) + 6)
+    for (int p = 0; p < n_pairs; p += 16) {
+      PIE_REVOLUTION(0)
+      if (p + 4 >= n_pairs) break;
+      PIE_REVOLUTION(4)
+      if (p + 8 >= n_pairs) break;
+      PIE_REVOLUTION(8)
+      if (p + 12 >= n_pairs) break;
+      PIE_REVOLUTION(12)
     }
+#undef PIE_REVOLUTION
+#undef PIE_STEP
     PIE_WAIT_VM(0);
 #undef PIE_WAIT_VM
   }
