@@ -305,8 +305,15 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
     constexpr int S = decltype(set_c)::value;
     if (has_bitmap && valid) { mw_a[S] = mrow[pl_a[S] >> 1]; mw_b[S] = mrow[pl_b[S] >> 1]; }
   };
-  auto fetch = [&](auto set_c, int j) {  // j is wave-uniform
+  // Exactly one batch of loads per call, also past the last pair (then every lane reads the first bytes of the
+  // last pair's blocks: a few cache lines, never used): with the same number of loads in flight on every path into
+  // the loop header the compiler keeps exact wait counts, and the batch requested ahead stays in flight while the
+  // current one is consumed.  (With conditional batches it waited for all outstanding loads in every compute.)
+  auto fetch = [&](auto set_c, int j_req) {  // j_req is wave-uniform
     constexpr int S = decltype(set_c)::value;
+    const bool real = j_req < n_pairs;
+    const int j = real ? j_req : n_pairs - 1;
+    const int ko = real ? koff : 0, vo = real ? voff : PAGE * D;
     const int src = (2 * j) & 63;
     const bool low = 2 * j < 64;
     const int pp_a = __builtin_amdgcn_readlane(low ? id_lo.x : id_hi.x, src);
@@ -320,14 +327,14 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
     const bf16_t* pb_ = a.kv + (int64_t)pp_b * blk;
 #pragma unroll
     for (int k = 0; k < KS; ++k) {
-      ka[S][k] = *reinterpret_cast<const bf16x8*>(pa_ + koff + k * 512);
-      kb[S][k] = *reinterpret_cast<const bf16x8*>(pb_ + koff + k * 512);
+      ka[S][k] = *reinterpret_cast<const bf16x8*>(pa_ + ko + k * 512);
+      kb[S][k] = *reinterpret_cast<const bf16x8*>(pb_ + ko + k * 512);
     }
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
-      const int vo = voff + (b >> 1) * 512 + (b & 1) * 128;
-      va[S][b] = *reinterpret_cast<const bf16x4*>(pa_ + vo);
-      vb[S][b] = *reinterpret_cast<const bf16x4*>(pb_ + vo);
+      const int vob = vo + (b >> 1) * 512 + (b & 1) * 128;
+      va[S][b] = *reinterpret_cast<const bf16x4*>(pa_ + vob);
+      vb[S][b] = *reinterpret_cast<const bf16x4*>(pb_ + vob);
     }
   };
   auto end_segment = [&]() {
@@ -420,10 +427,10 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
   std::integral_constant<int, 1> set1;
   fetch(set0, 0);
   for (int j = 0; j < n_pairs; j += 2) {
-    if (j + 1 < n_pairs) fetch(set1, j + 1);
+    fetch(set1, j + 1);
     compute(set0, set1, j);
     if (j + 1 >= n_pairs) break;
-    if (j + 2 < n_pairs) fetch(set0, j + 2);
+    fetch(set0, j + 2);
     compute(set1, set0, j + 1);
   }
   end_segment();
