@@ -248,8 +248,33 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
     const int c = (int)(idx % cpt);
     const int hv = (int)((idx / cpt) % Hkv);
     const int t = (int)(idx / ((int64_t)cpt * Hkv));
-    bf16_t* blk = kv_layer + ((int64_t)tok_page[t] * Hkv + hv) * (2 * PAGE * D);
-    const int slot = tok_slot[t];
+    const int page = tok_page[t], slot = tok_slot[t];
+    bf16_t* blk = kv_layer + ((int64_t)page * Hkv + hv) * (2 * PAGE * D);
+    // The V part keeps the 8 tokens of slots 8k .. 8k+7 next to each other for every d.  When the batch fills such
+    // an octet with consecutive tokens (prefill), the thread of its first token writes all eight at once, 16 bytes
+    // per d, and the other seven have nothing to do; single tokens (decode) store their 2-byte values one by one.
+    const int t0 = t - (slot & 7);
+    bool octet = t0 >= 0 && t0 + 7 < T;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) octet = octet && tok_page[t0 + i] == page && tok_slot[t0 + i] == (slot & ~7) + i;
+    if (octet) {
+      if (t != t0) return;
+      Pack16 a[8], b[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        a[i] = load8(t0 + i, (rot + hv) * D + c * 16);
+        b[i] = load8(t0 + i, (rot + hv) * D + c * 16 + 8);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        Pack16 oa, ob;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { oa.s[i] = a[i].s[e]; ob.s[i] = b[i].s[e]; }
+        *reinterpret_cast<u32x4*>(blk + v_elem_offset(slot, c * 16 + e, D)) = oa.u;
+        *reinterpret_cast<u32x4*>(blk + v_elem_offset(slot, c * 16 + 8 + e, D)) = ob.u;
+      }
+      return;
+    }
     const Pack16 a = load8(t, (rot + hv) * D + c * 16), b = load8(t, (rot + hv) * D + c * 16 + 8);
     uint16_t* dst = reinterpret_cast<uint16_t*>(blk);
 #pragma unroll
