@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
                                                           const int32_t* __restrict__ pos,
                                                           const int32_t* __restrict__ tok_page,
                                                           const int32_t* __restrict__ tok_slot,
-                                                          const double* __restrict__ inv_freq,
+                                                          const float* __restrict__ angles,
                                                           bf16_t* __restrict__ kv_layer, int hpt,
                                                           const float* __restrict__ part, int splits, int NP) {
   // Eight consecutive values of token t from column `col` of its qkv row: read as stored, or (splits > 0) summed
@@ -214,14 +214,13 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
     const int g = (int)((idx / cpt) % groups);
     const int t = (int)(idx / ((int64_t)cpt * groups));
     const int page = tok_page[t], slot = tok_slot[t];
-    const double p = (double)pos[t];
-    float fc[8], fs[8];
+    float fc[8], fs[8];  // cos and sin of the token's 8 angles of this piece, from the batch's table
+    {
+      const float* ang = angles + (int64_t)t * D + c * 8;
+      const f32x4 c0 = *reinterpret_cast<const f32x4*>(ang), c1 = *reinterpret_cast<const f32x4*>(ang + 4);
+      const f32x4 s0 = *reinterpret_cast<const f32x4*>(ang + D / 2), s1 = *reinterpret_cast<const f32x4*>(ang + D / 2 + 4);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      double sn, cs;
-      sincos(p * inv_freq[c * 8 + e], &sn, &cs);
-      fc[e] = (float)cs;
-      fs[e] = (float)sn;
+      for (int e = 0; e < 4; ++e) { fc[e] = c0[e]; fc[4 + e] = c1[e]; fs[e] = s0[e]; fs[4 + e] = s1[e]; }
     }
     const int h1 = min(rot, (g + 1) * hpt);
     for (int h = g * hpt; h < h1; ++h) {
@@ -285,19 +284,40 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* __restrict__ q
   }
 }
 
+// cos and sin of every (token, frequency) of a batch: angles[t][0 .. D/2) = cos, [D/2 .. D) = sin of
+// pos[t] * inv_freq[i], evaluated in double precision and rounded to float.  Positions do not change from layer to
+// layer, so the table is made once per batch and every layer's rotary step reads it.
+__global__ void rope_table_kernel(const int32_t* __restrict__ pos, const double* __restrict__ inv_freq, int T, int half,
+                                  float* __restrict__ angles) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)T * half) return;
+  const int t = (int)(idx / half), i = (int)(idx % half);
+  double sn, cs;
+  sincos((double)pos[t] * inv_freq[i], &sn, &cs);
+  angles[(int64_t)t * 2 * half + i] = (float)cs;
+  angles[(int64_t)t * 2 * half + half + i] = (float)sn;
+}
+
+hipError_t launch_rope_table(const int32_t* pos, const double* inv_freq, int T, int D, float* angles, hipStream_t s) {
+  const int64_t total = (int64_t)T * (D / 2);
+  if (total <= 0) return hipSuccess;
+  rope_table_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(pos, inv_freq, T, D / 2, angles);
+  return hipGetLastError();
+}
+
 hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const int32_t* pos, const int32_t* tok_page,
-                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, const float* part,
+                              const int32_t* tok_slot, const float* angles, bf16_t* kv_layer, const float* part,
                               int splits, int NP, hipStream_t s) {
   if (splits > 0 && (part == nullptr || NP < (Hq + 2 * Hkv) * D)) return hipErrorInvalidValue;
   if (splits <= 0) NP = (Hq + 2 * Hkv) * D;  // row length of the stored qkv
-  // few tokens: one head per thread keeps enough threads in flight; many tokens: share the angles of a token
-  // across 8 heads (the double-precision sincos dominates the kernel otherwise)
+  // few tokens: one head per thread keeps enough threads in flight; many tokens: a thread walks several heads
+  // with the same 8 angles
   const int hpt = T >= 1024 ? 8 : 1;
   const int groups = (Hq + Hkv + hpt - 1) / hpt;
   int64_t total = (int64_t)T * (groups + Hkv) * (D / 16);
   if (total <= 0) return hipSuccess;
   rope_append_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(qkv, T, Hq, Hkv, D, pos, tok_page,
-                                                                                   tok_slot, inv_freq, kv_layer, hpt,
+                                                                                   tok_slot, angles, kv_layer, hpt,
                                                                                    part, splits, NP);
   return hipGetLastError();
 }

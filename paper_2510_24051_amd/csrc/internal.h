@@ -83,6 +83,7 @@ struct pie_batch {
   std::vector<int32_t> out_ids_host;  // host copy of the output Embed ids (pie_forward_dist)
   void* dev_blob = nullptr;  // single allocation holding every array below
   size_t dev_blob_bytes = 0;
+  float* rope_angles = nullptr;  // [T, D] cos | sin of every token's rotary angles (made once per batch on the GPU)
   int32_t *in_ids = nullptr, *out_ids = nullptr, *pos = nullptr, *tok_page = nullptr, *tok_slot = nullptr;
   // tokens of requests that name an adapter, grouped by adapter in tiles of 32 rows (null / 0: no adapters)
   int32_t* lora_rows = nullptr;        // [n_lora_tiles * 32] token index, -1 = padding
@@ -157,8 +158,10 @@ hipError_t launch_rmsnorm_f32(const float* x, const bf16_t* gain, bf16_t* out, i
 // part/splits: when splits > 0 the q, k, v values are not read from qkv but summed from the split-K partials
 // [split][T][NP] of the QKV product (then rounded to bf16 as the epilogue would have stored them).
 hipError_t launch_rope_append(bf16_t* qkv, int T, int Hq, int Hkv, int D, const int32_t* pos, const int32_t* tok_page,
-                              const int32_t* tok_slot, const double* inv_freq, bf16_t* kv_layer, const float* part,
+                              const int32_t* tok_slot, const float* angles, bf16_t* kv_layer, const float* part,
                               int splits, int NP, hipStream_t s);
+// angles [T, D]: cos (first D/2) and sin (last D/2) of pos[t] * inv_freq[i], double precision rounded to float
+hipError_t launch_rope_table(const int32_t* pos, const double* inv_freq, int T, int D, float* angles, hipStream_t s);
 // Split-K epilogue of a residual projection fused with the RMSNorm that follows it: wide[m] = residual[m] + sum of
 // the partials [split][rows][NP] (residual: resid fp32 [rows, H], or Embed ids[m] when resid is null), and
 // out[m] = bf16(rmsnorm(wide[m]) * gain).

@@ -845,7 +845,8 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t part_rows = (size_t)pb->n_dsegs * pb->rows_cap;
   const size_t o_po = blob.add(nullptr, 0, 0);  // metadata ends here; the partial buffers are device-only
   const size_t o_pm = (o_po + part_rows * D * 4 + 255) / 256 * 256;
-  const size_t total_bytes = o_pm + part_rows * 2 * 4 + 256;
+  const size_t o_an = (o_pm + part_rows * 2 * 4 + 255) / 256 * 256;  // rotary angle table [T, D] floats
+  const size_t total_bytes = o_an + (size_t)T * D * 4 + 256;
   hipError_t e = hipSuccess;
   {  // the smallest kept block that is large enough, else a new one (sizes in 1 MiB steps so that blocks get reused)
     int best = -1;
@@ -866,6 +867,10 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   }
   // copy only the metadata part (everything before the partial buffers)
   e = hipMemcpyAsync(pb->dev_blob, blob.bytes.data(), blob.bytes.size(), hipMemcpyHostToDevice, c->stream);
+  if (e == hipSuccess)  // the rotary angles of the batch's positions: the same for every layer
+    e = launch_rope_table(reinterpret_cast<const int32_t*>(reinterpret_cast<unsigned char*>(pb->dev_blob) + o_pos),
+                          c->inv_freq, T, D, reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(pb->dev_blob) + o_an),
+                          c->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) {
     (void)hipFree(pb->dev_blob);
@@ -885,6 +890,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   pb->dcols = (DecodeCol*)(d + o_dc); pb->mref_indptr = (int32_t*)(d + o_mi); pb->mrefs = (int32_t*)(d + o_mr);
   pb->pitems = (PrefillItem*)(d + o_pi); pb->dec_reqs = (int32_t*)(d + o_dr);
   pb->part_o = (float*)(d + o_po); pb->part_ml = (float*)(d + o_pm);
+  pb->rope_angles = (float*)(d + o_an);
   *out = pb;
   return PIE_OK;
 }
@@ -981,7 +987,7 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
   }
 
   tm.begin(PIE_STAGE_ROPE_APPEND);
-  HIP_TRY(c, launch_rope_append(c->qkv, T, Hq, Hkv, D, b->pos, b->tok_page, b->tok_slot, c->inv_freq, kv_layer,
+  HIP_TRY(c, launch_rope_append(c->qkv, T, Hq, Hkv, D, b->pos, b->tok_page, b->tok_slot, b->rope_angles, kv_layer,
                                 c->splitk, qkv_splits, L.wqkv.NB * 32, s));
   tm.end(PIE_STAGE_ROPE_APPEND);
 
