@@ -25,7 +25,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 MFMA_RIDGE_ROWS = 312  # rows above which a bf16 GEMM stops being bound by streaming its weights
 # HBM bytes per launch of the decode-attention kernel from rocprofv3 counters (FETCH_SIZE scaled by the factor a
 # once-streamed weight matrix of known size gives, plus WRITE_SIZE); see profiles/c2_decode_pmc.md
-PMC_TRAFFIC_BYTES = {"c2": 524.3e6 + 5.1e6}
+PMC_TRAFFIC_BYTES = {"c2": 524.6e6 + 5.1e6}
 
 
 def main():
