@@ -62,6 +62,15 @@ typedef struct {
  * pie_forward / pie_get_next_dist. */
 pie_status pie_create(const pie_model_desc* model, const pie_pool_desc* pool, void* hip_stream, pie_ctx** out);
 pie_status pie_destroy(pie_ctx* ctx);
+/* A context that only deserialises and plans batches (Batch scheduler: the batch is validated and turned into the
+ * handler's work lists before anything is launched): no HIP call is made, nothing is allocated on a device, so it
+ * also works on a machine without a GPU.  `wave_slots` stands for the number of waves the decode-attention kernel
+ * keeps resident (8 per compute unit: 2048 on MI355X).  pie_batch_create (all its checks and error codes),
+ * pie_batch_work, pie_batch_destroy, pie_mask_kvpage, pie_last_error and pie_destroy work on it; every call that
+ * needs the device returns PIE_EINVAL.  For schedulers that want the cost of a batch before committing to it, and
+ * for tests of the host logic. */
+pie_status pie_create_planner(const pie_model_desc* model, const pie_pool_desc* pool, int32_t wave_slots,
+                              pie_ctx** out);
 /* Message of the last failing call on ctx (ctx may be NULL for pie_create failures); storage
  * is owned by the library and valid until the next call. */
 const char* pie_last_error(const pie_ctx* ctx);
@@ -240,6 +249,14 @@ pie_status pie_stage_times(pie_ctx* ctx, float* ms_out);
  * (what HBM has to deliver to them when pages are shared), out[5] = KV bytes the decode kernel asks for after requests
  * that share pages have been grouped (<= out[1]).  Host int64[6]. */
 pie_status pie_batch_work(const pie_batch* batch, int64_t* out);
+
+/* Shape of the launch plan of a batch: out[0] = waves of the decode-attention kernel, out[1] = segments (runs of
+ * one (column group, kv head) inside a wave's share; one partial row set each), out[2] = page pairs a wave's share
+ * holds at most, out[3] = workgroup rows of the prefill kernel ((request, 32-token query block) items), out[4] =
+ * requests on the decode path, out[5] = query columns per segment the partial buffers are sized for (at most 16;
+ * more than one request's rows when requests that share pages are walked together).
+ * Host int64[6]. */
+pie_status pie_batch_plan_info(const pie_batch* batch, int64_t* out);
 
 #ifdef __cplusplus
 }

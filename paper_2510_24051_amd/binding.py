@@ -90,6 +90,8 @@ def load_library():
         "pie_set_stage_timing": [vp, i32],
         "pie_stage_times": [vp, vp],
         "pie_batch_work": [vp, vp],
+        "pie_batch_plan_info": [vp, vp],
+        "pie_create_planner": [C.POINTER(ModelDescC), C.POINTER(PoolDescC), i32, C.POINTER(vp)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -118,6 +120,12 @@ class PieBatch:
         self.owner._check(self.owner.lib.pie_batch_work(self.handle, _ptr(out)))
         return {"kv_bytes": int(out[0]), "kv_bytes_decode": int(out[1]), "attn_flops": int(out[2]),
                 "visited_pages": int(out[3]), "kv_bytes_unique": int(out[4]), "kv_bytes_requested": int(out[5])}
+
+    def plan_info(self) -> dict:
+        out = np.zeros(6, dtype=np.int64)
+        self.owner._check(self.owner.lib.pie_batch_plan_info(self.handle, _ptr(out)))
+        return {"decode_waves": int(out[0]), "segments": int(out[1]), "max_pairs_per_wave": int(out[2]),
+                "prefill_items": int(out[3]), "decode_requests": int(out[4]), "rows_cap": int(out[5])}
 
     def destroy(self):
         if self.handle is not None:
@@ -154,6 +162,24 @@ class Pie:
         if st != 0:
             raise PieError(st, self.lib.pie_last_error(None).decode())
         self.ctx = h
+
+    @classmethod
+    def planner(cls, model, n_kv_pages: int, n_embeds: int, max_batch_tokens: int, max_batch_requests: int,
+                n_layers: int = 1, max_adapters: int = 0, max_lora_rank: int = 0, wave_slots: int = 2048) -> "Pie":
+        """A context that only deserialises and plans batches (pie_create_planner): needs no GPU.  batch_create,
+        PieBatch.work / plan_info and mask_kvpage work on it; everything else raises PieError."""
+        self = cls.__new__(cls)
+        self.lib = load_library()
+        self.device, self.stream, self.model = None, None, model
+        md = ModelDescC(model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim, model.mlp_dim, model.vocab,
+                        model.page_size, model.rms_eps, model.rope_theta, n_layers)
+        pd = PoolDescC(n_kv_pages, n_embeds, max_batch_tokens, max_batch_requests, 0, 0, max_adapters, max_lora_rank)
+        h = C.c_void_p()
+        st = self.lib.pie_create_planner(C.byref(md), C.byref(pd), int(wave_slots), C.byref(h))
+        if st != 0:
+            raise PieError(st, self.lib.pie_last_error(None).decode())
+        self.ctx = h
+        return self
 
     # ---- helpers ----
     def _check(self, st: int):

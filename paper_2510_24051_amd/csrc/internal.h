@@ -113,6 +113,7 @@ struct pie_ctx {
   hipStream_t stream = nullptr;
   int device = 0;
   int wave_slots = 2048;  // waves the chip keeps resident for the decode-attention kernel
+  bool host_only = false; // pie_create_planner: deserialises and plans batches, owns nothing on a device
   bf16_t* embeds = nullptr;
   bf16_t* kv = nullptr;
   size_t kv_layer_elems = 0;

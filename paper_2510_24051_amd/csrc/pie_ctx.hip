@@ -56,7 +56,8 @@ static hipError_t dev_alloc(T** p, size_t elems, bool zero, hipStream_t s) {
 
 static int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
-static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* p, void* hip_stream, pie_ctx** out) {
+static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* p, void* hip_stream, pie_ctx** out,
+                                  int planner_wave_slots = 0) {
   if (!m || !p || !out) return fail(nullptr, PIE_EINVAL, "pie_create: null argument");
   *out = nullptr;
   if (m->page_size != PAGE) return fail(nullptr, PIE_EUNSUPPORTED, "page_size %d: kernels are built for %d", m->page_size, PAGE);
@@ -86,6 +87,16 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
   c->err[0] = 0;
   for (int i = 0; i < PIE_N_STAGES; ++i) c->ev_used[i] = false;
   for (int i = 0; i < 2 * PIE_N_STAGES; ++i) c->ev[i] = nullptr;
+  if (planner_wave_slots > 0) {  // host-only context: deserialisation and planning, nothing on a device
+    c->host_only = true;
+    c->wave_slots = planner_wave_slots;
+    c->layers.resize(m->n_layers);
+    c->embed_pos.assign((size_t)p->n_embeds, -1);
+    c->page_mask.assign((size_t)p->n_kv_pages, 0xFFFFu);
+    if (p->max_adapters > 0) c->lora.assign((size_t)p->max_adapters * m->n_layers * PIE_N_PROJ, LoraPair());
+    *out = c;
+    return PIE_OK;
+  }
   hipError_t e = hipGetDevice(&c->device);
   {
     int cus = 0;
@@ -151,6 +162,13 @@ extern "C" pie_status pie_create(const pie_model_desc* m, const pie_pool_desc* p
   return guarded(nullptr, "pie_create", [&]() { return pie_create_impl(m, p, hip_stream, out); });
 }
 
+extern "C" pie_status pie_create_planner(const pie_model_desc* m, const pie_pool_desc* p, int32_t wave_slots,
+                                         pie_ctx** out) {
+  if (wave_slots <= 0 || wave_slots % 8 != 0)
+    return fail(nullptr, PIE_EINVAL, "pie_create_planner: wave_slots must be a positive multiple of 8");
+  return guarded(nullptr, "pie_create_planner", [&]() { return pie_create_impl(m, p, nullptr, out, wave_slots); });
+}
+
 static void free_packed(PackedWeight& w) {
   if (w.data) (void)hipFree(w.data);
   w = PackedWeight();
@@ -158,6 +176,10 @@ static void free_packed(PackedWeight& w) {
 
 extern "C" pie_status pie_destroy(pie_ctx* c) {
   if (!c) return PIE_OK;
+  if (c->host_only) {  // nothing lives on a device
+    delete c;
+    return PIE_OK;
+  }
   (void)hipStreamSynchronize(c->stream);
   for (auto& L : c->layers) {
     if (L.g1) (void)hipFree(L.g1);
@@ -203,6 +225,7 @@ extern "C" pie_status pie_load_layer(pie_ctx* c, int32_t layer, const void* g1, 
                                      const void* wv, const void* wo, const void* g2, const void* wgate,
                                      const void* wup, const void* wdown) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_load_layer: the context only plans batches (pie_create_planner)");
   if (!g1 || !wq || !wk || !wv || !wo || !g2 || !wgate || !wup || !wdown) return fail(c, PIE_EINVAL, "pie_load_layer: null weight");
   if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "pie_load_layer: layer %d of %d", layer, c->m.n_layers);
   const int H = c->m.hidden, QD = c->m.n_q_heads * c->m.head_dim, KD = c->m.n_kv_heads * c->m.head_dim, I = c->m.mlp_dim;
@@ -222,6 +245,7 @@ extern "C" pie_status pie_load_layer(pie_ctx* c, int32_t layer, const void* g1, 
 
 extern "C" pie_status pie_load_head(pie_ctx* c, const void* g_final, const void* w_lm) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_load_head: the context only plans batches (pie_create_planner)");
   if (!w_lm) return fail(c, PIE_EINVAL, "pie_load_head: null weight");
   if (c->m.vocab <= 0 || !c->logits) return fail(c, PIE_EINVAL, "pie_load_head: context created without vocab / dist rows");
   c->head_loaded = false;
@@ -240,6 +264,7 @@ extern "C" pie_status pie_load_head(pie_ctx* c, const void* g_final, const void*
 
 extern "C" pie_status pie_load_embedding(pie_ctx* c, const void* table) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_load_embedding: the context only plans batches (pie_create_planner)");
   if (!table) return fail(c, PIE_EINVAL, "pie_load_embedding: null table");
   if (c->m.vocab <= 0) return fail(c, PIE_EINVAL, "pie_load_embedding: context created without vocab");
   const size_t bytes = (size_t)c->m.vocab * c->m.hidden * sizeof(bf16_t);
@@ -255,6 +280,7 @@ extern "C" pie_status pie_load_embedding(pie_ctx* c, const void* table) {
 extern "C" pie_status pie_load_adapter(pie_ctx* c, int32_t adapter, int32_t layer, int32_t proj, int32_t rank,
                                        float scale, const void* A, const void* B) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_load_adapter: the context only plans batches (pie_create_planner)");
   if (c->p.max_adapters <= 0) return fail(c, PIE_EINVAL, "pie_load_adapter: context created without adapters");
   if (adapter < 0 || adapter >= c->p.max_adapters) return fail(c, PIE_ERANGE, "adapter %d outside [0, %d)", adapter, c->p.max_adapters);
   if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "layer %d of %d", layer, c->m.n_layers);
@@ -323,6 +349,7 @@ static pie_status stage_ids(pie_ctx* c, const int32_t* a, const int32_t* b, int 
 
 static pie_status embed_copy(pie_ctx* c, const int32_t* ids, int32_t n, void* buf, int to_pool) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_embed_write / pie_embed_read: the context only plans batches (pie_create_planner)");
   if (n < 0 || (n > 0 && (!ids || !buf))) return fail(c, PIE_EINVAL, "embed copy: null argument");
   if (n == 0) return PIE_OK;
   for (int i = 0; i < n; ++i)
@@ -343,6 +370,7 @@ extern "C" pie_status pie_embed_write(pie_ctx* c, const int32_t* ids, int32_t n,
 static pie_status pie_embed_txt_impl(pie_ctx* c, const int32_t* token_ids, const int32_t* positions, int32_t n,
                                     const int32_t* embed_ids) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_embed_txt: the context only plans batches (pie_create_planner)");
   if (n < 0 || (n > 0 && (!token_ids || !positions || !embed_ids))) return fail(c, PIE_EINVAL, "pie_embed_txt: null argument");
   if (!c->table) return fail(c, PIE_EINVAL, "pie_embed_txt: no embedding table loaded");
   if (n == 0) return PIE_OK;
@@ -376,6 +404,7 @@ extern "C" pie_status pie_embed_read(pie_ctx* c, const int32_t* ids, int32_t n, 
 static pie_status kv_copy(pie_ctx* c, int32_t layer, const int32_t* pages, const int32_t* slots, int32_t n, void* k,
                           void* v, int to_pool) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_kv_write / pie_kv_read: the context only plans batches (pie_create_planner)");
   if (n < 0 || (n > 0 && (!pages || !slots || !k || !v))) return fail(c, PIE_EINVAL, "kv copy: null argument");
   if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "kv copy: layer %d of %d", layer, c->m.n_layers);
   if (n == 0) return PIE_OK;
@@ -412,6 +441,7 @@ extern "C" pie_status pie_mask_kvpage(pie_ctx* c, const int32_t* page_ids, const
 static pie_status pie_copy_kvpage_impl(pie_ctx* c, const int32_t* src_pages, const int32_t* src_slots,
                                       const int32_t* dst_pages, const int32_t* dst_slots, int32_t n) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_copy_kvpage: the context only plans batches (pie_create_planner)");
   if (n < 0 || (n > 0 && (!src_pages || !src_slots || !dst_pages || !dst_slots)))
     return fail(c, PIE_EINVAL, "pie_copy_kvpage: null argument");
   if (n == 0) return PIE_OK;
@@ -847,6 +877,12 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t o_pm = (o_po + part_rows * D * 4 + 255) / 256 * 256;
   const size_t o_an = (o_pm + part_rows * 2 * 4 + 255) / 256 * 256;  // rotary angle table [T, D] floats
   const size_t total_bytes = o_an + (size_t)T * D * 4 + 256;
+  if (c->host_only) {  // plan only: the work lists stay on the host and are dropped, the statistics remain
+    pb->n_lora_tiles = (int)lora_tile_ad.size();
+    pb->used_adapters = used_adapters;
+    *out = pb;
+    return PIE_OK;
+  }
   hipError_t e = hipSuccess;
   {  // the smallest kept block that is large enough, else a new one (sizes in 1 MiB steps so that blocks get reused)
     int best = -1;
@@ -901,13 +937,24 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
 
 extern "C" pie_status pie_batch_destroy(pie_ctx* c, pie_batch* b) {
   if (!b) return PIE_OK;
-  if (c) (void)hipStreamSynchronize(c->stream);  // no kernel may still read the batch
+  if (c && !c->host_only) (void)hipStreamSynchronize(c->stream);  // no kernel may still read the batch
   if (b->dev_blob) {
     constexpr size_t POOL_BLOCKS = 8;
     if (c && c->blob_pool.size() < POOL_BLOCKS) c->blob_pool.emplace_back(b->dev_blob, b->dev_blob_bytes);
     else (void)hipFree(b->dev_blob);
   }
   delete b;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_batch_plan_info(const pie_batch* b, int64_t* out) {
+  if (!b || !out) return PIE_EINVAL;
+  out[0] = b->n_dwaves;
+  out[1] = b->n_dsegs;
+  out[2] = b->dslots / 2;
+  out[3] = b->n_pitems;
+  out[4] = b->n_dec_reqs;
+  out[5] = b->rows_cap;
   return PIE_OK;
 }
 
@@ -1064,6 +1111,7 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
 
 extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_forward: the context only plans batches (pie_create_planner)");
   if (!b) return fail(c, PIE_EINVAL, "pie_forward: null batch");
   if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "pie_forward: layer %d of %d", layer, c->m.n_layers);
   if (!c->layers[layer].loaded) return fail(c, PIE_EINVAL, "pie_forward: layer %d has no weights", layer);
@@ -1073,6 +1121,7 @@ extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b)
 
 extern "C" pie_status pie_forward_all(pie_ctx* c, const pie_batch* b) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_forward_all: the context only plans batches (pie_create_planner)");
   if (!b) return fail(c, PIE_EINVAL, "pie_forward_all: null batch");
   const int NL = c->m.n_layers;
   for (int l = 0; l < NL; ++l)
@@ -1116,6 +1165,7 @@ static pie_status check_dist_args(pie_ctx* c, const void* ids, int32_t n, int32_
 extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, int32_t n, int32_t top_k,
                                         float temperature, int32_t* out_ids, float* out_probs) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_get_next_dist: the context only plans batches (pie_create_planner)");
   pie_status chk = check_dist_args(c, embed_ids, n, top_k, temperature, out_ids, out_probs);
   if (chk != PIE_OK) return chk;
   for (int i = 0; i < n; ++i)
@@ -1146,6 +1196,7 @@ extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, in
 static pie_status pie_forward_dist_impl(pie_ctx* c, const pie_batch* b, const int32_t* rows, int32_t n, int32_t top_k,
                                        float temperature, int32_t* out_ids, float* out_probs) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_forward_dist: the context only plans batches (pie_create_planner)");
   if (!b) return fail(c, PIE_EINVAL, "pie_forward_dist: null batch");
   // every argument is checked before anything is enqueued
   pie_status st = check_dist_args(c, rows, n, top_k, temperature, out_ids, out_probs);
@@ -1168,6 +1219,7 @@ extern "C" pie_status pie_forward_dist(pie_ctx* c, const pie_batch* b, const int
 
 extern "C" pie_status pie_synchronize(pie_ctx* c) {
   if (!c) return PIE_EINVAL;
+  if (c->host_only) return PIE_OK;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   return PIE_OK;
 }
@@ -1177,6 +1229,7 @@ extern "C" pie_status pie_synchronize(pie_ctx* c) {
 // ---------------------------------------------------------------------------------------------
 extern "C" pie_status pie_read_tap(pie_ctx* c, int32_t which, void* dst, int64_t n_elements) {
   if (!c || !dst) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_read_tap: the context only plans batches (pie_create_planner)");
   const pie_model_desc& m = c->m;
   const int T = c->last_T, QD = m.n_q_heads * m.head_dim, QKV = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
   switch (which) {
@@ -1216,6 +1269,7 @@ extern "C" pie_status pie_set_stage_timing(pie_ctx* c, int32_t enabled) {
 
 extern "C" pie_status pie_stage_times(pie_ctx* c, float* ms_out) {
   if (!c || !ms_out) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_stage_times: the context only plans batches (pie_create_planner)");
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   for (int i = 0; i < PIE_N_STAGES; ++i) {
     ms_out[i] = 0.f;

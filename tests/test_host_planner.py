@@ -1,0 +1,220 @@
+"""Host logic of the library without a GPU: batch deserialisation, its error codes and the attention launch plan,
+through a planner context (pie_create_planner makes no HIP call)."""
+import numpy as np
+import pytest
+
+import workloads as W
+from helpers import clone_batch
+from paper_2510_24051_amd import Pie, PieError
+
+
+def small_model(head_dim=64, n_q=4, n_kv=2, hidden=128, mlp=256):
+    return W.ModelDesc(hidden=hidden, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=head_dim, mlp_dim=mlp, vocab=512,
+                       page_size=16, rms_eps=1e-5, rope_theta=1e4, n_layers=1)
+
+
+def random_mask(p):
+    def f(n_new, L, rng):
+        m = rng.random((n_new, L)) < p
+        m &= W.causal_bitmap(n_new, L)
+        return m
+    return f
+
+
+def planner_for(w, wave_slots=2048, **kw):
+    b = w.batch
+    return Pie.planner(w.model, w.n_kv_pages, w.n_embeds, max_batch_tokens=int(b.n_tokens),
+                       max_batch_requests=int(b.n_requests), wave_slots=wave_slots, **kw)
+
+
+def expected_work(w, page_mask=None):
+    """The statistics of pie_batch_work recomputed from the batch description alone."""
+    m, b = w.model, w.batch
+    P, G = m.page_size, m.n_q_heads // m.n_kv_heads
+    page_bytes = m.n_kv_heads * 2 * P * m.head_dim * 2
+    visited = visited_dec = 0
+    flops = 0
+    distinct = set()
+    n_items = n_dec = rows_cap = 0
+    for r in range(b.n_requests):
+        t0, t1 = int(b.tok_indptr[r]), int(b.tok_indptr[r + 1])
+        n_new, L = t1 - t0, int(b.kv_len[r])
+        n_pages = (L + P - 1) // P
+        pages = b.page_ids[b.page_indptr[r]:b.page_indptr[r] + n_pages]
+        has_mask = b.mask_indptr is not None and b.mask_indptr[r + 1] > b.mask_indptr[r]
+        masked_pages = page_mask is not None and any(page_mask.get(int(p), 0xFFFF) != 0xFFFF for p in pages)
+        if has_mask or masked_pages:
+            if has_mask:
+                wpr = (L + 31) // 32
+                words = b.mask_words[b.mask_indptr[r]:b.mask_indptr[r + 1]].reshape(n_new, wpr)
+                allowed = ((words[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(n_new, wpr * 32)[:, :L].astype(bool)
+            else:
+                allowed = W.causal_bitmap(n_new, L)
+            if masked_pages:
+                vis = np.concatenate([[(page_mask.get(int(p), 0xFFFF) >> s) & 1 for s in range(P)] for p in pages])[:L].astype(bool)
+                allowed = allowed & vis[None, :]
+            any_key = allowed.any(axis=0)
+            vis_pages = [pg for pg in range(n_pages) if any_key[pg * P:(pg + 1) * P].any()]
+            explicit = True
+        else:
+            vis_pages, explicit = list(range(n_pages)), False
+        nv = len(vis_pages)
+        visited += nv
+        if n_new * G <= 16:
+            n_dec += 1
+            rows_cap = max(rows_cap, n_new * G)
+            visited_dec += nv
+            distinct.update(int(pages[pg]) for pg in vis_pages)
+            flops += nv * P * n_new * m.n_q_heads * m.head_dim * 4
+        else:
+            n_items += (n_new + 31) // 32
+            if explicit:
+                flops += nv * P * n_new * m.n_q_heads * m.head_dim * 4
+            else:
+                flops += m.n_q_heads * m.head_dim * 4 * (n_new * (L - n_new) + n_new * (n_new + 1) // 2)
+    return dict(kv_bytes=visited * page_bytes, kv_bytes_decode=visited_dec * page_bytes, attn_flops=flops,
+                visited_pages=visited, kv_bytes_unique=len(distinct) * page_bytes), \
+        dict(prefill_items=n_items, decode_requests=n_dec, rows_cap=rows_cap)
+
+
+def workloads():
+    sparse = random_mask(0.3)
+    yield "c1", W.c1_tiny()
+    m = small_model(64, 4, 2)
+    reqs = [W.RequestSpec(1, 0), W.RequestSpec(1, 15), W.RequestSpec(2, 100), W.RequestSpec(3, 33, mask=sparse),
+            W.RequestSpec(9, 0), W.RequestSpec(31, 5, mask=W.causal_bitmap), W.RequestSpec(33, 47),
+            W.RequestSpec(70, 130, mask=sparse), W.RequestSpec(1, 700, mask=random_mask(0.02)),
+            W.RequestSpec(1, 257, in_place=True), W.RequestSpec(40, 0, mask=random_mask(0.9))]
+    yield "ragged", W.build_workload("ragged", m, reqs, n_kv_pages=160, seed=100, std=0.05, with_head=False)
+    P = 16
+    reqs = [W.RequestSpec(1, 5 * P + 3, prefix_group=0, prefix_len=5 * P),
+            W.RequestSpec(1, 5 * P + 40, prefix_group=0, prefix_len=5 * P),
+            W.RequestSpec(1, 5 * P, prefix_group=0, prefix_len=5 * P, in_place=True),
+            W.RequestSpec(1, 9 * P + 1, prefix_group=0, prefix_len=5 * P, mask=W.causal_bitmap),
+            W.RequestSpec(1, 33), W.RequestSpec(2, 3 * P + 5, prefix_group=1, prefix_len=3 * P),
+            W.RequestSpec(2, 3 * P + 20, prefix_group=1, prefix_len=3 * P),
+            W.RequestSpec(40, 3 * P, prefix_group=1, prefix_len=3 * P)]
+    yield "shared", W.build_workload("shared", small_model(128, 8, 2), reqs, n_kv_pages=96, seed=700, std=0.05,
+                                     with_head=False)
+    rng = np.random.default_rng(5)
+    reqs = [W.RequestSpec(1, int(c)) for c in rng.integers(512, 4097, size=64)]
+    yield "decode64", W.build_workload("decode64", small_model(64, 8, 2), reqs, n_kv_pages=12000, seed=2000, std=0.02,
+                                       with_head=False)
+
+
+@pytest.mark.parametrize("name,w", list(workloads()), ids=lambda x: x if isinstance(x, str) else "")
+def test_plan_statistics_match_the_batch(name, w):
+    ctx = planner_for(w)
+    pb = ctx.batch_create(w.batch, validate=True)
+    work, info = pb.work(), pb.plan_info()
+    exp_work, exp_info = expected_work(w)
+    for k, v in exp_work.items():
+        assert work[k] == v, (name, k, work[k], v)
+    for k in ("prefill_items", "decode_requests"):
+        assert info[k] == exp_info[k], (name, k, info[k], exp_info[k])
+    assert exp_info["rows_cap"] <= info["rows_cap"] <= 16  # wider when requests that share pages form one column group
+    # requests that share pages are walked together: never more bytes than the per-request count, never fewer
+    # than the distinct pages; without sharing all three agree
+    assert work["kv_bytes_unique"] <= work["kv_bytes_requested"] <= work["kv_bytes_decode"]
+    if name != "shared":
+        assert work["kv_bytes_requested"] == work["kv_bytes_decode"] == work["kv_bytes_unique"]
+    else:
+        assert work["kv_bytes_requested"] < work["kv_bytes_decode"]
+    assert 1 <= info["max_pairs_per_wave"] <= 64
+    # every share is sized for the resident waves: the wave count is a whole number of rounds or less than one
+    assert info["decode_waves"] <= 2048 or info["decode_waves"] % 2048 == 0 or info["max_pairs_per_wave"] == 64
+    assert info["segments"] >= info["decode_waves"] or info["decode_waves"] == 0
+    pb.destroy()
+    ctx.close()
+
+
+def test_plan_depends_on_the_resident_waves_but_the_work_does_not():
+    w = dict(workloads())["decode64"]
+    small, big = planner_for(w, wave_slots=64), planner_for(w, wave_slots=2048)
+    a, b = small.batch_create(w.batch), big.batch_create(w.batch)
+    assert a.work() == b.work()
+    ia, ib = a.plan_info(), b.plan_info()
+    assert ia["decode_waves"] < ib["decode_waves"] and ia["max_pairs_per_wave"] > ib["max_pairs_per_wave"]
+    pairs = sum((int(L) + 31) // 32 for L in w.batch.kv_len) * w.model.n_kv_heads
+    for info in (ia, ib):  # the shares cover every (request, kv head, page pair)
+        assert info["decode_waves"] * info["max_pairs_per_wave"] >= pairs
+
+
+def test_page_masks_are_read_when_the_batch_is_created():
+    w = dict(workloads())["ragged"]
+    b = w.batch
+    ctx = planner_for(w)
+    before = ctx.batch_create(b)
+    r = 8  # the single-token request over 700 prior tokens with a sparse mask of its own
+    pages = b.page_ids[b.page_indptr[r]:b.page_indptr[r + 1]]
+    hidden = {int(p): 0 for p in pages[:20]}          # no token of these pages stays visible
+    hidden[int(pages[20])] = 0x00F0                    # four tokens of this one do
+    ctx.mask_kvpage(np.fromiter(hidden.keys(), np.int32), np.fromiter(hidden.values(), np.uint32))
+    after = ctx.batch_create(b)
+    exp_work, _ = expected_work(w, page_mask=hidden)
+    assert after.work()["visited_pages"] == exp_work["visited_pages"] < before.work()["visited_pages"]
+    assert before.work()["visited_pages"] == expected_work(w)[0]["visited_pages"]  # the earlier batch keeps what it saw
+
+
+def status_of(fn):
+    with pytest.raises(PieError) as e:
+        fn()
+    return e.value.status
+
+
+def test_deserialisation_error_codes():
+    w = W.c1_tiny()
+    b = w.batch
+    ctx = planner_for(w, max_adapters=2, max_lora_rank=8)
+    ctx.batch_create(b).destroy()
+
+    def edited(field, index, value, **kw):
+        a = np.array(getattr(b, field)).copy()
+        a[index] = value
+        return clone_batch(b, **{field: a}, **kw)
+    assert status_of(lambda: ctx.batch_create(edited("page_ids", 3, w.n_kv_pages))) == -2      # page id out of range
+    assert status_of(lambda: ctx.batch_create(edited("page_ids", 0, -1))) == -2
+    assert status_of(lambda: ctx.batch_create(edited("in_embed_ids", 1, w.n_embeds))) == -2    # embed id out of range
+    assert status_of(lambda: ctx.batch_create(edited("out_embed_ids", 1, -2))) == -2
+    assert status_of(lambda: ctx.batch_create(edited("positions", 0, -5))) == -2               # negative position
+    assert status_of(lambda: ctx.batch_create(edited("kv_len", 0, 0))) == -1                   # shorter than its new tokens
+    assert status_of(lambda: ctx.batch_create(edited("kv_len", 0, 10_000))) == -1              # more KV than pages listed
+    assert status_of(lambda: ctx.batch_create(edited("tok_indptr", 0, 1))) == -1               # must start at 0
+    assert status_of(lambda: ctx.batch_create(clone_batch(b, positions=None))) == -1           # no positions recorded
+    assert status_of(lambda: ctx.batch_create(clone_batch(b, adapter_ids=np.full(b.n_requests, 2, np.int32)))) == -2
+    # two tokens writing one (page, slot): request 1 gets request 0's pages and length
+    pi = np.array(b.page_indptr)
+    pages = np.array(b.page_ids).copy()
+    n0 = pi[1] - pi[0]
+    assert pi[2] - pi[1] >= n0
+    pages[pi[1]:pi[1] + n0] = pages[pi[0]:pi[1]]
+    kv = np.array(b.kv_len).copy()
+    kv[1] = kv[0]
+    clash = clone_batch(b, page_ids=pages, kv_len=kv)
+    assert status_of(lambda: ctx.batch_create(clash, validate=True)) == -4
+    ctx.batch_create(clash, validate=False).destroy()                                          # only checked on request
+    # a batch larger than the context was sized for
+    tiny = Pie.planner(w.model, w.n_kv_pages, w.n_embeds, max_batch_tokens=int(b.n_tokens) - 1,
+                       max_batch_requests=int(b.n_requests))
+    assert status_of(lambda: tiny.batch_create(b)) == -3
+    few = Pie.planner(w.model, w.n_kv_pages, w.n_embeds, max_batch_tokens=int(b.n_tokens),
+                      max_batch_requests=int(b.n_requests) - 1)
+    assert status_of(lambda: few.batch_create(b)) == -3
+    # a mask with the wrong number of words
+    bm = W.c1_tiny(bitmap=True).batch if "bitmap" in W.c1_tiny.__code__.co_varnames else None
+    if bm is not None:
+        mi = np.array(bm.mask_indptr).copy()
+        mi[-1] -= 1
+        assert status_of(lambda: ctx.batch_create(clone_batch(bm, mask_indptr=mi))) == -1
+
+
+def test_planner_context_refuses_device_work():
+    w = W.c1_tiny()
+    ctx = planner_for(w)
+    pb = ctx.batch_create(w.batch)
+    assert status_of(lambda: ctx.forward(0, pb)) == -1
+    assert status_of(lambda: ctx.forward_all(pb)) == -1
+    assert "plans batches" in str(pytest.raises(PieError, lambda: ctx.forward(0, pb)).value)
+    ctx._check(ctx.lib.pie_synchronize(ctx.ctx))  # nothing to wait for
+    with pytest.raises(PieError):
+        Pie.planner(w.model, w.n_kv_pages, w.n_embeds, 8, 8, wave_slots=3)
