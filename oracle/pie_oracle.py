@@ -208,6 +208,7 @@ class ForwardResult:
     h: np.ndarray         # [len(rows), H] residual stream after the attention block
     k_new: np.ndarray     # [T, Hkv, D] uint16: appended K (after the rotary step), bf16 bits
     v_new: np.ndarray     # [T, Hkv, D] uint16: appended V, bf16 bits
+    act: Optional[np.ndarray] = None  # [len(rows), I] SwiGLU product silu(gate) * up, the down projection's input
 
 
 def _maybe_round(x: np.ndarray, on: bool) -> np.ndarray:
@@ -371,7 +372,7 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
         out_ids = np.asarray(batch.out_embed_ids, dtype=np.int64)[rows]
         keep = out_ids >= 0
         emb.bits[out_ids[keep]] = bf16_encode(y[keep])
-    return ForwardResult(rows=rows, y=y, q=q_out, o=o_out, h=h, k_new=k_new, v_new=v_new)
+    return ForwardResult(rows=rows, y=y, q=q_out, o=o_out, h=h, k_new=k_new, v_new=v_new, act=act)
 
 
 # --------------------------------------------------------------------------------------------

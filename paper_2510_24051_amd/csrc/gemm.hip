@@ -192,6 +192,29 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
     if (it + 1 < it1) step(std::integral_constant<int, 1>{}, it + 1);
     if (it + 2 < it1) step(std::integral_constant<int, 2>{}, it + 2);
   }
+  if constexpr (!PARTIAL && MODE == EPI_SWIGLU && NBW == 1) {
+    // One block per wave: the gate block sits in the even waves, its up block in the wave after it, which hands
+    // its sums over through LDS (the activation stages are free once the main loop has passed its last barrier).
+    float* xch = reinterpret_cast<float*>(smem_raw);  // [2 pairs][MB][16][64]
+    const int pair = wave >> 1;
+    if (wave & 1) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xch[((pair * MB + i) * 16 + v) * 64 + lane] = acc[0][i][v];
+    }
+    __syncthreads();
+    if (!(wave & 1) && wave_active) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        f32x16 up;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) up[v] = xch[((pair * MB + i) * 16 + v) * 64 + lane];
+        epi_tile<MODE>(epi, acc[0][i], up, i * 32, nb0 * 32, M, NB * 32, lane);
+      }
+    }
+    return;
+  }
   if (!wave_active) return;
   if (PARTIAL) {
     // raw partial sums: part[split][m][n_packed]
@@ -549,7 +572,7 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
 // ------------------------------------------------------------------------------------------------
 template <int MB, int MODE, int NBW>
 static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
-                               size_t ws_elems, int n_cus, hipStream_t s, int* defer) {
+                               size_t ws_elems, int n_cus, hipStream_t s, int* defer, int max_splits = SK_MAX_SPLITS) {
   const int wg_n = (W.NB + 4 * NBW - 1) / (4 * NBW);
   const int total_iters = (W.K + SK_BK - 1) / SK_BK;
   // Split K so that one round of workgroups fills the chip without spilling into a second, mostly empty round:
@@ -561,7 +584,7 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
   // Every split writes an M x N fp32 partial that is read back once and then sits dirty in the caches until the
   // next weight stream pushes it out to HBM; beyond 8 splits that costs more than the extra workgroups gain
   // (c2 forward -2.5 us, c5 -8 us against 16 and 12 splits).
-  if (splits > SK_MAX_SPLITS) splits = SK_MAX_SPLITS;
+  if (splits > max_splits) splits = max_splits;
   if (splits < 1) splits = 1;
   const int NP = W.NB * 32;
   while (splits > 1 && (size_t)splits * M * NP > ws_elems) --splits;
@@ -593,6 +616,13 @@ template <int MB, int MODE>
 static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
                              size_t ws_elems, int n_cus, hipStream_t s, int* defer) {
   if constexpr (MODE == EPI_SWIGLU) {
+    // Wide enough MLPs fill the chip with one block per wave and no split at all (gate and up meet through LDS):
+    // no partial sums to write, read back and write out of the caches (70B shape, 16 rows: 179 -> 163 us, the
+    // forward call 0.410 -> 0.389 ms).  With fewer workgroups than that (8B shape: 224 on 256 CUs) the split
+    // version with a gate/up pair per wave is faster.
+    if constexpr (MB <= 2)
+      if ((W.NB + 3) / 4 >= n_cus + n_cus / 2)
+        return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer, 1);
     return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   } else {
     // wide outputs (LM head): two blocks per wave halve the workgroup count and the activation reads from LDS

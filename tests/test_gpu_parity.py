@@ -47,6 +47,9 @@ def compare_layer(w, ctx=None, mode_b_only=False, check_taps=True, what=""):
         assert_close(o, res_b.o, f"{what} attention output", 2e-2 * max(1.0, np.abs(res_b.o).max()), 2e-3 * max(1.0, np.abs(res_b.o).mean() * 4))
         h = ctx.read_tap(TAP_RESID, T)
         assert_close(h, res_b.h, f"{what} residual after attention")
+        act = dec(ctx.read_tap(TAP_ACT, T))
+        assert_close(act, res_b.act, f"{what} SwiGLU activation", 2e-2 * max(1.0, np.abs(res_b.act).max()),
+                     2e-3 * max(1.0, np.abs(res_b.act).mean() * 4))
     # appended K/V land in the right (page, slot), values equal up to bf16 rounding of an fp32 vs fp64 product
     pages, slots = appended_positions(w)
     k_gpu, v_gpu = ctx.kv_read(0, pages, slots)
@@ -150,6 +153,19 @@ def test_mid_size_batches_split_k_tiles(n_decode, n_prefill):
         reqs.append(W.RequestSpec(n_prefill, 7))
     w = W.build_workload("mid", m, reqs, n_kv_pages=n_decode * 4 + 32, seed=900 + n_decode + n_prefill, std=0.012)
     compare_layer(w, what=f"T={w.batch.n_tokens} H1024 I2048")
+
+
+@pytest.mark.parametrize("mlp,n_decode", [(24576, 12), (24608, 40), (24576, 64)])
+def test_wide_mlp_gate_up_without_split(mlp, n_decode):
+    """An MLP wide enough that the gate/up product fills the chip with one 32-column block per wave and no split
+    along K: the gate block of a pair and its up block sit in neighbouring waves and meet through LDS.  24608 is
+    32 x 769: the last workgroup has two idle waves that still have to take part in the exchange's barrier."""
+    m = small_model(64, 4, 2, hidden=128, mlp=mlp, vocab=512)
+    rng = np.random.default_rng(mlp + n_decode)
+    reqs = [W.RequestSpec(1, int(c)) for c in rng.integers(0, 40, size=n_decode)]
+    w = W.build_workload("wide_mlp", m, reqs, n_kv_pages=n_decode * 3 + 8, seed=950 + n_decode, std=0.02,
+                         resid_std=0.02 / np.sqrt(mlp / 128.0))
+    compare_layer(w, what=f"T={w.batch.n_tokens} I{mlp}")
 
 
 # ---------------------------------------------------------------- shared prefixes (requests aliasing pages)
