@@ -88,13 +88,15 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
 #define SK_BK 128  // contraction elements per main-loop iteration (8 MFMA steps)
 #define SK_MAX_SPLITS 8
 
-template <int MB, int MODE, bool PARTIAL, int NBW>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restrict__ A, int lda, int M,
+// WAVES: waves per workgroup, 4 or (unsplit gate/up at widths that give too few workgroups of four) 2.
+template <int MB, int MODE, bool PARTIAL, int NBW, int WAVES = 4>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                           const bf16_t* __restrict__ Wp, int N, int NB, int K,
                                                           int iters_per_split, EpiArgs epi, float* __restrict__ part) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);  // [2][MB*32][SK_BK], 16-byte chunks swizzled by row
   constexpr int BM = MB * 32;
+  constexpr int NT = WAVES * 64;
   constexpr int A_ELEMS = BM * SK_BK;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int KB = K / 16;
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
   const int it0 = blockIdx.y * iters_per_split;
   const int it1 = min(total_iters, it0 + iters_per_split);
   // a wave owns NBW adjacent 32-column blocks (SWIGLU: a gate/up pair)
-  int nb0 = (blockIdx.x * 4 + wave) * NBW;
+  int nb0 = (blockIdx.x * WAVES + wave) * NBW;
   const bool wave_active = nb0 < NB;
   if (!wave_active) nb0 = 0;  // keep loads in bounds; results are dropped
 
@@ -116,14 +118,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
 
   // A tile loader: BM rows x 16 chunks (16 B) per iteration; chunk c of row r is stored at chunk (c ^ (r & 15))
   constexpr int A_CHUNKS = BM * 16;
-  constexpr int A_PER_THREAD = (A_CHUNKS + 255) / 256;
+  constexpr int A_PER_THREAD = (A_CHUNKS + NT - 1) / NT;
   u32x4 areg[A_PER_THREAD];
   // Loads always read an in-bounds address (row and k clamped); chunks outside the matrix are zeroed when the
   // registers are stored to LDS, so no register is written while an earlier load into it could be pending.
   auto load_a = [&](int it) {
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
-      const int c = min(tid + j * 256, A_CHUNKS - 1);
+      const int c = min(tid + j * NT, A_CHUNKS - 1);
       const int r = min(c >> 4, M - 1), kc = c & 15;
       const int k = min(it * SK_BK + kc * 8, K - 8);
       areg[j] = *reinterpret_cast<const u32x4*>(A + (int64_t)r * lda + k);
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
   auto store_a = [&](int buf, int it) {
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
-      const int c = tid + j * 256;
+      const int c = tid + j * NT;
       const int r = c >> 4, kc = c & 15;
       const bool inside = r < M && it * SK_BK + kc * 8 < K;
       if (c < A_CHUNKS)
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
   if constexpr (!PARTIAL && MODE == EPI_SWIGLU && NBW == 1) {
     // One block per wave: the gate block sits in the even waves, its up block in the wave after it, which hands
     // its sums over through LDS (the activation stages are free once the main loop has passed its last barrier).
-    float* xch = reinterpret_cast<float*>(smem_raw);  // [2 pairs][MB][16][64]
+    float* xch = reinterpret_cast<float*>(smem_raw);  // [WAVES / 2 pairs][MB][16][64]
     const int pair = wave >> 1;
     if (wave & 1) {
 #pragma unroll
@@ -570,10 +572,10 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
 // ------------------------------------------------------------------------------------------------
 // dispatch
 // ------------------------------------------------------------------------------------------------
-template <int MB, int MODE, int NBW>
+template <int MB, int MODE, int NBW, int WAVES = 4>
 static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
                                size_t ws_elems, int n_cus, hipStream_t s, int* defer, int max_splits = SK_MAX_SPLITS) {
-  const int wg_n = (W.NB + 4 * NBW - 1) / (4 * NBW);
+  const int wg_n = (W.NB + WAVES * NBW - 1) / (WAVES * NBW);
   const int total_iters = (W.K + SK_BK - 1) / SK_BK;
   // Split K so that one round of workgroups fills the chip without spilling into a second, mostly empty round:
   // the kernel keeps `occ` workgroups per CU resident (register-limited).
@@ -591,15 +593,15 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
   int ips = (total_iters + splits - 1) / splits;
   splits = (total_iters + ips - 1) / ips;
   size_t smem = (size_t)2 * MB * 32 * SK_BK * sizeof(bf16_t);
-  dim3 grid(wg_n, splits), block(256);
+  dim3 grid(wg_n, splits), block(WAVES * 64);
   if (splits == 1) {
-    auto kern = gemm_skinny_kernel<MB, MODE, false, NBW>;
+    auto kern = gemm_skinny_kernel<MB, MODE, false, NBW, WAVES>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, nullptr);
     return hipGetLastError();
   }
-  auto kern = gemm_skinny_kernel<MB, MODE, true, NBW>;
+  auto kern = gemm_skinny_kernel<MB, MODE, true, NBW, WAVES>;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, ws);
@@ -620,9 +622,14 @@ static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight
     // no partial sums to write, read back and write out of the caches (70B shape, 16 rows: 179 -> 163 us, the
     // forward call 0.410 -> 0.389 ms).  With fewer workgroups than that (8B shape: 224 on 256 CUs) the split
     // version with a gate/up pair per wave is faster.
-    if constexpr (MB <= 2)
+    if constexpr (MB <= 2) {
       if ((W.NB + 3) / 4 >= n_cus + n_cus / 2)
         return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer, 1);
+      // the 8B width gets there with workgroups of one pair (two waves): 448 of them; as fast as the split
+      // version and without its 29 MB of partial sums (the down projection after it gains 1 us)
+      if ((W.NB + 1) / 2 >= n_cus + n_cus / 2)
+        return run_skinny_n<MB, MODE, 1, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer, 1);
+    }
     return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   } else {
     // wide outputs (LM head): two blocks per wave halve the workgroup count and the activation reads from LDS

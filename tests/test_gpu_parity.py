@@ -155,11 +155,12 @@ def test_mid_size_batches_split_k_tiles(n_decode, n_prefill):
     compare_layer(w, what=f"T={w.batch.n_tokens} H1024 I2048")
 
 
-@pytest.mark.parametrize("mlp,n_decode", [(24576, 12), (24608, 40), (24576, 64)])
+@pytest.mark.parametrize("mlp,n_decode", [(24576, 12), (24608, 40), (24576, 64), (12320, 40), (12288, 12)])
 def test_wide_mlp_gate_up_without_split(mlp, n_decode):
     """An MLP wide enough that the gate/up product fills the chip with one 32-column block per wave and no split
     along K: the gate block of a pair and its up block sit in neighbouring waves and meet through LDS.  24608 is
-    32 x 769: the last workgroup has two idle waves that still have to take part in the exchange's barrier."""
+    32 x 769: the last workgroup has two idle waves that still have to take part in the exchange's barrier.  Half
+    that width runs the same scheme with workgroups of two waves (one pair each)."""
     m = small_model(64, 4, 2, hidden=128, mlp=mlp, vocab=512)
     rng = np.random.default_rng(mlp + n_decode)
     reqs = [W.RequestSpec(1, int(c)) for c in rng.integers(0, 40, size=n_decode)]
