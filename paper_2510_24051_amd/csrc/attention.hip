@@ -516,7 +516,8 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
   __shared__ __align__(16) bf16_t st0[2 * BLK], st1[2 * BLK], st2[2 * BLK], st3[2 * BLK];
   const int lane = threadIdx.x & 63, hg = threadIdx.x >> 6;
   const PrefillItem it = items[blockIdx.x];
-  const int hk = blockIdx.y;
+  if (it.r < 0) return;  // padding of the per-XCD lists (uniform over the workgroup)
+  const int hk = it.hk;
   const ReqInfo rq = a.reqs[it.r];
   const int qcol = lane & 31, g = lane >> 5, m = lane & 31;
   const int i_tok = it.qb * 32 + qcol;
@@ -684,7 +685,8 @@ template <int D>
 __global__ __launch_bounds__(512) void attn_prefill_direct_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
   const int lane = threadIdx.x & 63, hg = threadIdx.x >> 6;  // one wave per query head of the group
   const PrefillItem it = items[blockIdx.x];
-  const int hk = blockIdx.y;
+  if (it.r < 0) return;  // padding of the per-XCD lists (uniform over the workgroup)
+  const int hk = it.hk;
   const ReqInfo rq = a.reqs[it.r];
   const int G = a.Hq / a.Hkv;
   const int qcol = lane & 31, g = lane >> 5;
@@ -760,7 +762,7 @@ hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_d
 template <int D>
 static hipError_t launch_prefill_d(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
-  dim3 grid(n_items, a.Hkv), block(64 * G);
+  dim3 grid(n_items), block(64 * G);
   if (G == 1) attn_prefill_kernel<D, 1><<<grid, block, 0, s>>>(a, items);
   else if (G == 2) attn_prefill_kernel<D, 2><<<grid, block, 0, s>>>(a, items);
   else if (G == 4) attn_prefill_kernel<D, 4><<<grid, block, 0, s>>>(a, items);

@@ -76,7 +76,7 @@ struct DecodeCol {     // one query column of a column group: (request token, he
 // (shared prefixes), so that each K/V block is read once for all of them.
 struct DecodeSeg { int32_t cgroup, hk, n_pairs, pad; };  // a run of page pairs of one (column group, kv head) inside one wave's share
 struct DecodeWave { int32_t seg0, n_seg, n_pairs, pad; };  // a wave's share: segments [seg0, seg0 + n_seg)
-struct PrefillItem { int32_t r, qb; };           // query block qb (32 tokens) of request r
+struct PrefillItem { int32_t r, qb, hk, pad; };  // query block qb (32 tokens) of request r for kv head hk; r < 0: empty slot
 
 struct pie_batch {
   int32_t R = 0, T = 0;
@@ -102,6 +102,7 @@ struct pie_batch {
   PrefillItem* pitems = nullptr;
   int32_t* dec_reqs = nullptr;  // request indices on the decode path
   int32_t n_dsegs = 0, n_dwaves = 0, dslots = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
+  int32_t n_pwork = 0;  // workgroups of the prefill launch: (query block, kv head) items laid out per XCD, padded
   float* part_o = nullptr;   // [n_dsegs * rows_cap, D]
   float* part_ml = nullptr;  // [n_dsegs * rows_cap, 2]
   int64_t work[6] = {0, 0, 0, 0, 0, 0};

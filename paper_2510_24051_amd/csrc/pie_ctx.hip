@@ -625,7 +625,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
       flops += visited_pages * PAGE * (int64_t)n_new * c->m.n_q_heads * D * 4;
     } else {
       const int nqb = (n_new + 31) / 32;
-      for (int qb = 0; qb < nqb; ++qb) pitems.push_back(PrefillItem{r, qb});
+      for (int qb = 0; qb < nqb; ++qb) pitems.push_back(PrefillItem{r, qb, 0, 0});
       visited_pages = q.n_visit;  // each page is needed at least once
       if (q.wpr == 0) flops += (int64_t)c->m.n_q_heads * D * 4 * ((int64_t)n_new * (L - n_new) + (int64_t)n_new * (n_new + 1) / 2);
       else flops += visited_pages * PAGE * (int64_t)n_new * c->m.n_q_heads * D * 4;
@@ -822,14 +822,66 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     for (int32_t v : mref_lists[i]) mrefs.push_back((v / 16) * rows_cap + (v % 16));
     mref_indptr[i + 1] = (int32_t)mrefs.size();
   }
-  // heavy query blocks first
+  // Prefill work list.  The hardware hands workgroup i to XCD i % 8, and every XCD has an L2 of its own: the
+  // query blocks of one (request, kv head) read the same K/V pages, so they go to one XCD, next to each other in
+  // its list (heavy blocks first), and that XCD's L2 serves all but the first read of a page.  The groups are
+  // spread over the XCDs by cost, largest first onto the least loaded; while that leaves the XCDs uneven, groups
+  // are cut into interleaved parts.  Lists are padded with empty slots to one length and interleaved.
+  auto pcost = [&](const PrefillItem& it) {
+    const ReqInfo& q = reqs[it.r];
+    return q.wpr ? (int64_t)q.n_visit * PAGE : (int64_t)(q.kv_len - q.n_new + std::min(q.n_new, it.qb * 32 + 32));
+  };
   std::stable_sort(pitems.begin(), pitems.end(), [&](const PrefillItem& x, const PrefillItem& y) {
-    auto cost = [&](const PrefillItem& it) {
-      const ReqInfo& q = reqs[it.r];
-      return q.wpr ? (int64_t)q.n_visit : (int64_t)(q.kv_len - q.n_new + std::min(q.n_new, it.qb * 32 + 32));
-    };
-    return cost(x) > cost(y);
+    return x.r != y.r ? x.r < y.r : pcost(x) > pcost(y);
   });
+  std::vector<PrefillItem> pwork;
+  if (!pitems.empty()) {
+    constexpr int N_XCD = 8;
+    struct Unit { int32_t first, count, hk, part; int64_t cost; };
+    std::vector<int32_t> lists[N_XCD];
+    for (int parts = 1;; parts *= 2) {
+      std::vector<Unit> units;
+      size_t i0 = 0;
+      int32_t longest = 0;
+      while (i0 < pitems.size()) {
+        size_t i1 = i0;
+        while (i1 < pitems.size() && pitems[i1].r == pitems[i0].r) ++i1;
+        longest = std::max(longest, (int32_t)(i1 - i0));
+        for (int hk = 0; hk < Hkv; ++hk)
+          for (int pt = 0; pt < parts; ++pt) {
+            int64_t cst = 0;
+            for (size_t i = i0 + pt; i < i1; i += parts) cst += pcost(pitems[i]) + 64;
+            if (cst > 0) units.push_back(Unit{(int32_t)i0, (int32_t)(i1 - i0), hk, pt, cst});
+          }
+        i0 = i1;
+      }
+      std::stable_sort(units.begin(), units.end(), [](const Unit& x, const Unit& y) { return x.cost > y.cost; });
+      int64_t load[N_XCD] = {0}, total = 0;
+      for (auto& l : lists) l.clear();
+      std::vector<Unit> per_xcd[N_XCD];
+      for (const Unit& u : units) {
+        int best = 0;
+        for (int x = 1; x < N_XCD; ++x) if (load[x] < load[best]) best = x;
+        load[best] += u.cost; total += u.cost;
+        per_xcd[best].push_back(u);
+      }
+      const int64_t worst = *std::max_element(load, load + N_XCD);
+      if (worst * N_XCD > total + total / 8 && parts < longest) continue;  // more than 1/8 over the mean: cut finer
+      pwork.clear();
+      size_t lmax = 0;
+      std::vector<PrefillItem> flat[N_XCD];
+      for (int x = 0; x < N_XCD; ++x) {
+        for (const Unit& u : per_xcd[x])
+          for (int32_t i = u.first + u.part; i < u.first + u.count; i += parts)
+            flat[x].push_back(PrefillItem{pitems[i].r, pitems[i].qb, u.hk, 0});
+        lmax = std::max(lmax, flat[x].size());
+      }
+      pwork.assign(lmax * N_XCD, PrefillItem{-1, 0, 0, 0});
+      for (int x = 0; x < N_XCD; ++x)
+        for (size_t i = 0; i < flat[x].size(); ++i) pwork[i * N_XCD + x] = flat[x][i];
+      break;
+    }
+  }
 
   pie_batch* pb = new pie_batch();
   pb->R = R; pb->T = T;
@@ -838,6 +890,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   pb->n_dwaves = (int32_t)dwaves.size();
   pb->dslots = dslots;
   pb->n_pitems = (int32_t)pitems.size();
+  pb->n_pwork = (int32_t)pwork.size();
   pb->n_dec_reqs = (int32_t)dec_reqs.size();
   pb->rows_cap = std::max(rows_cap, 1);
   pb->work[0] = kv_bytes; pb->work[1] = kv_bytes_dec; pb->work[2] = flops; pb->work[3] = (int64_t)visit_phys.size();
@@ -870,7 +923,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t o_dc = blob.add(dcols.data(), dcols.size() * sizeof(DecodeCol), 16);
   const size_t o_mi = blob.add(mref_indptr.data(), mref_indptr.size() * 4, 4);
   const size_t o_mr = blob.add(mrefs.data(), mrefs.size() * 4, 4);
-  const size_t o_pi = blob.add(pitems.data(), pitems.size() * sizeof(PrefillItem), 8);
+  const size_t o_pi = blob.add(pwork.data(), pwork.size() * sizeof(PrefillItem), 16);
   const size_t o_dr = blob.add(dec_reqs.data(), dec_reqs.size() * 4, 4);
   const size_t part_rows = (size_t)pb->n_dsegs * pb->rows_cap;
   const size_t o_po = blob.add(nullptr, 0, 0);  // metadata ends here; the partial buffers are device-only
@@ -1047,7 +1100,7 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
   // which is bound by HBM reads.
   if (b->n_pitems > 0) {
     tm.begin(PIE_STAGE_ATTN_PREFILL);
-    HIP_TRY(c, launch_attn_prefill(a, b->pitems, b->n_pitems, s));
+    HIP_TRY(c, launch_attn_prefill(a, b->pitems, b->n_pwork, s));
     tm.end(PIE_STAGE_ATTN_PREFILL);
   }
   if (b->n_dec_reqs > 0) {
