@@ -496,6 +496,19 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, const int32_
   for (int e = 0; e < E; ++e) out[e] = f32_to_bf16(num[e] * inv);
 }
 
+// N consecutive 1 KiB pieces global -> LDS (16 bytes per lane each); the immediate offset of the instruction
+// moves both addresses, so one address computation serves the run.
+template <int N>
+__device__ __forceinline__ void lds_copy_run(const char* src, char* dst) {
+  static_assert(N >= 1 && N <= 4, "the immediate offset reaches 4 KiB");
+  const auto g = (const __attribute__((address_space(1))) void*)src;
+  const auto l = (__attribute__((address_space(3))) void*)dst;
+  __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
+  if constexpr (N > 1) __builtin_amdgcn_global_load_lds(g, l, 16, 1024, 0);
+  if constexpr (N > 2) __builtin_amdgcn_global_load_lds(g, l, 16, 2048, 0);
+  if constexpr (N > 3) __builtin_amdgcn_global_load_lds(g, l, 16, 3072, 0);
+}
+
 // ------------------------------------------------------------------------------------------------
 // prefill
 // ------------------------------------------------------------------------------------------------
@@ -505,8 +518,10 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, const int32_
 // instruction; the page block is already in operand order) into a ring of four stages, so the copies of the
 // next three pairs are in flight while a pair is computed.  Every step issues exactly one copy batch (past the
 // end it re-reads the last pair into a stage nobody consumes), which keeps the wait-counter arithmetic
-// uniform: a pair has landed when at most two younger batches are outstanding.  Page ids are read with scalar
-// loads one pair ahead; mask words are fetched with the copy, three steps ahead of their use.
+// uniform: a pair has landed when at most two younger batches are outstanding.  Page ids are read with one scalar
+// 16-byte load per pair, one pair ahead; mask words are fetched with the copy, three steps ahead of their use.
+// Workgroups are listed per XCD by the host (all query blocks of a (request, kv head) on one XCD, whose L2 then
+// serves the re-reads of its K/V); the lists are padded with empty items.
 template <int D, int G>
 __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
   constexpr int BLK = 2 * PAGE * D;            // elements of one (page, head) block: K part then V part
@@ -537,47 +552,47 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
   }
   const int n_pairs = (v_end + 1) / 2;
   if (n_pairs > 0) {
-    // Page ids are workgroup-uniform: they are read through the constant address space (scalar loads, which do
-    // not count as vector memory operations, so waiting for them never drains the copies in flight), one pair
-    // ahead of the pair that is started.
-    typedef const __attribute__((address_space(4))) int32_t* const_i32;
-    const const_i32 vis_phys = (const_i32)(a.visit_phys + rq.visit0);
-    const const_i32 vis_log = (const_i32)(a.visit_logical + rq.visit0);
-    int nx_pa = 0, nx_la = 0, nx_pb = 0, nx_lb = 0;
-    auto fetch_ids = [&](int pair) {  // ids of pair min(pair, n_pairs - 1); a missing second page repeats the first
-      const int v = (pair < n_pairs ? pair : n_pairs - 1) * 2;
-      const int v2 = v + 1 < v_end ? v + 1 : v;
-      nx_pa = vis_phys[v];
-      nx_la = vis_log[v];
-      nx_pb = vis_phys[v2];
-      nx_lb = vis_log[v2];
-    };
-    const bf16_t* kvh = a.kv + (int64_t)hk * BLK + lane * 8;
-    const int64_t page_stride = (int64_t)a.Hkv * BLK;
+    // Page ids are workgroup-uniform: one 16-byte scalar load per pair (physical and logical id of both pages)
+    // through the constant address space (scalar loads do not count as vector memory operations, so waiting for
+    // them never drains the copies in flight), one pair ahead of the pair that is started.
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(4))) i32x4* const_i32x4;
+    const const_i32x4 vis = (const_i32x4)(a.visit_pairs) + rq.pair0;
+    i32x4 nx = {0, 0, 0, 0};
+    auto fetch_ids = [&](int pair) { nx = vis[pair < n_pairs ? pair : n_pairs - 1]; };
+    // Copies: this wave's pieces of a pair are consecutive 1 KiB pieces of one page block (of both blocks when
+    // the workgroup is a single wave).  The source is a scalar base (page block) plus a per-lane offset, the
+    // pieces of a run differ only in the instruction's immediate offset, which applies to both addresses.
+    const int hgu = __builtin_amdgcn_readfirstlane(hg);
+    constexpr int RUN = IPW < 4 ? IPW : 4;
+    static_assert(IPW % RUN == 0 && PIECES % RUN == 0, "runs of copy pieces must not straddle page blocks");
+    const char* kv_hk = reinterpret_cast<const char*>(a.kv + (int64_t)hk * BLK);
+    const int64_t page_stride_b = (int64_t)a.Hkv * BLK * 2;
+    const uint32_t lane_off = lane * 16;
     const uint32_t* mrow = a.mask_words + rq.mask_off + (int64_t)i_ld * rq.wpr;
     struct Meta { int pl_a, pl_b; bool has_b, full; uint32_t mw_a, mw_b; };
     Meta m0{}, m1{}, m2{}, m3{};
-    // Inferred-causal blocks of 32 real rows: a pair whose last key is at or below the first row's limit is
-    // visible to every row, which the whole workgroup knows without any per-lane arithmetic.
+    // Inferred-causal blocks of 32 real rows: the first n_full pairs lie entirely at or below the first row's
+    // limit (pages are visited in logical order without gaps when there is no bitmap), so every row sees all of
+    // their keys, which the whole workgroup knows without any per-lane arithmetic.
     const bool rows_full = !has_bitmap && it.qb * 32 + 31 < rq.n_new;
     const int first_lim = rq.kv_len - rq.n_new + it.qb * 32;
+    const int n_full = rows_full ? min(v_end / 2, (first_lim + 1) / 32) : 0;
     auto start_pair = [&](bf16_t* stage, int pair, Meta& md) {
       const int pc = pair < n_pairs ? pair : n_pairs - 1;
-      const int pp_a = nx_pa, pp_b = nx_pb;  // fetched by the previous call (pairs are started in order)
-      md.pl_a = nx_la;
-      md.pl_b = nx_lb;
+      const int pp_a = nx[0], pp_b = nx[2];  // fetched by the previous call (pairs are started in order)
+      md.pl_a = nx[1];
+      md.pl_b = nx[3];
       md.has_b = pc * 2 + 1 < v_end;
       fetch_ids(pair + 1);
-      md.full = rows_full && md.has_b && max(md.pl_a, md.pl_b) * PAGE + PAGE - 1 <= first_lim;
+      md.full = pair < n_full;
       if (has_bitmap && valid) { md.mw_a = mrow[md.pl_a >> 1]; md.mw_b = mrow[md.pl_b >> 1]; }
-      const bf16_t* sa = kvh + (int64_t)pp_a * page_stride;
-      const bf16_t* sb = kvh + (int64_t)pp_b * page_stride;
 #pragma unroll
-      for (int q = 0; q < IPW; ++q) {
-        const int j = hg * IPW + q;  // workgroup-wide copy index: page j / PIECES, piece j % PIECES
-        const bf16_t* src = (j >= PIECES ? sb : sa) + (j % PIECES) * 512;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(stage + j * 512), 16, 0, 0);
+      for (int run = 0; run < IPW / RUN; ++run) {
+        const int j0 = hgu * IPW + run * RUN;  // workgroup-wide copy index: page j0 / PIECES, piece j0 % PIECES
+        const int page = j0 >= PIECES ? pp_b : pp_a;
+        const char* src = kv_hk + (int64_t)page * page_stride_b + (j0 % PIECES) * 1024;
+        lds_copy_run<RUN>(src + lane_off, reinterpret_cast<char*>(stage) + j0 * 1024);
       }
     };
     const int koff = (m < 16 ? 0 : BLK) + g * 128 + (m & 15) * 8;

@@ -59,7 +59,7 @@ struct ReqInfo {       // one per request, device + host
   int32_t wpr;         // mask words per row (0: inferred causal)
   int64_t mask_off;    // word offset of the request's first row
   int32_t dec_index;   // index among the decode-path requests, or -1
-  int32_t pad;
+  int32_t pair0;       // prefill path: first entry of the request's list of visited page pairs
 };
 
 struct DecodeCol {     // one query column of a column group: (request token, head within the kv group)
@@ -91,6 +91,7 @@ struct pie_batch {
   int n_lora_tiles = 0;
   std::vector<int32_t> used_adapters;  // host: distinct adapters named by the batch
   int32_t *visit_phys = nullptr, *visit_logical = nullptr;
+  int32_t* visit_pairs = nullptr;  // prefill-path requests: (physical, logical, physical, logical) per pair of visited pages
   uint32_t* mask_words = nullptr;
   ReqInfo* reqs = nullptr;
   DecodeSeg* dsegs = nullptr;
@@ -214,6 +215,7 @@ struct AttnArgs {
   const ReqInfo* reqs;
   const int32_t* visit_phys;
   const int32_t* visit_logical;
+  const int32_t* visit_pairs;  // 16-byte entries (physical a, logical a, physical b, logical b); an odd tail repeats its page
   const uint32_t* mask_words;
 };
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const int2* wave_pg, int slots,

@@ -525,7 +525,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     if (any) tok_adapter.assign(T, -1);  // filled once the token ranges have been checked
   }
   std::vector<ReqInfo> reqs(R);
-  std::vector<int32_t> tok_page(T), tok_slot(T), visit_phys, visit_logical, dec_reqs;
+  std::vector<int32_t> tok_page(T), tok_slot(T), visit_phys, visit_logical, visit_pairs, dec_reqs;
   std::vector<int32_t> pos_from_embeds;  // positions recorded by embed_txt, when the batch names none
   if (!b->positions) pos_from_embeds.resize(T);
   std::vector<PrefillItem> pitems;
@@ -548,7 +548,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     ReqInfo& q = reqs[r];
     q.tok0 = t0; q.n_new = n_new; q.kv_len = L;
     q.visit0 = (int32_t)visit_phys.size();
-    q.wpr = 0; q.mask_off = 0; q.dec_index = -1; q.pad = 0;
+    q.wpr = 0; q.mask_off = 0; q.dec_index = -1; q.pair0 = 0;
     for (int i = 0; i < n_new; ++i) {
       const int t = t0 + i, j = L - n_new + i;
       if (b->in_embed_ids[t] < 0 || b->in_embed_ids[t] >= c->p.n_embeds)
@@ -626,6 +626,14 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     } else {
       const int nqb = (n_new + 31) / 32;
       for (int qb = 0; qb < nqb; ++qb) pitems.push_back(PrefillItem{r, qb, 0, 0});
+      q.pair0 = (int32_t)(visit_pairs.size() / 4);
+      for (int v = 0; v < q.n_visit; v += 2) {
+        const int v2 = v + 1 < q.n_visit ? v + 1 : v;
+        visit_pairs.push_back(visit_phys[q.visit0 + v]);
+        visit_pairs.push_back(visit_logical[q.visit0 + v]);
+        visit_pairs.push_back(visit_phys[q.visit0 + v2]);
+        visit_pairs.push_back(visit_logical[q.visit0 + v2]);
+      }
       visited_pages = q.n_visit;  // each page is needed at least once
       if (q.wpr == 0) flops += (int64_t)c->m.n_q_heads * D * 4 * ((int64_t)n_new * (L - n_new) + (int64_t)n_new * (n_new + 1) / 2);
       else flops += visited_pages * PAGE * (int64_t)n_new * c->m.n_q_heads * D * 4;
@@ -909,6 +917,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t o_lt = blob.add(lora_tile_ad.empty() ? nullptr : lora_tile_ad.data(), lora_tile_ad.size() * 4, 4);
   const size_t o_vp = blob.add(visit_phys.data(), visit_phys.size() * 4, 8);
   const size_t o_vl = blob.add(visit_logical.data(), visit_logical.size() * 4, 8);
+  const size_t o_vq = blob.add(visit_pairs.data(), visit_pairs.size() * 4, 16);
   const size_t o_mw = blob.add(n_mask_given ? b->mask_words : nullptr, n_mask_given * 4, 0);
   if (!extra_words.empty()) {  // directly behind the caller's words: one array for the kernels
     const size_t at = blob.bytes.size();
@@ -973,7 +982,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   pb->lora_rows = lora_rows.empty() ? nullptr : (int32_t*)(d + o_lr);
   pb->lora_tile_ad = lora_tile_ad.empty() ? nullptr : (int32_t*)(d + o_lt);
   pb->used_adapters = used_adapters;
-  pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl);
+  pb->visit_phys = (int32_t*)(d + o_vp); pb->visit_logical = (int32_t*)(d + o_vl); pb->visit_pairs = (int32_t*)(d + o_vq);
   pb->mask_words = (uint32_t*)(d + o_mw); pb->reqs = (ReqInfo*)(d + o_rq);
   pb->dsegs = (DecodeSeg*)(d + o_di); pb->dwaves = (DecodeWave*)(d + o_ws); pb->wave_pg = (int2*)(d + o_wp);
   pb->dcols = (DecodeCol*)(d + o_dc); pb->mref_indptr = (int32_t*)(d + o_mi); pb->mrefs = (int32_t*)(d + o_mr);
@@ -1094,7 +1103,7 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
   AttnArgs a{};
   a.q = c->qkv; a.q_stride = QKV; a.kv = kv_layer; a.out = c->attn; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
   a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
-  a.reqs = b->reqs; a.visit_phys = b->visit_phys; a.visit_logical = b->visit_logical; a.mask_words = b->mask_words;
+  a.reqs = b->reqs; a.visit_phys = b->visit_phys; a.visit_logical = b->visit_logical; a.visit_pairs = b->visit_pairs; a.mask_words = b->mask_words;
   // Prefill attention first: it is bound by arithmetic, so the write-back of the lines the rotary step left dirty
   // (q rows and appended K/V of every prefill token) happens underneath it instead of slowing the decode kernel,
   // which is bound by HBM reads.
