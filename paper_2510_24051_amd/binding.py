@@ -91,6 +91,7 @@ def load_library():
         "pie_stage_times": [vp, vp],
         "pie_batch_work": [vp, vp],
         "pie_batch_plan_info": [vp, vp],
+        "pie_batch_prefill_work": [vp, vp, i32, vp],
         "pie_create_planner": [C.POINTER(ModelDescC), C.POINTER(PoolDescC), i32, C.POINTER(vp)],
     }
     for name, args in sigs.items():
@@ -126,6 +127,14 @@ class PieBatch:
         self.owner._check(self.owner.lib.pie_batch_plan_info(self.handle, _ptr(out)))
         return {"decode_waves": int(out[0]), "segments": int(out[1]), "max_pairs_per_wave": int(out[2]),
                 "prefill_items": int(out[3]), "decode_requests": int(out[4]), "rows_cap": int(out[5])}
+
+    def prefill_work(self) -> np.ndarray:
+        """[n, 3] int32 (request, query block, kv head) per workgroup of the prefill launch; request -1 = empty."""
+        n = C.c_int32(0)
+        self.owner._check(self.owner.lib.pie_batch_prefill_work(self.handle, None, 0, C.byref(n)))
+        out = np.zeros((max(n.value, 1), 3), dtype=np.int32)
+        self.owner._check(self.owner.lib.pie_batch_prefill_work(self.handle, _ptr(out), n.value, C.byref(n)))
+        return out[:n.value]
 
     def destroy(self):
         if self.handle is not None:

@@ -239,6 +239,7 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, in
   __shared__ uint32_t red[TM_THREADS / 64];
   __shared__ unsigned long long sh_prefix;
   __shared__ uint32_t sh_need, sh_eq, sh_count;
+  __shared__ uint32_t rank_s[256];
   __shared__ float sh_max, sh_sum;
   const int tid = threadIdx.x;
   const int row = blockIdx.x;
@@ -276,6 +277,29 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, in
       if (pos < (uint32_t)n2) top[pos] = c[i];  // exactly k by construction; never write past the buffer
     }
   __syncthreads();
+  const float inv_sum = 1.0f / sh_sum, gmax = sh_max;
+  auto emit = [&](int slot, unsigned long long v) {
+    const int id = (int)(0xFFFFFFFFu - (uint32_t)(v & 0xFFFFFFFFull));
+    out_ids[(int64_t)row * k + slot] = id;
+    out_probs[(int64_t)row * k + slot] = expf((key_to_float((uint32_t)(v >> 32)) - gmax) * inv_temp) * inv_sum;
+  };
+  if (n2 <= 256) {
+    // Few survivors: every composite finds its place by counting the larger ones (they are unique, so the counts
+    // are a permutation).  TM_THREADS / n2 threads share the comparisons of one element; the threads of a wave
+    // read the same composite in every step (an LDS broadcast).  Two barriers instead of one per bitonic stage.
+    const int parts = TM_THREADS / n2, e = tid & (n2 - 1), part = tid / n2;
+    if (tid < n2) rank_s[tid] = 0u;
+    __syncthreads();
+    if (e < k) {
+      const unsigned long long mine = top[e];
+      uint32_t larger = 0u;
+      for (int j = part; j < k; j += parts) larger += top[j] > mine ? 1u : 0u;
+      if (larger) atomicAdd(&rank_s[e], larger);
+    }
+    __syncthreads();
+    if (tid < k) emit((int)rank_s[tid], top[tid]);
+    return;
+  }
   for (int size = 2; size <= n2; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
       for (int i = tid; i < n2 / 2; i += TM_THREADS) {
@@ -291,13 +315,7 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, in
       __syncthreads();
     }
   }
-  const float inv_sum = 1.0f / sh_sum, gmax = sh_max;
-  for (int i = tid; i < k; i += TM_THREADS) {
-    const unsigned long long v = top[i];
-    const int id = (int)(0xFFFFFFFFu - (uint32_t)(v & 0xFFFFFFFFull));
-    out_ids[(int64_t)row * k + i] = id;
-    out_probs[(int64_t)row * k + i] = expf((key_to_float((uint32_t)(v >> 32)) - gmax) * inv_temp) * inv_sum;
-  }
+  for (int i = tid; i < k; i += TM_THREADS) emit(i, top[i]);
 }
 
 // chunks per row for a vocabulary of V entries; 0 when the combination is not supported

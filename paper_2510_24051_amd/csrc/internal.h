@@ -103,6 +103,7 @@ struct pie_batch {
   PrefillItem* pitems = nullptr;
   int32_t* dec_reqs = nullptr;  // request indices on the decode path
   int32_t n_dsegs = 0, n_dwaves = 0, dslots = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
+  std::vector<PrefillItem> pwork_host;  // host copy of the prefill launch layout (inspection)
   int32_t n_pwork = 0;  // workgroups of the prefill launch: (query block, kv head) items laid out per XCD, padded
   float* part_o = nullptr;   // [n_dsegs * rows_cap, D]
   float* part_ml = nullptr;  // [n_dsegs * rows_cap, 2]

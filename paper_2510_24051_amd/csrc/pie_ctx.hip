@@ -899,6 +899,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   pb->dslots = dslots;
   pb->n_pitems = (int32_t)pitems.size();
   pb->n_pwork = (int32_t)pwork.size();
+  pb->pwork_host = pwork;
   pb->n_dec_reqs = (int32_t)dec_reqs.size();
   pb->rows_cap = std::max(rows_cap, 1);
   pb->work[0] = kv_bytes; pb->work[1] = kv_bytes_dec; pb->work[2] = flops; pb->work[3] = (int64_t)visit_phys.size();
@@ -1017,6 +1018,18 @@ extern "C" pie_status pie_batch_plan_info(const pie_batch* b, int64_t* out) {
   out[3] = b->n_pitems;
   out[4] = b->n_dec_reqs;
   out[5] = b->rows_cap;
+  return PIE_OK;
+}
+
+extern "C" pie_status pie_batch_prefill_work(const pie_batch* b, int32_t* out, int32_t cap, int32_t* n_entries) {
+  if (!b || !n_entries || cap < 0 || (cap > 0 && !out)) return PIE_EINVAL;
+  *n_entries = (int32_t)b->pwork_host.size();
+  const int32_t n = std::min<int32_t>(cap, *n_entries);
+  for (int32_t i = 0; i < n; ++i) {
+    out[i * 3] = b->pwork_host[i].r;
+    out[i * 3 + 1] = b->pwork_host[i].qb;
+    out[i * 3 + 2] = b->pwork_host[i].hk;
+  }
   return PIE_OK;
 }
 

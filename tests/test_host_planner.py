@@ -128,6 +128,61 @@ def test_plan_statistics_match_the_batch(name, w):
     ctx.close()
 
 
+def prefill_mix(n_kv=8, sizes=((1024, 0), (1024, 1500), (512, 100), (300, 2040), (40, 0), (33, 700))):
+    m = small_model(128, 4 * n_kv if n_kv <= 2 else 2 * n_kv, n_kv)
+    reqs = [W.RequestSpec(n, prior) for n, prior in sizes] + [W.RequestSpec(1, 900), W.RequestSpec(1, 64)]
+    pages = sum((n + p + 15) // 16 for n, p in sizes) + 80
+    return W.build_workload("prefill_mix", m, reqs, n_kv_pages=pages, seed=4100 + n_kv, std=0.02, with_head=False)
+
+
+@pytest.mark.parametrize("n_kv", [8, 2, 1])
+def test_prefill_launch_covers_every_block_once_and_keeps_a_head_on_one_xcd(n_kv):
+    """The prefill launch lists one workgroup per (request, 32-token query block, kv head): each exactly once,
+    empty slots only as padding, workgroup i on XCD i % 8; the query blocks of one (request, kv head) share an
+    XCD unless the planner had to cut groups to even out the XCDs; the XCDs' loads are even."""
+    w = prefill_mix(n_kv)
+    b, m = w.batch, w.model
+    ctx = planner_for(w)
+    pb = ctx.batch_create(w.batch, validate=True)
+    work = pb.prefill_work()
+    G = m.n_q_heads // m.n_kv_heads
+    expected = set()
+    cost = {}
+    for r in range(b.n_requests):
+        n_new = int(b.tok_indptr[r + 1] - b.tok_indptr[r])
+        if n_new * G <= 16:
+            continue
+        for qb in range((n_new + 31) // 32):
+            for hk in range(m.n_kv_heads):
+                expected.add((r, qb, hk))
+                cost[(r, qb, hk)] = int(b.kv_len[r]) - n_new + min(n_new, qb * 32 + 32)
+    assert pb.plan_info()["prefill_items"] * m.n_kv_heads == len(expected)
+    assert work.shape[0] % 8 == 0
+    real = [tuple(int(x) for x in row) for row in work if row[0] >= 0]
+    assert len(real) == len(set(real)) == len(expected) and set(real) == expected
+    assert all(row[1] == 0 and row[2] == 0 for row in work if row[0] < 0)
+    xcd_of, load = {}, np.zeros(8)
+    for i, row in enumerate(work):
+        if row[0] >= 0:
+            key = (int(row[0]), int(row[1]), int(row[2]))
+            xcd_of.setdefault((key[0], key[2]), set()).add(i % 8)
+            load[i % 8] += cost[key]
+    groups = len(xcd_of)
+    if groups >= 16:  # enough groups to balance whole: none is cut
+        assert all(len(v) == 1 for v in xcd_of.values())
+    # even loads: no XCD more than a quarter above the mean, unless a single query block is that heavy
+    heaviest = max(cost.values())
+    assert load.max() <= max(1.25 * load.mean(), load.mean() + heaviest), load
+    # within an XCD's list the blocks of a group are next to each other when groups are whole
+    if groups >= 16:
+        for x in range(8):
+            seq = [(int(r), int(h)) for r, q, h in work[x::8] if r >= 0]
+            changes = sum(1 for a, c in zip(seq, seq[1:]) if a != c)
+            assert changes == len(set(seq)) - 1
+    pb.destroy()
+    ctx.close()
+
+
 def test_plan_depends_on_the_resident_waves_but_the_work_does_not():
     w = dict(workloads())["decode64"]
     small, big = planner_for(w, wave_slots=64), planner_for(w, wave_slots=2048)
