@@ -19,6 +19,7 @@
 #define TC_THREADS 512
 // keys per thread of the chunk kernel: 16 (chunks of at most 8192 logits) or, when there are enough rows to fill
 // the chip with half as many workgroups, 32 (16384 logits): half the block-wide synchronisation per logit
+#define TC_LIST 2048  // composites the chunk kernel's short-list selection holds (4 per thread)
 #define TM_THREADS 1024
 #define TM_PER 16  // composites per thread: at most 16384 candidates per row
 
@@ -45,6 +46,28 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* red) {
   return t;
 }
 
+// Top byte of the need-th largest key: walk the byte values downward from the maximum's, counting matches in
+// registers.  On return *out_b is that byte, *out_need what is still needed among the keys that carry it and
+// *out_cnt how many keys carry it (need - *out_need keys have a larger top byte).
+template <typename KeyT, int PER, int THREADS>
+__device__ __forceinline__ void walk_top_byte(const KeyT (&keys)[PER], uint32_t need, int top_byte_max, uint32_t* red,
+                                              int* out_b, uint32_t* out_need, uint32_t* out_cnt) {
+  constexpr int TOP = sizeof(KeyT) * 8 - 8;
+  int b = top_byte_max;
+  uint32_t cnt = 0;
+  for (;; --b) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) c += ((int)(keys[i] >> TOP) == b && keys[i] != 0) ? 1u : 0u;
+    cnt = block_sum<THREADS>(c, red);
+    if (cnt >= need || b == 0) break;
+    need -= cnt;
+  }
+  *out_b = b;
+  *out_need = need;
+  *out_cnt = cnt;
+}
+
 // k-th largest of the workgroup's keys (PER per thread in registers, key 0 = padding below every real key).
 // On return: *out_kth the selected value, *out_need how many keys equal to it belong to the top set, *out_eq
 // how many keys equal it in total.  hist: 256 words, red: THREADS / 64 words of LDS.
@@ -57,17 +80,9 @@ __device__ __forceinline__ void select_kth(const KeyT (&keys)[PER], uint32_t nee
                                            uint32_t* sh_eq, KeyT* out_kth, uint32_t* out_need, uint32_t* out_eq) {
   constexpr int TOP = sizeof(KeyT) * 8 - 8;
   const int tid = threadIdx.x, lane = tid & 63;
-  // top byte: walk downward from the maximum's
-  int b = top_byte_max;
-  uint32_t cnt = 0;
-  for (;; --b) {
-    uint32_t c = 0;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) c += ((int)(keys[i] >> TOP) == b && keys[i] != 0) ? 1u : 0u;
-    cnt = block_sum<THREADS>(c, red);
-    if (cnt >= need || b == 0) break;
-    need -= cnt;
-  }
+  int b;
+  uint32_t cnt;
+  walk_top_byte<KeyT, PER, THREADS>(keys, need, top_byte_max, red, &b, &need, &cnt);
   KeyT prefix = (KeyT)b << TOP;
   uint32_t eq = cnt;  // keys matching the decided bits
   for (int shift = TOP - 8; shift >= 0; shift -= 8) {
@@ -122,6 +137,8 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
   __shared__ uint32_t red[TC_THREADS / 64];
   __shared__ float fred[TC_THREADS / 64];
   __shared__ uint32_t sh_prefix, sh_need, sh_eq, sh_count, sh_count_eq, sh_wave_off[TC_THREADS / 64 + 1];
+  __shared__ unsigned long long sh_prefix64;
+  __shared__ unsigned long long list[TC_LIST];
   __shared__ float sh_max;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = blockIdx.x, chunk = blockIdx.y, n_chunks = gridDim.y;
@@ -156,10 +173,12 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
   }
   __syncthreads();
   const float cmax = sh_max;
+  // exponentials on the hardware's base-2 instruction (1 ulp): arguments are <= 0, nothing to guard
+  const float c2 = inv_temp * 1.44269504088896340736f;
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < TC_PER; ++i)
-    if (keys[i] != 0u) sum += expf((key_to_float(keys[i]) - cmax) * inv_temp);
+    if (keys[i] != 0u) sum += __builtin_amdgcn_exp2f((key_to_float(keys[i]) - cmax) * c2);
   sum = wave_sum(sum);
   __syncthreads();
   if (lane == 0) fred[wave] = sum;
@@ -171,17 +190,67 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
     stats[((int64_t)row * n_chunks + chunk) * 2 + 1] = t;
   }
   const int kc = min(k, n);  // candidates this chunk contributes
-  uint32_t kth, need_eq, eq_total;
-  select_kth<uint32_t, TC_PER, TC_THREADS>(keys, (uint32_t)kc, (int)(order_key(cmax) >> 24), 0, hist, red, &sh_prefix,
-                                           &sh_need, &sh_eq, &kth, &need_eq, &eq_total);
   unsigned long long* out = cand + ((int64_t)row * n_chunks + chunk) * k;
-  // keys above kth: any order, slots [need_eq, kc); keys equal to kth: slots [0, need_eq), lowest ids first when
-  // only some of them are taken
-  const bool split_tie = eq_total != need_eq;
   auto comp_of = [&](int i) {
     const int id = start + tid * 4 + (i >> 2) * 4 * TC_THREADS + (i & 3);
     return ((unsigned long long)keys[i] << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)id);
   };
+  // Usually only a few per cent of the keys share the top byte of the k-th largest or lie above it.  Those are
+  // collected as composites in LDS (per-thread counts, a wave scan, one atomic per wave), and the selection runs
+  // on that short list, at most TC_LIST / TC_THREADS composites per thread; composites are unique, so equal
+  // logits at the cut resolve to the lower ids without a separate pass.  Longer lists (e.g. many equal logits)
+  // take the selection over all keys in registers below.
+  const int top_byte = (int)(order_key(cmax) >> 24);
+  int wb;
+  uint32_t w_need, w_cnt;
+  walk_top_byte<uint32_t, TC_PER, TC_THREADS>(keys, (uint32_t)kc, top_byte, red, &wb, &w_need, &w_cnt);
+  const uint32_t n_list = (uint32_t)kc - w_need + w_cnt;  // keys whose top byte is wb or larger
+  if (n_list <= TC_LIST) {
+    uint32_t mine = 0u;
+#pragma unroll
+    for (int i = 0; i < TC_PER; ++i) mine += ((int)(keys[i] >> 24) >= wb && keys[i] != 0u) ? 1u : 0u;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    uint32_t base = 0u;
+    if (lane == 63 && incl) base = atomicAdd(&sh_count_eq, incl);  // sh_count_eq: entries of the list so far
+    uint32_t pos = __shfl(base, 63) + incl - mine;
+#pragma unroll
+    for (int i = 0; i < TC_PER; ++i)
+      if ((int)(keys[i] >> 24) >= wb && keys[i] != 0u) {
+        if (pos < TC_LIST) list[pos] = comp_of(i);
+        ++pos;
+      }
+    __syncthreads();
+    unsigned long long c[TC_LIST / TC_THREADS];
+#pragma unroll
+    for (int j = 0; j < TC_LIST / TC_THREADS; ++j) {
+      const uint32_t idx = tid + j * TC_THREADS;
+      c[j] = idx < n_list ? list[idx] : 0ull;
+    }
+    unsigned long long kth64;
+    uint32_t need64, eq64;
+    select_kth<unsigned long long, TC_LIST / TC_THREADS, TC_THREADS>(c, (uint32_t)kc, top_byte, 32, hist, red, &sh_prefix64,
+                                                                     &sh_need, &sh_eq, &kth64, &need64, &eq64);
+    // exactly kc composites are >= kth64
+#pragma unroll
+    for (int j = 0; j < TC_LIST / TC_THREADS; ++j)
+      if (c[j] >= kth64 && c[j] != 0ull) {
+        const uint32_t p2 = atomicAdd(&sh_count, 1u);
+        if (p2 < (uint32_t)kc) out[p2] = c[j];
+      }
+    for (int i = kc + tid; i < k; i += TC_THREADS) out[i] = 0ull;  // short chunk: pad (a zero never wins)
+    return;
+  }
+  uint32_t kth, need_eq, eq_total;
+  select_kth<uint32_t, TC_PER, TC_THREADS>(keys, (uint32_t)kc, (int)(order_key(cmax) >> 24), 0, hist, red, &sh_prefix,
+                                           &sh_need, &sh_eq, &kth, &need_eq, &eq_total);
+  // keys above kth: any order, slots [need_eq, kc); keys equal to kth: slots [0, need_eq), lowest ids first when
+  // only some of them are taken
+  const bool split_tie = eq_total != need_eq;
 #pragma unroll
   for (int i = 0; i < TC_PER; ++i) {
     if (keys[i] > kth) {
@@ -228,6 +297,7 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
   for (int i = kc + tid; i < k; i += TC_THREADS) out[i] = 0ull;  // short chunk: pad (a zero never wins)
 }
 
+template <int PER>  // composites per thread: the smallest of 2, 4, 8, 16 that holds the row's candidates
 __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, int k, float inv_temp,
                                                                 const unsigned long long* __restrict__ cand,
                                                                 const float* __restrict__ stats, int n2,
@@ -244,9 +314,9 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, in
   const int tid = threadIdx.x;
   const int row = blockIdx.x;
   const int n = n_chunks * k;
-  unsigned long long c[TM_PER];
+  unsigned long long c[PER];
 #pragma unroll
-  for (int i = 0; i < TM_PER; ++i) {
+  for (int i = 0; i < PER; ++i) {
     const int idx = tid + i * TM_THREADS;
     c[i] = idx < n ? cand[(int64_t)row * n + idx] : 0ull;
   }
@@ -267,11 +337,11 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, in
   uint32_t need_eq, eq_total;
   // the id half of a composite only matters when equal logits straddle the cut: stop after the key half when
   // every candidate sharing the selected key is needed
-  select_kth<unsigned long long, TM_PER, TM_THREADS>(c, (uint32_t)k, top_byte, 32, hist, red, &sh_prefix, &sh_need,
+  select_kth<unsigned long long, PER, TM_THREADS>(c, (uint32_t)k, top_byte, 32, hist, red, &sh_prefix, &sh_need,
                                                      &sh_eq, &kth, &need_eq, &eq_total);
   // composites are unique: exactly k of them are >= kth
 #pragma unroll
-  for (int i = 0; i < TM_PER; ++i)
+  for (int i = 0; i < PER; ++i)
     if (c[i] >= kth && c[i] != 0ull) {
       const uint32_t pos = atomicAdd(&sh_count, 1u);
       if (pos < (uint32_t)n2) top[pos] = c[i];  // exactly k by construction; never write past the buffer
@@ -346,7 +416,15 @@ hipError_t launch_topk(const float* logits, int n, int V, int k, float inv_temp,
     topk_chunk_kernel<16><<<dim3(n, n_chunks), dim3(TC_THREADS), 0, s>>>(logits, V, chunk_len, k, inv_temp, cand_ws, stats_ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  topk_merge_kernel<<<dim3(n), dim3(TM_THREADS), smem_b, s>>>(n_chunks, k, inv_temp, cand_ws, stats_ws, n2, out_ids,
-                                                               out_probs);
+  const int n_cand = n_chunks * k;
+  const dim3 mg(n), mb(TM_THREADS);
+  if (n_cand <= 2 * TM_THREADS)
+    topk_merge_kernel<2><<<mg, mb, smem_b, s>>>(n_chunks, k, inv_temp, cand_ws, stats_ws, n2, out_ids, out_probs);
+  else if (n_cand <= 4 * TM_THREADS)
+    topk_merge_kernel<4><<<mg, mb, smem_b, s>>>(n_chunks, k, inv_temp, cand_ws, stats_ws, n2, out_ids, out_probs);
+  else if (n_cand <= 8 * TM_THREADS)
+    topk_merge_kernel<8><<<mg, mb, smem_b, s>>>(n_chunks, k, inv_temp, cand_ws, stats_ws, n2, out_ids, out_probs);
+  else
+    topk_merge_kernel<TM_PER><<<mg, mb, smem_b, s>>>(n_chunks, k, inv_temp, cand_ws, stats_ws, n2, out_ids, out_probs);
   return hipGetLastError();
 }

@@ -356,6 +356,22 @@ def test_top_k_ties_pick_lower_ids():
     np.testing.assert_allclose(gp[0], 1.0 / 512, rtol=1e-5)
 
 
+@pytest.mark.parametrize("vocab,k", [(16384, 40), (65536, 300)])
+def test_top_k_ties_in_long_rows(vocab, k):
+    """All logits equal in rows of several chunks: every key shares the top byte of the k-th largest, so the chunk
+    kernel's short list overflows and the selection over all keys in registers runs, with the cut inside the tie."""
+    m = small_model(vocab=vocab)
+    w = W.build_workload("ties_long", m, [W.RequestSpec(1, 3), W.RequestSpec(1, 2)], n_kv_pages=4, seed=44, std=0.05,
+                         top_k=k)
+    w.head.w_lm[:] = 0
+    ctx = make_ctx(w, max_top_k=512)
+    gpu_forward(ctx, w)
+    gi, gp = ctx.get_next_dist(w.batch.out_embed_ids[:2], k, 1.0)
+    for r in range(2):
+        assert gi[r].tolist() == list(range(k))
+    np.testing.assert_allclose(gp, 1.0 / vocab, rtol=1e-5)
+
+
 # ---------------------------------------------------------------- error paths (detected on the host)
 def test_error_codes():
     from paper_2510_24051_amd import Pie, PieError
