@@ -19,9 +19,12 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 
 // Loads are batched ahead of the stores (ids, then residual values, then all stores) so that a tile costs
 // three dependent memory round trips instead of one per element.
-template <int MODE>
+// FULL: all 32 rows of the tile exist (the caller's uniform test), so no per-row predicates are needed; with them
+// every element is its own predicated block and the loads cannot be batched.
+template <int MODE, bool FULL = false>
 __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, const f32x16& acc2, int m0, int n0,
-                                         int M, int N, int lane) {
+                                         int M_rows, int N, int lane) {
+  const int M = FULL ? 0x7fffffff : M_rows;
   const int n = n0 + (lane & 31);
   const int g = lane >> 5;
   if (n >= N) return;
@@ -553,20 +556,82 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
       }
     return;
   }
+  // row tiles that lie wholly inside the matrix (all of them except in a ragged last row block) take the
+  // epilogue without per-row predicates
+  auto epilogue = [&](auto full_c) {
+    constexpr bool FULL = decltype(full_c)::value;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int mt = m0 + wm * (BM / 2) + i * 32;
-    if (MODE == EPI_SWIGLU) {
-      int nb = nb0 + wn * 2;
-      if (nb < NB) epi_tile<MODE>(epi, acc[i][0], acc[i][1], mt, nb * 32, M, NB * 32, lane);
-    } else {
+    for (int i = 0; i < MI; ++i) {
+      const int mt = m0 + wm * (BM / 2) + i * 32;
+      if (MODE == EPI_SWIGLU) {
+        int nb = nb0 + wn * 2;
+        if (nb < NB) epi_tile<MODE, FULL>(epi, acc[i][0], acc[i][1], mt, nb * 32, M, NB * 32, lane);
+      } else {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        int nb = nb0 + wn * 2 + j;
-        if (nb < NB) epi_tile<MODE>(epi, acc[i][j], acc[i][j], mt, nb * 32, M, N, lane);
+        for (int j = 0; j < 2; ++j) {
+          int nb = nb0 + wn * 2 + j;
+          if (nb < NB) epi_tile<MODE, FULL>(epi, acc[i][j], acc[i][j], mt, nb * 32, M, N, lane);
+        }
       }
     }
+  };
+  const bool rows_full = m0 + wm * (BM / 2) + MI * 32 <= M;
+  if constexpr (MODE == EPI_RESID_EMBED || MODE == EPI_RESID_OUT) {
+    // Residual epilogues of full row tiles, pipelined over the wave's 2 * MI accumulator tiles: the Embed ids of
+    // all its rows are read first (one round trip), then the residual values of tile t + 1 are requested before
+    // tile t is stored, so a tile no longer costs two or three dependent round trips of its own.
+    if (rows_full && N % 32 == 0) {
+      const bool by_id = MODE == EPI_RESID_EMBED ? epi.resid == nullptr : epi.out == nullptr;
+      const int g = lane >> 5;
+      const int mw = m0 + wm * (BM / 2) + g * 4;
+      auto row_of = [&](int i, int v) { return mw + i * 32 + (v >> 2) * 8 + (v & 3); };
+      auto run = [&](auto by_id_c) {
+        constexpr bool BY_ID = decltype(by_id_c)::value;
+        int id[MI][16];
+        if (BY_ID) {
+#pragma unroll
+          for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) id[i][v] = epi.ids[row_of(i, v)];
+        }
+        float r[2][16];
+        auto col_of = [&](int t) { return (nb0 + wn * 2 + (t & 1)) * 32 + (lane & 31); };
+        auto fetch = [&](int t, float (&dst)[16]) {
+          const int i = t >> 1, n = col_of(t);
+          if (n >= N) return;  // uniform: a column block past the matrix
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            if (MODE == EPI_RESID_EMBED && BY_ID) dst[v] = bf16_to_f32(epi.embeds[(int64_t)id[i][v] * epi.H + n]);
+            else dst[v] = epi.resid[(int64_t)row_of(i, v) * epi.H + n];
+          }
+        };
+        auto put = [&](int t, const float (&src)[16]) {
+          const int i = t >> 1, j = t & 1, n = col_of(t);
+          if (n >= N) return;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float y = src[v] + acc[i][j][v];
+            if (MODE == EPI_RESID_OUT && BY_ID) {
+              if (id[i][v] >= 0) epi.embeds[(int64_t)id[i][v] * epi.H + n] = f32_to_bf16(y);
+            } else {
+              reinterpret_cast<float*>(epi.out)[(int64_t)row_of(i, v) * epi.ldo + n] = y;
+            }
+          }
+        };
+        fetch(0, r[0]);
+#pragma unroll
+        for (int t = 0; t < 2 * MI; ++t) {
+          if (t + 1 < 2 * MI) fetch(t + 1, r[(t + 1) & 1]);
+          put(t, r[t & 1]);
+        }
+      };
+      if (by_id) run(std::true_type{});
+      else run(std::false_type{});
+      return;
+    }
   }
+  if (rows_full) epilogue(std::true_type{});
+  else epilogue(std::false_type{});
 }
 
 // ------------------------------------------------------------------------------------------------
