@@ -122,19 +122,30 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
   // A tile loader: BM rows x 16 chunks (16 B) per iteration; chunk c of row r is stored at chunk (c ^ (r & 15))
   constexpr int A_CHUNKS = BM * 16;
   constexpr int A_PER_THREAD = (A_CHUNKS + NT - 1) / NT;
-  u32x4 areg[A_PER_THREAD];
+  // The activation chunks travel in the same ring of three register sets as the weights, requested two iterations
+  // ahead and stored to LDS one iteration ahead: the memory counter completes in order, so waiting for the chunks
+  // of iteration it + 1 also waits for every load requested before them; with the chunks requested in the
+  // previous step, the weights of two iterations stay in flight across that wait instead of one.  Only for several
+  // row blocks of one column block per wave (64-row layer products: 0.244 -> 0.239 ms per forward call): with one
+  // row block the extra registers cost the third wave per SIMD, and with two column blocks per wave (LM head) the
+  // kernel got 2-3% slower.
+  constexpr bool A_RING = MB >= 2 && NBW == 1;
+  constexpr int A_SETS = A_RING ? 3 : 1;
+  u32x4 areg[A_SETS][A_PER_THREAD];
   // Loads always read an in-bounds address (row and k clamped); chunks outside the matrix are zeroed when the
   // registers are stored to LDS, so no register is written while an earlier load into it could be pending.
-  auto load_a = [&](int it) {
+  auto load_a = [&](int it, const int slot_ring) {
+    const int slot = A_RING ? slot_ring : 0;
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
       const int c = min(tid + j * NT, A_CHUNKS - 1);
       const int r = min(c >> 4, M - 1), kc = c & 15;
       const int k = min(it * SK_BK + kc * 8, K - 8);
-      areg[j] = *reinterpret_cast<const u32x4*>(A + (int64_t)r * lda + k);
+      areg[slot][j] = *reinterpret_cast<const u32x4*>(A + (int64_t)r * lda + k);
     }
   };
-  auto store_a = [&](int buf, int it) {
+  auto store_a = [&](int buf, int it, const int slot_ring) {
+    const int slot = A_RING ? slot_ring : 0;
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
       const int c = tid + j * NT;
@@ -142,7 +153,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
       const bool inside = r < M && it * SK_BK + kc * 8 < K;
       if (c < A_CHUNKS)
         *reinterpret_cast<u32x4*>(As + buf * A_ELEMS + r * SK_BK + ((kc ^ (r & 15)) << 3)) =
-            inside ? areg[j] : u32x4{0, 0, 0, 0};
+            inside ? areg[slot][j] : u32x4{0, 0, 0, 0};
     }
   };
   bf16x8 breg[3][NBW][8];  // ring of three register sets: the weights of the next two iterations are in flight
@@ -166,8 +177,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
     constexpr int SLOT = decltype(slot_c)::value;
     const int cur = (it - it0) & 1;
     const bool more = it + 1 < it1;
-    if (more) load_a(it + 1);
-    if (it + 2 < it1) load_b(it + 2, (SLOT + 2) % 3);
+    if (!A_RING && more) load_a(it + 1, 0);
+    if (it + 2 < it1) {
+      if (A_RING) load_a(it + 2, (SLOT + 2) % 3);
+      load_b(it + 2, (SLOT + 2) % 3);
+    }
     const bf16_t* Ab = As + cur * A_ELEMS;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -180,15 +194,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
         for (int j = 0; j < NBW; ++j) acc[j][i] = mfma32(af, breg[SLOT][j][s], acc[j][i]);
       }
     }
-    if (more) store_a(cur ^ 1, it + 1);
+    if (more) store_a(cur ^ 1, it + 1, (SLOT + 1) % 3);
     PIE_S_WAIT_LGKMCNT0();
     wg_barrier();
   };
   if (it0 < it1) {
-    load_a(it0);
+    load_a(it0, 0);
     load_b(it0, 0);
-    if (it0 + 1 < it1) load_b(it0 + 1, 1);
-    store_a(0, it0);
+    if (it0 + 1 < it1) {
+      if (A_RING) load_a(it0 + 1, 1);
+      load_b(it0 + 1, 1);
+    }
+    store_a(0, it0, 0);  // waits for the oldest loads only
   }
   PIE_S_WAIT_LGKMCNT0();
   wg_barrier();
