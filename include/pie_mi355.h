@@ -261,7 +261,8 @@ pie_status pie_batch_plan_info(const pie_batch* batch, int64_t* out);
 /* The prefill attention launch of a batch, as the planner laid it out: one entry per workgroup in launch order,
  * three values each (request, 32-token query block, kv head); request -1 marks an empty slot.  Workgroup i runs
  * on XCD i % 8 (the hardware's round-robin), and the planner puts all query blocks of one (request, kv head) on
- * one XCD (section 4.3 leaves batch execution to the handler; this is its layout on this chip, exposed for the
+ * one XCD (System Architecture, Inference layer: how a batch of API calls is executed is the handler's business;
+ * this is its layout on this chip, exposed for the
  * host-logic tests).  Copies at most cap entries into out (host int32[cap * 3]) and stores the total number of
  * entries in *n_entries.  Works on planner contexts. */
 pie_status pie_batch_prefill_work(const pie_batch* batch, int32_t* out, int32_t cap, int32_t* n_entries);
