@@ -142,6 +142,13 @@ struct pie_ctx {
   // device blocks of destroyed batches, kept for the next pie_batch_create (a serving loop creates and destroys a
   // batch per step; hipMalloc + hipFree cost more than the deserialisation itself)
   std::vector<std::pair<void*, size_t>> blob_pool;
+  // host image of a batch's device block, reused from batch to batch (pinned when the context has a device, so
+  // the copy to the device is a single DMA; plain memory on planner contexts)
+  unsigned char* host_blob = nullptr;
+  size_t host_blob_cap = 0;
+  bool host_blob_pinned = false;
+  std::vector<uint32_t> page_stamp;  // host: per pool page, the last batch plan that counted it (distinct-page statistic)
+  uint32_t page_stamp_id = 0;
   int32_t* ids_dev = nullptr;  // staging for id lists of the small resource calls
   size_t ids_cap = 0;
   int last_T = 0, last_dist_n = 0;

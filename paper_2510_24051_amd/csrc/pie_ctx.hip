@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <unordered_set>
@@ -177,6 +178,7 @@ static void free_packed(PackedWeight& w) {
 extern "C" pie_status pie_destroy(pie_ctx* c) {
   if (!c) return PIE_OK;
   if (c->host_only) {  // nothing lives on a device
+    std::free(c->host_blob);
     delete c;
     return PIE_OK;
   }
@@ -195,6 +197,7 @@ extern "C" pie_status pie_destroy(pie_ctx* c) {
   }
   for (void* b : bufs) if (b) (void)hipFree(b);
   for (auto& blk : c->blob_pool) (void)hipFree(blk.first);
+  if (c->host_blob) { if (c->host_blob_pinned) (void)hipHostFree(c->host_blob); else std::free(c->host_blob); }
   for (int i = 0; i < 2 * PIE_N_STAGES; ++i) if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
   delete c;
   return PIE_OK;
@@ -485,12 +488,41 @@ extern "C" pie_status pie_copy_kvpage(pie_ctx* c, const int32_t* src_pages, cons
 // batch deserialisation
 // ---------------------------------------------------------------------------------------------
 namespace {
-struct Blob {  // host image of the device allocation
-  std::vector<unsigned char> bytes;
-  size_t add(const void* src, size_t n, size_t pad = 0) {  // n bytes copied from src, pad zero bytes after
-    size_t off = (bytes.size() + 255) / 256 * 256;
-    bytes.resize(off + n + pad, 0);
-    if (n && src) std::memcpy(bytes.data() + off, src, n);
+struct Blob {  // host image of the device allocation, written into the context's reusable buffer
+  pie_ctx* c;
+  size_t size = 0;
+  bool ok = true;
+  explicit Blob(pie_ctx* ctx) : c(ctx) {}
+  unsigned char* data() const { return c->host_blob; }
+  void reserve(size_t n) {
+    if (n <= c->host_blob_cap) return;
+    size_t cap = std::max<size_t>(std::max(n, c->host_blob_cap * 2), (size_t)1 << 20);
+    unsigned char* p = nullptr;
+    bool pinned = false;
+    if (!c->host_only) {
+      if (hipHostMalloc((void**)&p, cap, hipHostMallocDefault) == hipSuccess) pinned = true;
+      else { (void)hipGetLastError(); p = nullptr; }
+    }
+    if (!p) p = (unsigned char*)std::malloc(cap);
+    if (!p) { ok = false; return; }
+    if (size) std::memcpy(p, c->host_blob, size);
+    if (c->host_blob) { if (c->host_blob_pinned) (void)hipHostFree(c->host_blob); else std::free(c->host_blob); }
+    c->host_blob = p; c->host_blob_cap = cap; c->host_blob_pinned = pinned;
+  }
+  void append(const void* src, size_t n) {  // n bytes from src (zeros when src is null), no alignment
+    reserve(size + n);
+    if (!ok || !n) return;
+    if (src) std::memcpy(c->host_blob + size, src, n); else std::memset(c->host_blob + size, 0, n);
+    size += n;
+  }
+  size_t add(const void* src, size_t n, size_t pad = 0) {  // at the next multiple of 256; pad zero bytes after
+    const size_t off = (size + 255) / 256 * 256;
+    reserve(off + n + pad);
+    if (!ok) return off;
+    std::memset(c->host_blob + size, 0, off - size);
+    size = off;
+    append(n ? src : nullptr, n);
+    append(nullptr, pad);
     return off;
   }
 };
@@ -903,14 +935,23 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   pb->n_dec_reqs = (int32_t)dec_reqs.size();
   pb->rows_cap = std::max(rows_cap, 1);
   pb->work[0] = kv_bytes; pb->work[1] = kv_bytes_dec; pb->work[2] = flops; pb->work[3] = (int64_t)visit_phys.size();
-  {
-    std::unordered_set<int32_t> distinct;
+  {  // distinct pages the decode path visits: a stamp per pool page kept in the context (no clearing, no hashing)
+    if (c->page_stamp.size() != (size_t)c->p.n_kv_pages) c->page_stamp.assign(c->p.n_kv_pages, 0u);
+    if (++c->page_stamp_id == 0u) {  // wrapped: start over
+      std::fill(c->page_stamp.begin(), c->page_stamp.end(), 0u);
+      c->page_stamp_id = 1u;
+    }
+    const uint32_t id = c->page_stamp_id;
+    int64_t distinct = 0;
     for (int r : dec_reqs)
-      distinct.insert(visit_phys.begin() + reqs[r].visit0, visit_phys.begin() + reqs[r].visit0 + reqs[r].n_visit);
-    pb->work[4] = (int64_t)distinct.size() * page_bytes;
+      for (int v = reqs[r].visit0; v < reqs[r].visit0 + reqs[r].n_visit; ++v) {
+        uint32_t& st = c->page_stamp[visit_phys[v]];  // page ids were range-checked when the visit list was built
+        if (st != id) { st = id; ++distinct; }
+      }
+    pb->work[4] = distinct * page_bytes;
   }
   pb->work[5] = kv_bytes_req;
-  Blob blob;
+  Blob blob(c);
   const size_t o_in = blob.add(b->in_embed_ids, (size_t)T * 4), o_out = blob.add(b->out_embed_ids, (size_t)T * 4);
   const size_t o_pos = blob.add(b->positions ? b->positions : pos_from_embeds.data(), (size_t)T * 4), o_tp = blob.add(tok_page.data(), (size_t)T * 4);
   const size_t o_ts = blob.add(tok_slot.data(), (size_t)T * 4);
@@ -921,11 +962,9 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t o_vq = blob.add(visit_pairs.data(), visit_pairs.size() * 4, 16);
   const size_t o_mw = blob.add(n_mask_given ? b->mask_words : nullptr, n_mask_given * 4, 0);
   if (!extra_words.empty()) {  // directly behind the caller's words: one array for the kernels
-    const size_t at = blob.bytes.size();
-    blob.bytes.resize(at + extra_words.size() * 4);
-    std::memcpy(blob.bytes.data() + at, extra_words.data(), extra_words.size() * 4);
+    blob.append(extra_words.data(), extra_words.size() * 4);
   }
-  blob.bytes.resize(blob.bytes.size() + 4, 0);
+  blob.append(nullptr, 4);
   const size_t o_rq = blob.add(reqs.data(), reqs.size() * sizeof(ReqInfo));
   const size_t o_di = blob.add(dsegs.data(), dsegs.size() * sizeof(DecodeSeg), 16);
   const size_t o_ws = blob.add(dwaves.data(), dwaves.size() * sizeof(DecodeWave), 16);
@@ -937,6 +976,10 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   const size_t o_dr = blob.add(dec_reqs.data(), dec_reqs.size() * 4, 4);
   const size_t part_rows = (size_t)pb->n_dsegs * pb->rows_cap;
   const size_t o_po = blob.add(nullptr, 0, 0);  // metadata ends here; the partial buffers are device-only
+  if (!blob.ok) {
+    delete pb;
+    return fail(c, PIE_ENOMEM, "pie_batch_create: no host memory for the batch image");
+  }
   const size_t o_pm = (o_po + part_rows * D * 4 + 255) / 256 * 256;
   const size_t o_an = (o_pm + part_rows * 2 * 4 + 255) / 256 * 256;  // rotary angle table [T, D] floats
   const size_t total_bytes = o_an + (size_t)T * D * 4 + 256;
@@ -965,7 +1008,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     return fail(c, PIE_ENOMEM, "pie_batch_create: %s (%zu bytes)", hipGetErrorString(e), total_bytes);
   }
   // copy only the metadata part (everything before the partial buffers)
-  e = hipMemcpyAsync(pb->dev_blob, blob.bytes.data(), blob.bytes.size(), hipMemcpyHostToDevice, c->stream);
+  e = hipMemcpyAsync(pb->dev_blob, blob.data(), blob.size, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess)  // the rotary angles of the batch's positions: the same for every layer
     e = launch_rope_table(reinterpret_cast<const int32_t*>(reinterpret_cast<unsigned char*>(pb->dev_blob) + o_pos),
                           c->inv_freq, T, D, reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(pb->dev_blob) + o_an),
