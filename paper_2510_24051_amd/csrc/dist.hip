@@ -68,37 +68,38 @@ __device__ __forceinline__ void walk_top_byte(const KeyT (&keys)[PER], uint32_t 
   *out_cnt = cnt;
 }
 
-// k-th largest of the workgroup's keys (PER per thread in registers, key 0 = padding below every real key).
-// On return: *out_kth the selected value, *out_need how many keys equal to it belong to the top set, *out_eq
-// how many keys equal it in total.  hist: 256 words, red: THREADS / 64 words of LDS.
-// `top_byte_max`: top byte of the largest key.  With stop_at_shift > 0 the search stops before the passes below
-// that shift when every key sharing the bits decided so far is needed anyway (then the low bits of *out_kth
-// are 0 and it is a lower bound of exactly the selected set).
+// The lower bytes of the need-th largest among the keys whose top byte is b (eq of them), eight bits per pass with
+// an LDS histogram; keys with another top byte take no part.  On return: *out_kth the selected value, *out_need
+// how many keys equal to it belong to the top set, *out_eq how many keys equal it in total.  With
+// stop_at_shift > 0 the search stops before the passes below that shift when every key sharing the bits decided
+// so far is needed anyway (then the low bits of *out_kth are 0 and it is a lower bound of exactly the selected
+// set).  hist: 2 x 256 words (the passes alternate between the halves: while the first wave scans one, other
+// threads clear the other, so a pass costs two barriers), red: THREADS / 64 words of LDS.
 template <typename KeyT, int PER, int THREADS>
-__device__ __forceinline__ void select_kth(const KeyT (&keys)[PER], uint32_t need, int top_byte_max, int stop_at_shift,
-                                           uint32_t* hist, uint32_t* red, KeyT* sh_prefix, uint32_t* sh_need,
-                                           uint32_t* sh_eq, KeyT* out_kth, uint32_t* out_need, uint32_t* out_eq) {
+__device__ __forceinline__ void select_lower_bytes(const KeyT (&keys)[PER], int b, uint32_t need, uint32_t eq,
+                                                   int stop_at_shift, uint32_t* hist, KeyT* sh_prefix,
+                                                   uint32_t* sh_need, uint32_t* sh_eq, KeyT* out_kth,
+                                                   uint32_t* out_need, uint32_t* out_eq) {
+  static_assert(THREADS >= 512, "threads 256..511 clear the idle histogram");
   constexpr int TOP = sizeof(KeyT) * 8 - 8;
   const int tid = threadIdx.x, lane = tid & 63;
-  int b;
-  uint32_t cnt;
-  walk_top_byte<KeyT, PER, THREADS>(keys, need, top_byte_max, red, &b, &need, &cnt);
   KeyT prefix = (KeyT)b << TOP;
-  uint32_t eq = cnt;  // keys matching the decided bits
-  for (int shift = TOP - 8; shift >= 0; shift -= 8) {
+  __syncthreads();  // earlier users of hist and of the shared results are done
+  if (tid < 512) hist[tid] = 0u;
+  __syncthreads();
+  int pass = 0;
+  for (int shift = TOP - 8; shift >= 0; shift -= 8, ++pass) {
     if (stop_at_shift > 0 && shift < stop_at_shift && eq == need) break;
-    __syncthreads();
-    if (tid < 256) hist[tid] = 0u;
-    __syncthreads();
+    uint32_t* h = hist + (pass & 1) * 256;
     const KeyT hi_mask = ~(KeyT)0 << (shift + 8);
 #pragma unroll
     for (int i = 0; i < PER; ++i)
-      if ((keys[i] & hi_mask) == prefix && keys[i] != 0) atomicAdd(&hist[(uint32_t)(keys[i] >> shift) & 0xFFu], 1u);
+      if ((keys[i] & hi_mask) == prefix && keys[i] != 0) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & 0xFFu], 1u);
     __syncthreads();
     if (tid < 64) {
       // lane L owns bins 255-4L .. 252-4L (descending); a wave scan gives the number of keys in higher bins
       const int b0 = 255 - 4 * lane;
-      const uint32_t h0 = hist[b0], h1 = hist[b0 - 1], h2 = hist[b0 - 2], h3 = hist[b0 - 3];
+      const uint32_t h0 = h[b0], h1 = h[b0 - 1], h2 = h[b0 - 2], h3 = h[b0 - 3];
       const uint32_t tot = h0 + h1 + h2 + h3;
       uint32_t incl = tot;
 #pragma unroll
@@ -117,6 +118,8 @@ __device__ __forceinline__ void select_kth(const KeyT (&keys)[PER], uint32_t nee
         *sh_eq = hb;
         *sh_prefix = prefix | ((KeyT)bb << shift);
       }
+    } else if (tid >= 256 && tid < 512) {
+      hist[((pass + 1) & 1) * 256 + (tid - 256)] = 0u;  // scanned a pass ago; the next pass counts into it
     }
     __syncthreads();
     need = *sh_need;
@@ -128,12 +131,26 @@ __device__ __forceinline__ void select_kth(const KeyT (&keys)[PER], uint32_t nee
   *out_eq = eq;
 }
 
+// k-th largest of the workgroup's keys (PER per thread in registers, key 0 = padding below every real key):
+// the top byte by walking down from `top_byte_max` (the top byte of the largest key), the rest by
+// select_lower_bytes.
+template <typename KeyT, int PER, int THREADS>
+__device__ __forceinline__ void select_kth(const KeyT (&keys)[PER], uint32_t need, int top_byte_max, int stop_at_shift,
+                                           uint32_t* hist, uint32_t* red, KeyT* sh_prefix, uint32_t* sh_need,
+                                           uint32_t* sh_eq, KeyT* out_kth, uint32_t* out_need, uint32_t* out_eq) {
+  int b;
+  uint32_t cnt;
+  walk_top_byte<KeyT, PER, THREADS>(keys, need, top_byte_max, red, &b, &need, &cnt);
+  select_lower_bytes<KeyT, PER, THREADS>(keys, b, need, cnt, stop_at_shift, hist, sh_prefix, sh_need, sh_eq, out_kth,
+                                         out_need, out_eq);
+}
+
 template <int TC_PER>
 __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __restrict__ logits, int V, int chunk_len,
                                                                 int k, float inv_temp,
                                                                 unsigned long long* __restrict__ cand,
                                                                 float* __restrict__ stats) {
-  __shared__ uint32_t hist[256];
+  __shared__ uint32_t hist[512];
   __shared__ uint32_t red[TC_THREADS / 64];
   __shared__ float fred[TC_THREADS / 64];
   __shared__ uint32_t sh_prefix, sh_need, sh_eq, sh_count, sh_count_eq, sh_wave_off[TC_THREADS / 64 + 1];
@@ -233,8 +250,9 @@ __global__ __launch_bounds__(TC_THREADS) void topk_chunk_kernel(const float* __r
     }
     unsigned long long kth64;
     uint32_t need64, eq64;
-    select_kth<unsigned long long, TC_LIST / TC_THREADS, TC_THREADS>(c, (uint32_t)kc, top_byte, 32, hist, red, &sh_prefix64,
-                                                                     &sh_need, &sh_eq, &kth64, &need64, &eq64);
+    // the walk above already found the top byte and what is still needed among the composites that carry it
+    select_lower_bytes<unsigned long long, TC_LIST / TC_THREADS, TC_THREADS>(c, wb, w_need, w_cnt, 32, hist, &sh_prefix64,
+                                                                             &sh_need, &sh_eq, &kth64, &need64, &eq64);
     // exactly kc composites are >= kth64
 #pragma unroll
     for (int j = 0; j < TC_LIST / TC_THREADS; ++j)
@@ -305,7 +323,7 @@ __global__ __launch_bounds__(TM_THREADS) void topk_merge_kernel(int n_chunks, in
                                                                 float* __restrict__ out_probs) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   unsigned long long* top = reinterpret_cast<unsigned long long*>(smem_raw);  // [n2 >= k]
-  __shared__ uint32_t hist[256];
+  __shared__ uint32_t hist[512];
   __shared__ uint32_t red[TM_THREADS / 64];
   __shared__ unsigned long long sh_prefix;
   __shared__ uint32_t sh_need, sh_eq, sh_count;
