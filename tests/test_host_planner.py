@@ -179,6 +179,15 @@ def test_prefill_launch_covers_every_block_once_and_keeps_a_head_on_one_xcd(n_kv
             seq = [(int(r), int(h)) for r, q, h in work[x::8] if r >= 0]
             changes = sum(1 for a, c in zip(seq, seq[1:]) if a != c)
             assert changes == len(set(seq)) - 1
+    # the accessor copies at most `cap` entries and always reports the total; bad arguments are refused
+    import ctypes as C
+    n = C.c_int32(0)
+    part = np.full((5, 3), -7, dtype=np.int32)
+    assert ctx.lib.pie_batch_prefill_work(pb.handle, part.ctypes.data_as(C.c_void_p), 5, C.byref(n)) == 0
+    assert n.value == work.shape[0] and (part == work[:5]).all()
+    assert ctx.lib.pie_batch_prefill_work(pb.handle, None, 3, C.byref(n)) == -1
+    assert ctx.lib.pie_batch_prefill_work(pb.handle, part.ctypes.data_as(C.c_void_p), 5, None) == -1
+    assert ctx.lib.pie_batch_prefill_work(None, part.ctypes.data_as(C.c_void_p), 5, C.byref(n)) == -1
     pb.destroy()
     ctx.close()
 
