@@ -254,14 +254,18 @@ pie_status pie_batch_work(const pie_batch* batch, int64_t* out);
  * one (column group, kv head) inside a wave's share; one partial row set each), out[2] = page pairs a wave's share
  * holds at most, out[3] = workgroup rows of the prefill kernel ((request, 32-token query block) items), out[4] =
  * requests on the decode path, out[5] = query columns per segment the partial buffers are sized for (at most 16;
- * more than one request's rows when requests that share pages are walked together).
- * Host int64[6]. */
+ * more than one request's rows when requests that share pages are walked together), out[6] and out[7] = workgroups
+ * of the first and the second prefill launch (see pie_batch_prefill_work).
+ * Host int64[8]. */
 pie_status pie_batch_plan_info(const pie_batch* batch, int64_t* out);
 
-/* The prefill attention launch of a batch, as the planner laid it out: one entry per workgroup in launch order,
- * three values each (request, 32-token query block, kv head); request -1 marks an empty slot.  Workgroup i runs
- * on XCD i % 8 (the hardware's round-robin), and the planner puts all query blocks of one (request, kv head) on
- * one XCD (System Architecture, Inference layer: how a batch of API calls is executed is the handler's business;
+/* The prefill attention launches of a batch, as the planner laid them out: one entry per workgroup in launch order,
+ * three values each (request, 32-token query block, kv head); request -1 marks an empty slot.  There are two
+ * launches, listed one after the other (their sizes: pie_batch_plan_info out[6], out[7], both multiples of 8): the
+ * second holds the query blocks whose rows may see only a few keys (requests with a bitmap; blocks of causal
+ * requests that start within the first 64 keys) and runs with the softmax weights held as bf16 pairs.  Workgroup i
+ * of a launch runs on XCD i % 8 (the hardware's round-robin), and within a launch the planner puts all query blocks
+ * of one (request, kv head) on one XCD (System Architecture, Inference layer: how a batch of API calls is executed is the handler's business;
  * this is its layout on this chip, exposed for the
  * host-logic tests).  Copies at most cap entries into out (host int32[cap * 3]) and stores the total number of
  * entries in *n_entries.  Works on planner contexts. */

@@ -123,13 +123,15 @@ class PieBatch:
                 "visited_pages": int(out[3]), "kv_bytes_unique": int(out[4]), "kv_bytes_requested": int(out[5])}
 
     def plan_info(self) -> dict:
-        out = np.zeros(6, dtype=np.int64)
+        out = np.zeros(8, dtype=np.int64)
         self.owner._check(self.owner.lib.pie_batch_plan_info(self.handle, _ptr(out)))
         return {"decode_waves": int(out[0]), "segments": int(out[1]), "max_pairs_per_wave": int(out[2]),
-                "prefill_items": int(out[3]), "decode_requests": int(out[4]), "rows_cap": int(out[5])}
+                "prefill_items": int(out[3]), "decode_requests": int(out[4]), "rows_cap": int(out[5]),
+                "prefill_workgroups": int(out[6]), "prefill_workgroups_pair_weights": int(out[7])}
 
     def prefill_work(self) -> np.ndarray:
-        """[n, 3] int32 (request, query block, kv head) per workgroup of the prefill launch; request -1 = empty."""
+        """[n, 3] int32 (request, query block, kv head) per workgroup of the two prefill launches, one after the
+        other (sizes in plan_info); request -1 = empty."""
         n = C.c_int32(0)
         self.owner._check(self.owner.lib.pie_batch_prefill_work(self.handle, None, 0, C.byref(n)))
         out = np.zeros((max(n.value, 1), 3), dtype=np.int32)

@@ -95,20 +95,22 @@ __device__ __forceinline__ void attn_step(AttnState<D>& st, const bf16x8 (&kf)[D
       for (int v = 0; v < 16; ++v) st.o[b][v] *= alpha;
     st.m = m_new;
   }
-  float lsum = 0.f;
-  Pack16 pa, pb;
+  Pack16 pa, pb, la, lb;  // every weight as a bf16 pair hi + lo (see attn_softmax)
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], scale_log2, -m_safe));  // masked keys: exp2(-inf) = 0
-    lsum += p;
-    if (v < 8) pa.h[v] = f32_to_bf16(p);
-    else pb.h[v - 8] = f32_to_bf16(p);
+    const bf16_t hi = f32_to_bf16(p);
+    const bf16_t lo = f32_to_bf16(p - bf16_to_f32(hi));
+    if (v < 8) { pa.h[v] = hi; la.h[v] = lo; }
+    else { pb.h[v - 8] = hi; lb.h[v - 8] = lo; }
   }
-  st.l += lsum;
+  st.l = sum_bf16x8(lb.h, sum_bf16x8(la.h, sum_bf16x8(pb.h, sum_bf16x8(pa.h, st.l))));
 #pragma unroll
   for (int b = 0; b < D / 32; ++b) {
     st.o[b] = mfma32(va[b], pa.h, st.o[b]);
     st.o[b] = mfma32(vb[b], pb.h, st.o[b]);
+    st.o[b] = mfma32(va[b], la.h, st.o[b]);
+    st.o[b] = mfma32(vb[b], lb.h, st.o[b]);
   }
 }
 
@@ -126,9 +128,16 @@ __device__ __forceinline__ f32x16 attn_qk(const bf16x8 (&kf)[D / 16], const bf16
   return s;
 }
 
-template <int D>
+// LO: the softmax weights enter the PV product as bf16 pairs hi + lo (lo = the rounding error of hi, itself rounded
+// to bf16), i.e. with 16 significand bits instead of 8, at the price of a second PV product.  A bf16 weight is off
+// by up to 2^-9 relative; over hundreds of visible keys that averages out far below the rounding step of the bf16
+// attention output, but a row that sees a handful of keys has outputs of order one and the weights' rounding
+// flips the output's last bit for one element in six, which the output projection then sums over all heads.  The
+// callers use LO where rows can see few keys (bitmap masks; causal blocks within the first 64 keys).
+template <int D, bool LO = false>
 __device__ __forceinline__ void attn_softmax(AttnState<D>& st, f32x16 s, uint32_t bits_a, uint32_t bits_b,
-                                             float scale_log2, bf16x8& pa_out, bf16x8& pb_out) {
+                                             float scale_log2, bf16x8& pa_out, bf16x8& pb_out, bf16x8* la_out = nullptr,
+                                             bf16x8* lb_out = nullptr) {
   const uint32_t bits = bits_a | (bits_b << 8);
   if (__builtin_amdgcn_ballot_w64(bits != 0xFFFFu) != 0ull) {
 #pragma unroll
@@ -155,18 +164,27 @@ __device__ __forceinline__ void attn_softmax(AttnState<D>& st, f32x16 s, uint32_
     st.m = m_new;
   }
   const float m_safe = (st.m == -INFINITY) ? 0.f : st.m;
-  float lsum = 0.f;
-  Pack16 pa, pb;
+  Pack16 pa, pb, la, lb;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], scale_log2, -m_safe));
-    lsum += p;
-    if (v < 8) pa.h[v] = f32_to_bf16(p);
-    else pb.h[v - 8] = f32_to_bf16(p);
+    const bf16_t hi = f32_to_bf16(p);
+    if (v < 8) pa.h[v] = hi;
+    else pb.h[v - 8] = hi;
+    if (LO) {
+      const bf16_t lo = f32_to_bf16(p - bf16_to_f32(hi));
+      if (v < 8) la.h[v] = lo;
+      else lb.h[v - 8] = lo;
+    }
   }
-  st.l += lsum;
+  st.l = sum_bf16x8(pb.h, sum_bf16x8(pa.h, st.l));  // the normaliser of the weights as rounded for the PV product
   pa_out = pa.h;
   pb_out = pb.h;
+  if (LO) {
+    st.l = sum_bf16x8(lb.h, sum_bf16x8(la.h, st.l));
+    *la_out = la.h;
+    *lb_out = lb.h;
+  }
 }
 
 template <int D>
@@ -402,15 +420,16 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
     const float m_new = fmaxf(st_m, mx);
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(st_m - m_safe);
-    float lsum = 0.f;
-    Pack16 pp;
+    // The weights enter the PV product as bf16 pairs hi + lo (see attn_softmax): decode rows under sparse masks or
+    // with short contexts see few keys, and the matrix cores are idle most of the time in this kernel anyway.
+    Pack16 pp, pl;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float p = __builtin_amdgcn_exp2f(sv[e] - m_safe);
-      lsum += p;
       pp.h[e] = f32_to_bf16(p);
+      pl.h[e] = f32_to_bf16(p - bf16_to_f32(pp.h[e]));
     }
-    st_l = st_l * alpha + lsum;
+    st_l = sum_bf16x8(pl.h, sum_bf16x8(pp.h, st_l * alpha));  // the normaliser of the weights as the PV product sees them
     st_m = m_new;
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
@@ -420,6 +439,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
 #pragma unroll
       for (int e = 0; e < 4; ++e) o[b][e] *= alpha;
       o[b] = mfma16(vv, pp.h, o[b]);
+      o[b] = mfma16(vv, pl.h, o[b]);
     }
   };
   if (n_pairs <= 0) return;
@@ -522,7 +542,8 @@ __device__ __forceinline__ void lds_copy_run(const char* src, char* dst) {
 // 16-byte load per pair, one pair ahead; mask words are fetched with the copy, three steps ahead of their use.
 // Workgroups are listed per XCD by the host (all query blocks of a (request, kv head) on one XCD, whose L2 then
 // serves the re-reads of its K/V); the lists are padded with empty items.
-template <int D, int G>
+// LO: the softmax weights as bf16 pairs (see attn_softmax); the host lists the items that need it separately.
+template <int D, int G, bool LO>
 __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
   constexpr int BLK = 2 * PAGE * D;            // elements of one (page, head) block: K part then V part
   constexpr int PIECES = BLK * 2 / 1024;       // 1 KiB copy instructions per page block
@@ -633,9 +654,10 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
         vb[bb] = *reinterpret_cast<const bf16x8*>(stage + BLK + voff + bb * 512);
       }
       __builtin_amdgcn_sched_barrier(0);
-      bf16x8 pa, pb;
-      attn_softmax<D>(st, sc, bits_a, bits_b, a.scale_log2, pa, pb);
+      bf16x8 pa, pb, la, lb;
+      attn_softmax<D, LO>(st, sc, bits_a, bits_b, a.scale_log2, pa, pb, &la, &lb);
       attn_pv<D>(st, va, vb, pa, pb);
+      if (LO) attn_pv<D>(st, va, vb, la, lb);
     };
 #define PIE_WAIT_VM(n) PIE_S_WAIT_VMCNT(n)
     // Step i: the scores of pair i+1 are issued to the matrix cores first, so they run under the softmax
@@ -774,21 +796,24 @@ hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_d
   return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool LO>
 static hipError_t launch_prefill_d(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
   dim3 grid(n_items), block(64 * G);
-  if (G == 1) attn_prefill_kernel<D, 1><<<grid, block, 0, s>>>(a, items);
-  else if (G == 2) attn_prefill_kernel<D, 2><<<grid, block, 0, s>>>(a, items);
-  else if (G == 4) attn_prefill_kernel<D, 4><<<grid, block, 0, s>>>(a, items);
-  else if (G == 8) attn_prefill_kernel<D, 8><<<grid, block, 0, s>>>(a, items);
+  if (G == 1) attn_prefill_kernel<D, 1, LO><<<grid, block, 0, s>>>(a, items);
+  else if (G == 2) attn_prefill_kernel<D, 2, LO><<<grid, block, 0, s>>>(a, items);
+  else if (G == 4) attn_prefill_kernel<D, 4, LO><<<grid, block, 0, s>>>(a, items);
+  else if (G == 8) attn_prefill_kernel<D, 8, LO><<<grid, block, 0, s>>>(a, items);
   else attn_prefill_direct_kernel<D><<<grid, block, 0, s>>>(a, items);  // other group sizes: no LDS sharing
   return hipGetLastError();
 }
 
-hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s) {
+hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, bool pair_weights,
+                               hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
-  if (a.D == 128) return launch_prefill_d<128>(a, items, n_items, s);
-  if (a.D == 64) return launch_prefill_d<64>(a, items, n_items, s);
+  if (a.D == 128)
+    return pair_weights ? launch_prefill_d<128, true>(a, items, n_items, s) : launch_prefill_d<128, false>(a, items, n_items, s);
+  if (a.D == 64)
+    return pair_weights ? launch_prefill_d<64, true>(a, items, n_items, s) : launch_prefill_d<64, false>(a, items, n_items, s);
   return hipErrorInvalidValue;
 }

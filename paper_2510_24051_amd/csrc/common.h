@@ -73,6 +73,22 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Sum of the eight bf16 values of a packed MFMA operand added to `acc` in fp32 (v_dot2c_f32_bf16 against a pair of
+// ones: two values per instruction, the products by 1 are exact).  The softmax normaliser is summed from the
+// rounded weights that the PV product multiplies by, so the weights applied and their sum carry the same rounding:
+// a row with one visible key returns that key's V row exactly, and with a handful of keys the rounding of the
+// weights largely cancels in the final division instead of showing as a 2^-9 relative error of the output.
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float sum_bf16x8(bf16x8 p, float acc) {
+  const bf16x2v ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bf16x2v pr = {p[2 * i], p[2 * i + 1]};
+    acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+  }
+  return acc;
+}
+
 // Tiled weight storage: W[N, K] (Linear layout) is cut into tiles of 32 output rows x 16 inputs,
 // 1 KiB each, stored [N/32][K/16]; inside a tile lane l = g * 32 + n holds W[nb*32 + n][kb*16 + g*8 .. +8].
 // One 16-byte load per lane is then exactly the B operand of mfma32.

@@ -104,7 +104,10 @@ struct pie_batch {
   int32_t* dec_reqs = nullptr;  // request indices on the decode path
   int32_t n_dsegs = 0, n_dwaves = 0, dslots = 0, n_pitems = 0, n_dec_reqs = 0, rows_cap = 0;
   std::vector<PrefillItem> pwork_host;  // host copy of the prefill launch layout (inspection)
-  int32_t n_pwork = 0;  // workgroups of the prefill launch: (query block, kv head) items laid out per XCD, padded
+  // workgroups of the two prefill launches, (query block, kv head) items laid out per XCD and padded: the first
+  // n_pwork entries of pitems run with plain bf16 softmax weights, the following n_pwork_lo (query blocks whose rows
+  // may see few keys: bitmap masks, causal blocks that start within the first 64 keys) with weights as bf16 pairs
+  int32_t n_pwork = 0, n_pwork_lo = 0;
   float* part_o = nullptr;   // [n_dsegs * rows_cap, D]
   float* part_ml = nullptr;  // [n_dsegs * rows_cap, 2]
   int64_t work[6] = {0, 0, 0, 0, 0, 0};
@@ -232,7 +235,9 @@ hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const 
 hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const int32_t* mref_indptr,
                              const int32_t* mrefs, int rows_cap, const float* part_o, const float* part_ml,
                              hipStream_t s);
-hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, hipStream_t s);
+// pair_weights: the items' softmax weights enter the PV product as bf16 pairs hi + lo (rows that may see few keys)
+hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillItem* items, int n_items, bool pair_weights,
+                               hipStream_t s);
 
 // rows / tile_ad: the batch's adapter tiles (32 rows each); z: [ksplits][n_tiles * 32, 3, rmax_p] fp32, where
 // ksplits (from lora_ksplits, the same for the down and the up launch of a projection group) splits the input

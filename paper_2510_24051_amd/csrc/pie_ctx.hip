@@ -871,6 +871,14 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     const ReqInfo& q = reqs[it.r];
     return q.wpr ? (int64_t)q.n_visit * PAGE : (int64_t)(q.kv_len - q.n_new + std::min(q.n_new, it.qb * 32 + 32));
   };
+  // Two launches: query blocks whose rows may see only a few keys (requests with a bitmap, and blocks of causal
+  // requests that start within the first 64 keys) run with their softmax weights as bf16 pairs; all others with
+  // plain bf16 weights.  Each launch gets a layout of its own.
+  auto few_keys = [&](const PrefillItem& it) {
+    const ReqInfo& q = reqs[it.r];
+    return q.wpr > 0 || q.kv_len - q.n_new + it.qb * 32 < 64;
+  };
+  auto layout = [&](std::vector<PrefillItem> pitems) {
   std::stable_sort(pitems.begin(), pitems.end(), [&](const PrefillItem& x, const PrefillItem& y) {
     return x.r != y.r ? x.r < y.r : pcost(x) > pcost(y);
   });
@@ -922,6 +930,16 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
       break;
     }
   }
+  return pwork;
+  };
+  std::vector<PrefillItem> pitems_plain, pitems_pair;
+  for (const PrefillItem& it : pitems) (few_keys(it) ? pitems_pair : pitems_plain).push_back(it);
+  std::vector<PrefillItem> pwork = layout(std::move(pitems_plain));
+  const size_t n_pwork_plain = pwork.size();
+  {
+    const std::vector<PrefillItem> lo = layout(std::move(pitems_pair));
+    pwork.insert(pwork.end(), lo.begin(), lo.end());
+  }
 
   pie_batch* pb = new pie_batch();
   pb->R = R; pb->T = T;
@@ -930,7 +948,8 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   pb->n_dwaves = (int32_t)dwaves.size();
   pb->dslots = dslots;
   pb->n_pitems = (int32_t)pitems.size();
-  pb->n_pwork = (int32_t)pwork.size();
+  pb->n_pwork = (int32_t)n_pwork_plain;
+  pb->n_pwork_lo = (int32_t)(pwork.size() - n_pwork_plain);
   pb->pwork_host = pwork;
   pb->n_dec_reqs = (int32_t)dec_reqs.size();
   pb->rows_cap = std::max(rows_cap, 1);
@@ -1061,6 +1080,8 @@ extern "C" pie_status pie_batch_plan_info(const pie_batch* b, int64_t* out) {
   out[3] = b->n_pitems;
   out[4] = b->n_dec_reqs;
   out[5] = b->rows_cap;
+  out[6] = b->n_pwork;
+  out[7] = b->n_pwork_lo;
   return PIE_OK;
 }
 
@@ -1165,7 +1186,8 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
   // which is bound by HBM reads.
   if (b->n_pitems > 0) {
     tm.begin(PIE_STAGE_ATTN_PREFILL);
-    HIP_TRY(c, launch_attn_prefill(a, b->pitems, b->n_pwork, s));
+    HIP_TRY(c, launch_attn_prefill(a, b->pitems, b->n_pwork, false, s));
+    HIP_TRY(c, launch_attn_prefill(a, b->pitems + b->n_pwork, b->n_pwork_lo, true, s));
     tm.end(PIE_STAGE_ATTN_PREFILL);
   }
   if (b->n_dec_reqs > 0) {

@@ -9,7 +9,8 @@ import pytest
 
 import workloads as W
 from oracle import pie_oracle as O
-from gpu_helpers import (appended_positions, assert_bf16_close, assert_close, dec, gpu_forward, make_ctx, seed_ctx)
+from gpu_helpers import (appended_positions, assert_bf16_close, assert_close, assert_y_close, dec, gpu_forward, make_ctx,
+                         seed_ctx)
 from helpers import check_topk, oracle_pools, run_oracle
 
 pytestmark = pytest.mark.gpu
@@ -34,10 +35,10 @@ def compare_layer(w, ctx=None, mode_b_only=False, check_taps=True, what=""):
     pb, stored, y_bits = gpu_forward(ctx, w)
     T = w.batch.n_tokens
     res_b, kv_b, _ = run_oracle(w, round_intermediates=True)
-    assert_close(dec(y_bits), res_b.y[stored], f"{what} y vs oracle (bf16 intermediates)")
+    assert_y_close(dec(y_bits), res_b.y[stored], f"{what} y vs oracle (bf16 intermediates)")
     if not mode_b_only:
         res_a, _, _ = run_oracle(w)
-        assert_close(dec(y_bits), res_a.y[stored], f"{what} y vs oracle (wide intermediates)")
+        assert_y_close(dec(y_bits), res_a.y[stored], f"{what} y vs oracle (wide intermediates)", stored_as=res_b.y[stored])
     if check_taps:
         from paper_2510_24051_amd import TAP_ACT, TAP_ATTN, TAP_Q, TAP_RESID
         m = w.model

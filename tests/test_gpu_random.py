@@ -46,7 +46,11 @@ def draw_case(seed):
     return m, reqs, pages + 8
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16, 17, 18, 19, 20])
+# 124, 159, 289 and 314 are the draws of a 210-seed sweep that once fell outside the limits: 124 has outputs with
+# |y| >= 8 (the format's half-ulp there is 0.031), 289 a 2%-dense bitmap (a handful of visible keys per row: the
+# softmax weights' bf16 rounding showed until their normaliser was summed from the rounded weights), 159 and 314
+# exceeded the mean limit against the wide-intermediate oracle.
+@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 124, 159, 289, 314])
 def test_random_small_configurations(seed):
     m, reqs, n_pages = draw_case(seed)
     std = 0.05 * np.sqrt(128.0 / m.hidden)  # the same output scale at every width (the tolerance is absolute)

@@ -137,9 +137,11 @@ def prefill_mix(n_kv=8, sizes=((1024, 0), (1024, 1500), (512, 100), (300, 2040),
 
 @pytest.mark.parametrize("n_kv", [8, 2, 1])
 def test_prefill_launch_covers_every_block_once_and_keeps_a_head_on_one_xcd(n_kv):
-    """The prefill launch lists one workgroup per (request, 32-token query block, kv head): each exactly once,
-    empty slots only as padding, workgroup i on XCD i % 8; the query blocks of one (request, kv head) share an
-    XCD unless the planner had to cut groups to even out the XCDs; the XCDs' loads are even."""
+    """The two prefill launches together list one workgroup per (request, 32-token query block, kv head): each
+    exactly once, empty slots only as padding, workgroup i of a launch on XCD i % 8; the second launch holds exactly
+    the blocks whose rows may see few keys (here: causal blocks that start within the first 64 keys); within a launch
+    the query blocks of one (request, kv head) share an XCD unless the planner had to cut groups to even out the
+    XCDs; the XCDs' loads are even."""
     w = prefill_mix(n_kv)
     b, m = w.batch, w.model
     ctx = planner_for(w)
@@ -157,10 +159,16 @@ def test_prefill_launch_covers_every_block_once_and_keeps_a_head_on_one_xcd(n_kv
                 expected.add((r, qb, hk))
                 cost[(r, qb, hk)] = int(b.kv_len[r]) - n_new + min(n_new, qb * 32 + 32)
     assert pb.plan_info()["prefill_items"] * m.n_kv_heads == len(expected)
-    assert work.shape[0] % 8 == 0
+    info = pb.plan_info()
+    n_plain, n_pair = info["prefill_workgroups"], info["prefill_workgroups_pair_weights"]
+    assert work.shape[0] == n_plain + n_pair and n_plain % 8 == 0 and n_pair % 8 == 0
     real = [tuple(int(x) for x in row) for row in work if row[0] >= 0]
     assert len(real) == len(set(real)) == len(expected) and set(real) == expected
     assert all(row[1] == 0 and row[2] == 0 for row in work if row[0] < 0)
+    few = lambda r, qb: int(b.kv_len[r]) - int(b.tok_indptr[r + 1] - b.tok_indptr[r]) + qb * 32 < 64
+    assert {k for k in map(tuple, work[n_plain:].tolist()) if k[0] >= 0} == {k for k in expected if few(k[0], k[1])}
+    assert n_pair > 0
+    work_all, work = work, work[:n_plain]  # the layout properties below are those of one launch: the large one
     xcd_of, load = {}, np.zeros(8)
     for i, row in enumerate(work):
         if row[0] >= 0:
@@ -184,7 +192,7 @@ def test_prefill_launch_covers_every_block_once_and_keeps_a_head_on_one_xcd(n_kv
     n = C.c_int32(0)
     part = np.full((5, 3), -7, dtype=np.int32)
     assert ctx.lib.pie_batch_prefill_work(pb.handle, part.ctypes.data_as(C.c_void_p), 5, C.byref(n)) == 0
-    assert n.value == work.shape[0] and (part == work[:5]).all()
+    assert n.value == work_all.shape[0] and (part == work_all[:5]).all()
     assert ctx.lib.pie_batch_prefill_work(pb.handle, None, 3, C.byref(n)) == -1
     assert ctx.lib.pie_batch_prefill_work(pb.handle, part.ctypes.data_as(C.c_void_p), 5, None) == -1
     assert ctx.lib.pie_batch_prefill_work(None, part.ctypes.data_as(C.c_void_p), 5, C.byref(n)) == -1

@@ -32,14 +32,18 @@ def dec(bits):
 
 
 # ---------------------------------------------------------------- whole layer against torch CPU
-def torch_llama_layer(model, w, x, pos):
-    """Textbook pre-norm Llama layer for ONE contiguous causal sequence, written with torch library ops."""
+def torch_llama_layer(model, w, x, pos, act_bf16=False, taps=None):
+    """Textbook pre-norm Llama layer for ONE contiguous causal sequence, written with torch library ops.
+    `act_bf16`: cast to torch.bfloat16 (and back) exactly where the paper's stated activation precision puts a
+    bf16 tensor between two contractions: the normalised input, q/k/v as projected, q after the rotary step, the
+    attention output, the second norm's output and the SwiGLU product; the residual stream stays wide."""
     H, Hq, Hkv, D = model.hidden, model.n_q_heads, model.n_kv_heads, model.head_dim
     t = lambda b: torch.from_numpy(dec(b))
-    xn = F.rms_norm(x, (H,), t(w.g1), eps=model.rms_eps)
-    q = F.linear(xn, t(w.wq)).view(-1, Hq, D)
-    k = F.linear(xn, t(w.wk)).view(-1, Hkv, D)
-    v = F.linear(xn, t(w.wv)).view(-1, Hkv, D)
+    r = (lambda a: a.to(torch.bfloat16).to(torch.float64)) if act_bf16 else (lambda a: a)
+    xn = r(F.rms_norm(x, (H,), t(w.g1), eps=model.rms_eps))
+    q = r(F.linear(xn, t(w.wq))).view(-1, Hq, D)
+    k = r(F.linear(xn, t(w.wk))).view(-1, Hkv, D)
+    v = r(F.linear(xn, t(w.wv))).view(-1, Hkv, D)
 
     def rot(a):  # complex formulation of the rotary step
         z = torch.complex(a[..., : D // 2], a[..., D // 2:])
@@ -48,16 +52,19 @@ def torch_llama_layer(model, w, x, pos):
         z = z * ph
         return torch.cat([z.real, z.imag], dim=-1)
 
-    q, k = rot(q), rot(k)
+    q, k = r(rot(q)), rot(k)
     k = k.to(torch.bfloat16).to(torch.float64)  # KvPages are bf16 storage
     v = v.to(torch.float32).to(torch.bfloat16).to(torch.float64)
     g = Hq // Hkv
     o = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2).repeat_interleave(g, 0)[None],
                                        v.permute(1, 0, 2).repeat_interleave(g, 0)[None], is_causal=True)
-    o = o[0].permute(1, 0, 2).reshape(-1, Hq * D)
+    o = r(o[0].permute(1, 0, 2).reshape(-1, Hq * D))
     h = x + F.linear(o, t(w.wo))
-    hn = F.rms_norm(h, (H,), t(w.g2), eps=model.rms_eps)
-    return h + F.linear(F.silu(F.linear(hn, t(w.wgate))) * F.linear(hn, t(w.wup)), t(w.wdown))
+    hn = r(F.rms_norm(h, (H,), t(w.g2), eps=model.rms_eps))
+    act = r(F.silu(F.linear(hn, t(w.wgate))) * F.linear(hn, t(w.wup)))
+    if taps is not None:
+        taps.update(q=q, o=o, h=h, act=act)
+    return h + F.linear(act, t(w.wdown))
 
 
 def test_layer_matches_torch_textbook_layer():
@@ -286,6 +293,42 @@ def test_in_place_embed_is_read_before_written():
     res2, _, emb2 = run_oracle(wl2)
     assert np.array_equal(res.y, res2.y)
     assert np.array_equal(emb.read(wl.batch.out_embed_ids), emb2.read([90, 91, 92]))
+
+
+def test_round_intermediates_mode_matches_torch_layer_with_bf16_casts():
+    """The oracle's bf16-intermediate mode (the primary comparator of the GPU parity tests) against an independent
+    torch expression that casts `.to(torch.bfloat16)` at exactly the points where the oracle rounds.  A rounding
+    point that is missing, misplaced or added (e.g. a rounded residual stream) moves most elements of y by a bf16
+    ulp of some intermediate, far above the limits here; torch's float64 -> float32 -> bf16 cast may double-round
+    one value in ~2**29, which at most shows as an isolated element."""
+    m = small_model(hidden=128, mlp_dim=192)
+    wl = W.build_workload("one_b", m, [W.RequestSpec(37, 0)], n_kv_pages=8, seed=5, std=0.2)
+    res, kv, _ = run_oracle(wl, round_intermediates=True)
+    x = torch.from_numpy(dec(wl.embed_bits))
+    pos = torch.from_numpy(wl.batch.positions.astype(np.float64))
+    taps = {}
+    ref = torch_llama_layer(m, wl.weights, x, pos, act_bf16=True, taps=taps).numpy()
+    for name, got, want in (("q", res.q, taps["q"].numpy()), ("o", res.o.reshape(37, -1), taps["o"].numpy()),
+                            ("h", res.h, taps["h"].numpy()), ("act", res.act, taps["act"].numpy()), ("y", res.y, ref)):
+        d = np.abs(got.reshape(want.shape) - want)
+        assert np.mean(d > 1e-9) < 1e-3 and d.mean() < 1e-6, (name, float(d.max()), float(d.mean()))
+    # the planted alternatives are all far away: wide mode, and a torch layer that also rounds the residual stream
+    wide, _, _ = run_oracle(wl)
+    assert np.abs(wide.y - ref).mean() > 1e-4
+    h_rounded = taps["h"].to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.abs(h_rounded - res.h).mean() > 1e-4  # the oracle's residual stream is not rounded
+    # the head: the normalised Embed is rounded to bf16 before the LM head, the logits stay wide
+    wl2 = W.c1_tiny()
+    _, _, emb = run_oracle(wl2, round_intermediates=True)
+    ids_e = wl2.batch.out_embed_ids[wl2.dist_rows]
+    z = O.logits_from_embeds(wl2.model, wl2.head, emb, ids_e, round_intermediates=True)
+    e = torch.from_numpy(dec(emb.read(ids_e)))
+    en = F.rms_norm(e, (wl2.model.hidden,), torch.from_numpy(dec(wl2.head.g_final)), eps=wl2.model.rms_eps)
+    zz = F.linear(en.to(torch.bfloat16).to(torch.float64), torch.from_numpy(dec(wl2.head.w_lm))).numpy()
+    dz = np.abs(z - zz)
+    assert np.mean(dz > 1e-9) < 1e-3 and dz.mean() < 1e-6
+    z_wide = O.logits_from_embeds(wl2.model, wl2.head, emb, ids_e)
+    assert np.abs(z_wide - zz).mean() > 1e-5
 
 
 def test_round_intermediates_mode_is_close_to_wide_mode():
