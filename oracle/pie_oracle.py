@@ -230,7 +230,8 @@ def _lora_delta(adapter, name: str, x: np.ndarray) -> np.ndarray:
 
 def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional[Sequence[int]] = None,
             round_intermediates: bool = False, write_embeds: bool = True,
-            x_in: Optional[np.ndarray] = None, adapters=None, adapter_ids=None) -> ForwardResult:
+            x_in: Optional[np.ndarray] = None, adapters=None, adapter_ids=None,
+            attention_only: bool = False) -> ForwardResult:
     """One decoder layer over a batch of `forward` commands (Forward API; Table 1 `forward`).
 
     `model`   : hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, page_size, rms_eps, rope_theta
@@ -245,6 +246,8 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
                 the layers after the first, whose input is the previous layer's output).
     `batch.positions` may be None: the positions are then those recorded with the input Embeds by
     `embed_txt` (Forward API: the call works on the sequence positions associated with its resources).
+    `attention_only`: stop after the attention step (y, h and act of the result are None, no Embed is written);
+                for tests that compare the attention output of many rows without paying for their MLP.
     `adapters`, `adapter_ids`: `forward_with_adapter` (Forward API): request r uses the LoRA adapter
                 `adapters[adapter_ids[r]]` (a dict projection name -> (A bits [rank, in], B bits [out, rank],
                 scale); -1 = none): every projection that has a pair computes W x + scale * B (A x).  With
@@ -348,6 +351,9 @@ def forward(model, weights, kv: KvPool, emb: EmbedPool, batch, *, rows: Optional
         o = masked_attention(q, kk, vv, allowed)
         q_out[sel] = q
         o_out[sel] = _maybe_round(o, rnd)
+
+    if attention_only:
+        return ForwardResult(rows=rows, y=None, q=q_out, o=o_out, h=None, k_new=k_new, v_new=v_new, act=None)
 
     # 7-8: output projection + residual, second norm, SwiGLU MLP + residual
     Wo = bf16_decode(weights.wo)

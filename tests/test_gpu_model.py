@@ -214,6 +214,15 @@ def test_forward_dist_equals_forward_then_get_next_dist():
     ctx.embed_txt(dw.token_ids, b.positions, b.in_embed_ids)
     pb = ctx.batch_create(clone_batch(b, positions=None))
     ids1, p1 = ctx.forward_dist(pb, rows, w.top_k, 0.7)
+    # against the oracle: the layer stack's output Embeds, then the distribution of the stored Embed bits
+    res, _, _ = oracle_deep(dw)
+    stored = np.nonzero(b.out_embed_ids >= 0)[0]
+    assert_close(dec(ctx.embed_read(b.out_embed_ids[stored])), res[-1].y[stored], "forward_dist output Embeds")
+    ids_e = b.out_embed_ids[rows]
+    probe = O.EmbedPool(w.n_embeds, w.model.hidden)
+    probe.write(ids_e, ctx.embed_read(ids_e))
+    oi, op, z = O.get_next_dist(w.model, w.head, probe, ids_e, w.top_k, 0.7, round_intermediates=True)
+    check_topk(ids1, p1, z / 0.7, oi, op)
     ctx2 = make_deep_ctx(dw)
     ctx2.embed_txt(dw.token_ids, b.positions, b.in_embed_ids)
     pb2 = ctx2.batch_create(clone_batch(b, positions=None))

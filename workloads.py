@@ -390,8 +390,11 @@ def model_70b(vocab: int = 128256) -> ModelDesc:
                      page_size=16, rms_eps=1e-5, rope_theta=5e5, n_layers=80)
 
 
-def _resid_std(model: ModelDesc) -> float:
-    return 0.02 / float(np.sqrt(2.0 * model.n_layers))
+def _resid_std(model: ModelDesc, literal: bool = False) -> Optional[float]:
+    """Standard deviation of the two residual-writing projections: depth-scaled (0.02 / sqrt(2 n_layers)), which
+    keeps the layer output at unit scale, or with `literal` the same N(0, 0.02) as every other weight (the layer
+    output then has a standard deviation of about 2.7 at the 8B shape and 7 at the 70B shape)."""
+    return None if literal else 0.02 / float(np.sqrt(2.0 * model.n_layers))
 
 
 def c1_tiny(seed: int = 1000, bitmap: bool = False) -> Workload:
@@ -403,44 +406,45 @@ def c1_tiny(seed: int = 1000, bitmap: bool = False) -> Workload:
 
 def c2_decode(seed: int = 2000, n_requests: int = 64, ctx_lo: int = 512, ctx_hi: int = 4096,
               n_kv_pages: int = 40000, model: Optional[ModelDesc] = None, with_head: bool = True,
-              weights=None, head=None, top_k: int = 256) -> Workload:
+              weights=None, head=None, top_k: int = 256, literal: bool = False) -> Workload:
     m = model or model_8b()
     ctx = rng_for(seed, STREAM_CTX).integers(ctx_lo, ctx_hi + 1, size=n_requests)
     reqs = [RequestSpec(1, int(c), in_place=True) for c in ctx]
-    return build_workload("c2_decode", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m), with_head=with_head,
+    return build_workload("c2_decode", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m, literal), with_head=with_head,
                           weights=weights, head=head, top_k=top_k)
 
 
 def c3_mixed(seed: int = 3000, n_prefill: int = 8, prefill_len: int = 1024, prior_hi: int = 2048,
              n_decode: int = 128, decode_ctx: int = 2048, n_kv_pages: int = 40000,
-             model: Optional[ModelDesc] = None, with_head: bool = True, weights=None, head=None) -> Workload:
+             model: Optional[ModelDesc] = None, with_head: bool = True, weights=None, head=None,
+             literal: bool = False) -> Workload:
     m = model or model_8b()
     pri = rng_for(seed, STREAM_CTX).integers(0, prior_hi + 1, size=n_prefill)
     reqs = [RequestSpec(prefill_len, int(p)) for p in pri] + \
            [RequestSpec(1, decode_ctx, in_place=True) for _ in range(n_decode)]
-    return build_workload("c3_mixed", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m), with_head=with_head,
+    return build_workload("c3_mixed", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m, literal), with_head=with_head,
                           weights=weights, head=head, top_k=32, dist_rows="decode")
 
 
 def c4_prefix_tree(seed: int = 4000, n_branches: int = 256, prefix_len: int = 4096, suffix_prior: int = 63,
                    span: int = 512, n_kv_pages: int = 2048, model: Optional[ModelDesc] = None,
-                   with_head: bool = False, weights=None, head=None) -> Workload:
+                   with_head: bool = False, weights=None, head=None, literal: bool = False) -> Workload:
     m = model or model_8b()
     hidden = set(rng_for(seed, STREAM_CTX).permutation(n_branches)[: n_branches // 4].tolist())  # exactly 25%
     reqs = [RequestSpec(1, prefix_len + suffix_prior, prefix_group=0, prefix_len=prefix_len, in_place=True,
                         mask=tree_branch_mask(span, 1.0 if b in hidden else 0.0, prefix_len))
             for b in range(n_branches)]
-    return build_workload("c4_prefix_tree", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m), with_head=with_head,
+    return build_workload("c4_prefix_tree", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m, literal), with_head=with_head,
                           weights=weights, head=head, top_k=0, dist_rows="none")
 
 
 def c5_sparse_long(seed: int = 5000, n_requests: int = 16, ctx: int = 32768, n_sink: int = 4, window: int = 4096,
                    n_kv_pages: int = 40000, model: Optional[ModelDesc] = None, with_head: bool = True,
-                   weights=None, head=None) -> Workload:
+                   weights=None, head=None, literal: bool = False) -> Workload:
     m = model or model_70b()
     mk = sink_window_mask(n_sink, window)
     reqs = [RequestSpec(1, ctx, mask=mk, in_place=True) for _ in range(n_requests)]
-    return build_workload("c5_sparse_long", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m), with_head=with_head,
+    return build_workload("c5_sparse_long", m, reqs, n_kv_pages, seed, resid_std=_resid_std(m, literal), with_head=with_head,
                           weights=weights, head=head, top_k=50)
 
 
