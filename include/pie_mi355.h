@@ -57,8 +57,9 @@ typedef struct {
   int32_t max_adapters, max_lora_rank; /* LoRA adapters (pie_load_adapter); both 0 = none */
 } pie_pool_desc;
 
-/* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (NULL = default
- * stream).  Allocates pools (zero-filled) and workspace; nothing is allocated afterwards by
+/* Create a context on the current HIP device (System Architecture, Inference layer: the handlers own the resource
+ * pools and a workspace set up once at start; API handlers: a native handler with pre-allocated buffers).
+ * `hip_stream` is a hipStream_t (NULL = default stream).  Allocates pools (zero-filled) and workspace; nothing is allocated afterwards by
  * pie_forward / pie_get_next_dist. */
 pie_status pie_create(const pie_model_desc* model, const pie_pool_desc* pool, void* hip_stream, pie_ctx** out);
 pie_status pie_destroy(pie_ctx* ctx);
@@ -184,6 +185,9 @@ typedef struct {
  * Errors: PIE_EINVAL, PIE_ERANGE, PIE_EBATCH, PIE_ECONFLICT, PIE_ENOMEM, PIE_EHIP. */
 pie_status pie_batch_create(pie_ctx* ctx, const pie_forward_batch* batch, int32_t validate, pie_batch** out);
 pie_status pie_batch_destroy(pie_ctx* ctx, pie_batch* batch);
+
+/* A batch runs only on the context that created it: the forward calls and pie_batch_destroy return PIE_EINVAL for a
+ * batch of another context, and the forward calls for a batch made by a planning context (it has no device block). */
 
 /* Run one decoder layer over the batch (Forward API: attention and transformation steps):
  * RMSNorm, QKV projection, rotary step + KV append into pages, paged masked GQA attention,

@@ -654,6 +654,17 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
 // ------------------------------------------------------------------------------------------------
 // dispatch
 // ------------------------------------------------------------------------------------------------
+// Raises a kernel's dynamic LDS limit once per process and device (done: one bit per device), not per launch.
+static hipError_t set_lds_limit_once(const void* kern, size_t bytes, uint32_t& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 32 && ((done >> dev) & 1u)) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && dev >= 0 && dev < 32) done |= 1u << dev;
+  return e;
+}
+
 template <int MB, int MODE, int NBW, int WAVES = 4>
 static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
                                size_t ws_elems, int n_cus, hipStream_t s, int* defer, int max_splits = SK_MAX_SPLITS) {
@@ -678,13 +689,15 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
   dim3 grid(wg_n, splits), block(WAVES * 64);
   if (splits == 1) {
     auto kern = gemm_skinny_kernel<MB, MODE, false, NBW, WAVES>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static uint32_t lds_set = 0;
+    hipError_t e = set_lds_limit_once((const void*)kern, smem, lds_set);
     if (e != hipSuccess) return e;
     kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, nullptr);
     return hipGetLastError();
   }
   auto kern = gemm_skinny_kernel<MB, MODE, true, NBW, WAVES>;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static uint32_t lds_set_partial = 0;
+  hipError_t e = set_lds_limit_once((const void*)kern, smem, lds_set_partial);
   if (e != hipSuccess) return e;
   kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, ws);
   e = hipGetLastError();
@@ -799,7 +812,8 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   }
   auto kern = gemm_large_kernel<MODE>;
   size_t smem = (size_t)4 * LG_BM * LG_BK * sizeof(bf16_t);
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static uint32_t lds_set_large = 0;
+  hipError_t e = set_lds_limit_once((const void*)kern, smem, lds_set_large);
   if (e != hipSuccess) return e;
   dim3 grid((W.NB + 7) / 8, (M + LG_BM - 1) / LG_BM), block(512);
   kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, epi);

@@ -79,6 +79,7 @@ struct DecodeWave { int32_t seg0, n_seg, n_pairs, pad; };  // a wave's share: se
 struct PrefillItem { int32_t r, qb, hk, pad; };  // query block qb (32 tokens) of request r for kv head hk; r < 0: empty slot
 
 struct pie_batch {
+  const pie_ctx* owner = nullptr;  // the context that deserialised the batch: its pools, ranges and wave count are baked in
   int32_t R = 0, T = 0;
   std::vector<int32_t> out_ids_host;  // host copy of the output Embed ids (pie_forward_dist)
   void* dev_blob = nullptr;  // single allocation holding every array below

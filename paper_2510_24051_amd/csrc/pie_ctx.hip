@@ -140,7 +140,9 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
     chk(dev_alloc(&c->topk_cand, (size_t)p->max_dist_rows * 16 * std::max(p->max_top_k, 1), false, c->stream));
     chk(dev_alloc(&c->topk_stats, (size_t)p->max_dist_rows * 16 * 2, false, c->stream));
   }
-  c->ids_cap = std::max<size_t>(4096, 2 * T);
+  // staging for id lists: get_next_dist stages at most max_dist_rows ids, so the serving path never outgrows it
+  // (only the seeding / inspection calls may, and they re-allocate)
+  c->ids_cap = std::max<size_t>(std::max<size_t>(4096, 2 * T), (size_t)p->max_dist_rows);
   chk(dev_alloc(&c->ids_dev, c->ids_cap, false, c->stream));
   chk(dev_alloc(&c->inv_freq, (size_t)m->head_dim / 2, false, c->stream));
   if (e == hipSuccess) {
@@ -942,6 +944,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   }
 
   pie_batch* pb = new pie_batch();
+  pb->owner = c;
   pb->R = R; pb->T = T;
   pb->out_ids_host.assign(b->out_embed_ids, b->out_embed_ids + T);
   pb->n_dsegs = (int32_t)dsegs.size();
@@ -1062,6 +1065,7 @@ extern "C" pie_status pie_batch_create(pie_ctx* c, const pie_forward_batch* b, i
 
 extern "C" pie_status pie_batch_destroy(pie_ctx* c, pie_batch* b) {
   if (!b) return PIE_OK;
+  if (c != b->owner) return fail(c, PIE_EINVAL, "pie_batch_destroy: the batch belongs to another context");
   if (c && !c->host_only) (void)hipStreamSynchronize(c->stream);  // no kernel may still read the batch
   if (b->dev_blob) {
     constexpr size_t POOL_BLOCKS = 8;
@@ -1116,6 +1120,16 @@ struct StageTimer {
   void end(int s) { if (c->timing) { (void)hipEventRecord(c->ev[2 * s + 1], c->stream); c->ev_used[s] = true; } }
 };
 }  // namespace
+
+// A batch can only run on the context that deserialised it (its device block, id ranges and launch plan belong to
+// that context), and only when it has a device block at all (a planner's batch has none).
+static pie_status check_batch(pie_ctx* c, const pie_batch* b, const char* who) {
+  if (!b) return fail(c, PIE_EINVAL, "%s: null batch", who);
+  if (b->owner != c) return fail(c, PIE_EINVAL, "%s: the batch was created by another context", who);
+  if (!b->dev_blob) return fail(c, PIE_EINVAL, "%s: the batch has no device block (created by a planning context)", who);
+  if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "%s: batch larger than the context", who);
+  return PIE_OK;
+}
 
 // One decoder layer.  x_in: wide [T, H] layer input, or null to read the batch's input Embeds; y_out: wide
 // [T, H] destination of the layer output, or null to store it as bf16 into the batch's output Embeds.
@@ -1252,21 +1266,19 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
 extern "C" pie_status pie_forward(pie_ctx* c, int32_t layer, const pie_batch* b) {
   if (!c) return PIE_EINVAL;
   if (c->host_only) return fail(c, PIE_EINVAL, "pie_forward: the context only plans batches (pie_create_planner)");
-  if (!b) return fail(c, PIE_EINVAL, "pie_forward: null batch");
+  if (pie_status st = check_batch(c, b, "pie_forward")) return st;
   if (layer < 0 || layer >= c->m.n_layers) return fail(c, PIE_ERANGE, "pie_forward: layer %d of %d", layer, c->m.n_layers);
   if (!c->layers[layer].loaded) return fail(c, PIE_EINVAL, "pie_forward: layer %d has no weights", layer);
-  if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "batch larger than the context");
   return run_layer(c, layer, b, nullptr, nullptr, true);
 }
 
 extern "C" pie_status pie_forward_all(pie_ctx* c, const pie_batch* b) {
   if (!c) return PIE_EINVAL;
   if (c->host_only) return fail(c, PIE_EINVAL, "pie_forward_all: the context only plans batches (pie_create_planner)");
-  if (!b) return fail(c, PIE_EINVAL, "pie_forward_all: null batch");
+  if (pie_status st = check_batch(c, b, "pie_forward_all")) return st;
   const int NL = c->m.n_layers;
   for (int l = 0; l < NL; ++l)
     if (!c->layers[l].loaded) return fail(c, PIE_EINVAL, "pie_forward_all: layer %d has no weights", l);
-  if (b->T > c->p.max_batch_tokens) return fail(c, PIE_EBATCH, "batch larger than the context");
   int carry = 0;
   for (int l = 0; l < NL; ++l) {
     // the layer output stays wide between layers; only the last layer stores bf16 Embeds

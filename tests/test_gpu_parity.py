@@ -406,5 +406,17 @@ def test_error_codes():
     with pytest.raises(PieError) as e:
         Pie(bad, 8, 8, 4, 4)
     assert e.value.status == -7  # PIE_EUNSUPPORTED
+    # a batch of another context, or of a planning context (no device block), is refused before anything is launched
+    other = make_ctx(w)
+    pb_other = other.batch_create(w.batch)
+    assert ctx.lib.pie_forward(ctx.ctx, 0, pb_other.handle) == -1 and ctx.lib.pie_forward_all(ctx.ctx, pb_other.handle) == -1
+    assert ctx.lib.pie_batch_destroy(ctx.ctx, pb_other.handle) == -1
+    pb_other.destroy()
+    other.close()
+    planner = Pie.planner(m, w.n_kv_pages, w.n_embeds, 3, 2)
+    pb_plan = planner.batch_create(w.batch)
+    assert ctx.lib.pie_forward(ctx.ctx, 0, pb_plan.handle) == -1
+    pb_plan.destroy()
+    planner.close()
     # the context still works after the failed calls
     compare_layer(w, ctx=ctx, what="after errors")

@@ -290,3 +290,18 @@ def test_planner_context_refuses_device_work():
     ctx._check(ctx.lib.pie_synchronize(ctx.ctx))  # nothing to wait for
     with pytest.raises(PieError):
         Pie.planner(w.model, w.n_kv_pages, w.n_embeds, 8, 8, wave_slots=3)
+
+
+def test_a_batch_belongs_to_the_context_that_created_it():
+    """A batch carries the ranges, the wave count and (on a device context) the device block of its context: another
+    context refuses to run or to destroy it, and a planning context's batch cannot be run at all."""
+    w = dict(workloads())["decode64"]
+    a, b = planner_for(w), planner_for(w)
+    pb = a.batch_create(w.batch)
+    assert b.lib.pie_batch_destroy(b.ctx, pb.handle) == -1 and b"another context" in b.lib.pie_last_error(b.ctx)
+    assert a.lib.pie_forward(a.ctx, 0, pb.handle) == -1       # planning context: nothing can run
+    assert a.lib.pie_forward_all(a.ctx, pb.handle) == -1
+    assert a.lib.pie_batch_destroy(None, pb.handle) == -1      # no context at all
+    pb.destroy()
+    a.close()
+    b.close()
