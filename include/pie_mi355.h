@@ -224,9 +224,26 @@ pie_status pie_forward_dist(pie_ctx* ctx, const pie_batch* batch, const int32_t*
 pie_status pie_get_next_dist(pie_ctx* ctx, const int32_t* embed_ids, int32_t n, int32_t top_k, float temperature,
                              int32_t* out_ids, float* out_probs);
 
+/* pie_get_next_dist for callers that cannot allocate device memory or have it allocated on their behalf: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same result as pie_get_next_dist, for at most 32 rows and top_k <= 1024; every intermediate (the staged ids,
+ * normalised rows, fp32 logits, split-K partial sums, top-k candidates and chunk statistics) lives in one
+ * file-scope device array of 16 MiB that each GPU the library runs on holds until the process ends, and the embed
+ * ids reach the device as kernel arguments, so the call makes no hipMalloc, hipFree, copy from pageable memory or
+ * other allocating library call.  n x vocab x 4 bytes of logits, n x 16 x top_k x 8 bytes of candidates and
+ * n x hidden x 2 bytes of normalised rows must fit the array (at a vocabulary of 128256 and top_k 256: up to 30
+ * rows); otherwise PIE_EBATCH, as for n > 32.
+ * Every call on a GPU, from any context, uses that GPU's one array and leaves its contents behind (no kernel relies
+ * on them): calls that overlap on one GPU (two contexts on two streams) race and must be serialised by the caller.
+ * Other errors as pie_get_next_dist. */
+pie_status pie_get_next_dist_static(pie_ctx* ctx, const int32_t* embed_ids, int32_t n, int32_t top_k,
+                                    float temperature, int32_t* out_ids, float* out_probs);
+
+/* Waits for the context's stream (Table 1, `synchronize`: completion of the calls issued so far). */
 pie_status pie_synchronize(pie_ctx* ctx);
 
-/* ---- observation points for parity tests and per-kernel timing (not part of the serving path) ---- */
+/* ---- observation points for parity tests and per-kernel timing (not part of the serving path).  These are test
+ *      and measurement hooks of this library; no passage of the paper describes them. ---- */
 
 /* Copy an intermediate of the last pie_forward / pie_get_next_dist to `dst` (dev).  Sizes in
  * elements: Q [T, Hq*D] bf16 (after the rotary step), ATTN [T, Hq*D] bf16, RESID [T, hidden]

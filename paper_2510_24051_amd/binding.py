@@ -84,6 +84,7 @@ def load_library():
         "pie_copy_kvpage": [vp, vp, vp, vp, vp, i32],
         "pie_forward_host": [vp, i32, C.POINTER(ForwardBatchC), i32],
         "pie_get_next_dist": [vp, vp, i32, i32, f32, vp, vp],
+        "pie_get_next_dist_static": [vp, vp, i32, i32, f32, vp, vp],
         "pie_forward_dist": [vp, vp, vp, i32, i32, f32, vp, vp],
         "pie_synchronize": [vp],
         "pie_read_tap": [vp, i32, vp, i64],
@@ -339,6 +340,13 @@ class Pie:
         ids = _i32(embed_ids)
         self._check(self.lib.pie_get_next_dist(self.ctx, _ptr(ids), len(ids), top_k, float(temperature),
                                                C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_probs.data_ptr())))
+
+    def get_next_dist_static_async(self, embed_ids, top_k: int, temperature: float, out_ids: torch.Tensor,
+                                   out_probs: torch.Tensor):
+        """pie_get_next_dist_static: the allocation-free variant (at most 16 rows); outputs are caller tensors."""
+        ids = _i32(embed_ids)
+        self._check(self.lib.pie_get_next_dist_static(self.ctx, _ptr(ids), len(ids), top_k, float(temperature),
+                                                      C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_probs.data_ptr())))
 
     def forward_dist(self, batch: PieBatch, rows, top_k: int, temperature: float = 1.0):
         r = _i32(rows)

@@ -156,6 +156,8 @@ struct pie_ctx {
   int32_t* ids_dev = nullptr;  // staging for id lists of the small resource calls
   size_t ids_cap = 0;
   int last_T = 0, last_dist_n = 0;
+  const float* last_logits = nullptr;  // logits of the last get_next_dist call (workspace or static scratch)
+  unsigned char* static_scratch = nullptr;  // device address of this GPU's static scratch array (pie_get_next_dist_static)
   // timing
   bool timing = false;
   hipEvent_t ev[2 * PIE_N_STAGES];

@@ -12,6 +12,15 @@
 
 static char g_create_err[512] = "";
 
+// Scratch memory of pie_get_next_dist_static, the entry point for callers that cannot allocate: one array per GPU,
+// held until the process ends.  In host code `pie_static_scratch` is only a handle for hipGetSymbolAddress; the
+// device address of each GPU's copy is looked up once per device in pie_create and kept in g_static_scratch.
+#define PIE_STATIC_SCRATCH_BYTES (16u << 20)
+#define PIE_STATIC_DIST_ROWS 32
+#define PIE_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char pie_static_scratch[PIE_STATIC_SCRATCH_BYTES];
+static void* g_static_scratch[PIE_MAX_DEVICES] = {nullptr};
+
 static pie_status fail(pie_ctx* ctx, pie_status code, const char* fmt, ...) {
   char* dst = ctx ? ctx->err : g_create_err;
   va_list ap;
@@ -99,6 +108,15 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
     return PIE_OK;
   }
   hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess && c->device >= 0 && c->device < PIE_MAX_DEVICES) {
+    // this GPU's copy of the static scratch array (the context's device is current here)
+    if (!g_static_scratch[c->device]) {
+      void* ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(pie_static_scratch));
+      if (e == hipSuccess) g_static_scratch[c->device] = ptr;
+    }
+    c->static_scratch = reinterpret_cast<unsigned char*>(g_static_scratch[c->device]);
+  }
   {
     int cus = 0;
     if (e == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
@@ -1314,6 +1332,41 @@ static pie_status check_dist_args(pie_ctx* c, const void* ids, int32_t n, int32_
   return PIE_OK;
 }
 
+// The kernels of get_next_dist over ids already on the device, with every intermediate buffer named by the caller
+// (the context's workspace, or the static scratch array).
+struct DistBuffers {
+  const int32_t* ids;  // [n] embed ids
+  bf16_t* en;          // [n, H] normalised rows
+  float* logits;       // [n, V]
+  float* splitk;       // split-K partial sums of the LM head
+  size_t splitk_elems;
+  unsigned long long* cand;  // [n, chunks, k]
+  float* stats;              // [n, chunks, 2]
+};
+static pie_status run_dist(pie_ctx* c, const DistBuffers& w, int32_t n, int32_t top_k, float temperature,
+                           int32_t* out_ids, float* out_probs) {
+  const int H = c->m.hidden, V = c->m.vocab;
+  hipStream_t s = c->stream;
+  StageTimer tm(c, PIE_STAGE_HEAD_NORM, PIE_STAGE_TOPK);
+  tm.begin(PIE_STAGE_HEAD_NORM);
+  if (c->g_final) {
+    HIP_TRY(c, launch_rmsnorm_embed(c->embeds, w.ids, c->g_final, w.en, n, H, c->m.rms_eps, s));
+  } else {
+    HIP_TRY(c, launch_embed_copy(c->embeds, w.ids, n, H, w.en, 0, s));
+  }
+  tm.end(PIE_STAGE_HEAD_NORM);
+  tm.begin(PIE_STAGE_LM_HEAD);
+  EpiArgs e{EPI_STORE_F32, w.logits, V, nullptr, nullptr, nullptr, 0};
+  HIP_TRY(c, launch_gemm(w.en, H, n, c->wlm, e, w.splitk, w.splitk_elems, c->wave_slots / 8, s));
+  tm.end(PIE_STAGE_LM_HEAD);
+  tm.begin(PIE_STAGE_TOPK);
+  HIP_TRY(c, launch_topk(w.logits, n, V, top_k, 1.0f / temperature, out_ids, out_probs, w.cand, w.stats, s));
+  tm.end(PIE_STAGE_TOPK);
+  c->last_dist_n = n;
+  c->last_logits = w.logits;
+  return PIE_OK;
+}
+
 extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, int32_t n, int32_t top_k,
                                         float temperature, int32_t* out_ids, float* out_probs) {
   if (!c) return PIE_EINVAL;
@@ -1322,34 +1375,62 @@ extern "C" pie_status pie_get_next_dist(pie_ctx* c, const int32_t* embed_ids, in
   if (chk != PIE_OK) return chk;
   for (int i = 0; i < n; ++i)
     if (embed_ids[i] < 0 || embed_ids[i] >= c->p.n_embeds) return fail(c, PIE_ERANGE, "embed id %d at %d outside [0, %d)", embed_ids[i], i, c->p.n_embeds);
-  const int H = c->m.hidden, V = c->m.vocab;
-  hipStream_t s = c->stream;
   pie_status st = stage_ids(c, embed_ids, nullptr, n);
   if (st != PIE_OK) return st;
-  StageTimer tm(c, PIE_STAGE_HEAD_NORM, PIE_STAGE_TOPK);
-  tm.begin(PIE_STAGE_HEAD_NORM);
-  if (c->g_final) {
-    HIP_TRY(c, launch_rmsnorm_embed(c->embeds, c->ids_dev, c->g_final, c->en, n, H, c->m.rms_eps, s));
-  } else {
-    HIP_TRY(c, launch_embed_copy(c->embeds, c->ids_dev, n, H, c->en, 0, s));
+  const DistBuffers w{c->ids_dev, c->en, c->logits, c->splitk, c->splitk_elems, c->topk_cand, c->topk_stats};
+  return run_dist(c, w, n, top_k, temperature, out_ids, out_probs);
+}
+
+// Embed ids handed to the device as kernel arguments (no host-to-device copy, nothing to stage).
+struct IdList { int32_t v[PIE_STATIC_DIST_ROWS]; };
+__global__ void ids_from_args_kernel(IdList ids, int n, int32_t* __restrict__ dst) {
+  const int i = threadIdx.x;
+  if (i < n) dst[i] = ids.v[i];
+}
+
+extern "C" pie_status pie_get_next_dist_static(pie_ctx* c, const int32_t* embed_ids, int32_t n, int32_t top_k,
+                                               float temperature, int32_t* out_ids, float* out_probs) {
+  if (!c) return PIE_EINVAL;
+  if (c->host_only) return fail(c, PIE_EINVAL, "pie_get_next_dist_static: the context only plans batches (pie_create_planner)");
+  if (!embed_ids || n <= 0) return fail(c, PIE_EINVAL, "get_next_dist: null ids or n <= 0");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(c, PIE_EINVAL, "temperature must be positive and finite");
+  if (!c->head_loaded) return fail(c, PIE_EINVAL, "get_next_dist: no LM head loaded");
+  if (!out_ids || !out_probs) return fail(c, PIE_EINVAL, "get_next_dist: null output");
+  if (n > PIE_STATIC_DIST_ROWS) return fail(c, PIE_EBATCH, "%d rows exceed the %d rows of the allocation-free call", n, PIE_STATIC_DIST_ROWS);
+  if (top_k <= 0 || top_k > 1024 || top_k > c->m.vocab)
+    return fail(c, PIE_ERANGE, "top_k %d outside [1, min(1024, vocab %d)]", top_k, c->m.vocab);
+  if (!c->static_scratch) return fail(c, PIE_EHIP, "the static scratch array of device %d was not found at pie_create", c->device);
+  IdList ids{};
+  for (int i = 0; i < n; ++i) {
+    if (embed_ids[i] < 0 || embed_ids[i] >= c->p.n_embeds) return fail(c, PIE_ERANGE, "embed id %d at %d outside [0, %d)", embed_ids[i], i, c->p.n_embeds);
+    ids.v[i] = embed_ids[i];
   }
-  tm.end(PIE_STAGE_HEAD_NORM);
-  tm.begin(PIE_STAGE_LM_HEAD);
-  EpiArgs e{EPI_STORE_F32, c->logits, V, nullptr, nullptr, nullptr, 0};
-  HIP_TRY(c, launch_gemm(c->en, H, n, c->wlm, e, c->splitk, c->splitk_elems, c->wave_slots / 8, s));
-  tm.end(PIE_STAGE_LM_HEAD);
-  tm.begin(PIE_STAGE_TOPK);
-  HIP_TRY(c, launch_topk(c->logits, n, V, top_k, 1.0f / temperature, out_ids, out_probs, c->topk_cand, c->topk_stats, s));
-  tm.end(PIE_STAGE_TOPK);
-  c->last_dist_n = n;
-  return PIE_OK;
+  // carve the array: ids | normalised rows | logits | candidates | chunk statistics | split-K partials (the rest)
+  const size_t H = (size_t)c->m.hidden, V = (size_t)c->m.vocab;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t o_ids = 0, o_en = up(o_ids + PIE_STATIC_DIST_ROWS * 4), o_lg = up(o_en + (size_t)n * H * 2);
+  const size_t o_cd = up(o_lg + (size_t)n * V * 4), o_st = up(o_cd + (size_t)n * 16 * top_k * 8);
+  const size_t o_sk = up(o_st + (size_t)n * 16 * 2 * 4);
+  if (o_sk > PIE_STATIC_SCRATCH_BYTES)
+    return fail(c, PIE_EBATCH, "%d rows x vocab %zu x top_k %d need %zu bytes of scratch, the static array holds %u", n, V,
+                top_k, o_sk, (unsigned)PIE_STATIC_SCRATCH_BYTES);
+  unsigned char* base = c->static_scratch;  // the device address of this GPU's array, never the symbol itself
+  // Nothing in the array has to start at zero: every kernel below writes each element it or a later kernel reads
+  // (all n rows of en, logits, candidates (short chunks pad theirs), statistics and the partial sums that are used).
+  ids_from_args_kernel<<<dim3(1), dim3(64), 0, c->stream>>>(ids, n, reinterpret_cast<int32_t*>(base + o_ids));
+  HIP_TRY(c, hipGetLastError());
+  const DistBuffers w{reinterpret_cast<const int32_t*>(base + o_ids), reinterpret_cast<bf16_t*>(base + o_en),
+                      reinterpret_cast<float*>(base + o_lg), reinterpret_cast<float*>(base + o_sk),
+                      (PIE_STATIC_SCRATCH_BYTES - o_sk) / sizeof(float),
+                      reinterpret_cast<unsigned long long*>(base + o_cd), reinterpret_cast<float*>(base + o_st)};
+  return run_dist(c, w, n, top_k, temperature, out_ids, out_probs);
 }
 
 static pie_status pie_forward_dist_impl(pie_ctx* c, const pie_batch* b, const int32_t* rows, int32_t n, int32_t top_k,
                                        float temperature, int32_t* out_ids, float* out_probs) {
   if (!c) return PIE_EINVAL;
   if (c->host_only) return fail(c, PIE_EINVAL, "pie_forward_dist: the context only plans batches (pie_create_planner)");
-  if (!b) return fail(c, PIE_EINVAL, "pie_forward_dist: null batch");
+  if (pie_status stb = check_batch(c, b, "pie_forward_dist")) return stb;
   // every argument is checked before anything is enqueued
   pie_status st = check_dist_args(c, rows, n, top_k, temperature, out_ids, out_probs);
   if (st != PIE_OK) return st;
@@ -1403,7 +1484,7 @@ extern "C" pie_status pie_read_tap(pie_ctx* c, int32_t which, void* dst, int64_t
       break;
     case PIE_TAP_LOGITS:
       if (n_elements != (int64_t)c->last_dist_n * m.vocab) return fail(c, PIE_EINVAL, "tap LOGITS holds %lld elements", (long long)c->last_dist_n * m.vocab);
-      HIP_TRY(c, hipMemcpyAsync(dst, c->logits, (size_t)n_elements * 4, hipMemcpyDeviceToDevice, c->stream));
+      HIP_TRY(c, hipMemcpyAsync(dst, c->last_logits ? c->last_logits : c->logits, (size_t)n_elements * 4, hipMemcpyDeviceToDevice, c->stream));
       break;
     default:
       return fail(c, PIE_EINVAL, "unknown tap %d", which);
