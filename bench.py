@@ -24,8 +24,81 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 MFMA_RIDGE_ROWS = 312  # rows above which a bf16 GEMM stops being bound by streaming its weights
 # HBM bytes per launch of the decode-attention kernel from rocprofv3 counters (FETCH_SIZE scaled by the factor a
-# once-streamed weight matrix of known size gives, plus WRITE_SIZE); see profiles/c2_decode_pmc.md
-PMC_TRAFFIC_BYTES = {"c2": 524.6e6 + 5.1e6}
+# once-streamed weight matrix of known size gives, plus WRITE_SIZE), taken in a profiling session of its own on
+# exactly the default configuration (workload c2, 64 requests, one layer, no adapters): reported only when this run
+# is that configuration, with the file that holds the counters named beside it; any other run reports null.
+PMC_TRAFFIC = {"workload": "c2", "requests": 64, "layers": 1, "lora_rank": 0, "bytes": 524.6e6 + 5.1e6,
+               "source": "profiles/c2_decode_pmc.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this command)"}
+
+
+def mixed_workload_fractions(w_dec, args):
+    """A short run of the mixed workload (configs[2]: 8 prefill requests of 1024 tokens + 128 decode requests through
+    the same 8B-shaped layer, whose weights are reused) for the MFMA-bound kernels: the four tiled layer GEMMs and
+    prefill attention as fractions of the dense bf16 matrix peak, from the library's per-stage HIP events."""
+    import numpy as np
+    import workloads as W
+    from paper_2510_24051_amd import Pie
+    w = W.c3_mixed(weights=w_dec.weights, head=w_dec.head, with_head=False)
+    b, m = w.batch, w.model
+    T = int(b.n_tokens)
+    free_ids = np.setdiff1d(np.arange(w.n_embeds, dtype=np.int32), b.in_embed_ids)
+    b.out_embed_ids = free_ids[:T].astype(np.int32)
+    ctx = Pie(m, w.n_kv_pages, w.n_embeds, max_batch_tokens=T, max_batch_requests=b.n_requests, max_top_k=0,
+              max_dist_rows=0)
+    ctx.load_layer(0, w.weights)
+    ctx.embed_write(b.in_embed_ids, w.embed_bits)
+    ctx.kv_write(0, w.prior.page_ids, w.prior.slots, w.prior.k_bits, w.prior.v_bits)
+    pb = ctx.batch_create(b, validate=True)
+    for _ in range(3):
+        ctx.forward(0, pb)
+    ctx.synchronize()
+    n = 10
+    t0 = time.perf_counter()
+    for _ in range(n):
+        ctx.forward(0, pb)
+    ctx.synchronize()
+    fwd_ms = (time.perf_counter() - t0) * 1e3 / n
+    ctx.set_stage_timing(True)
+    acc = {}
+    for _ in range(n):
+        ctx.forward(0, pb)
+        for k, v in ctx.stage_times().items():
+            acc[k] = acc.get(k, 0.0) + v / n
+    ctx.set_stage_timing(False)
+    QD, KD, H, I = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim, m.hidden, m.mlp_dim
+    shapes = {"qkv": H * (QD + 2 * KD), "oproj": QD * H, "gateup": 2 * H * I, "down": I * H}
+    out = {"workload": "configs[2]: 8 prefill x 1024 (prior U[0,2048]) + 128 decode @2048, one 8B-shaped layer",
+           "tokens": T, "forward_ms": round(fwd_ms, 4), "tokens_per_s": round(T / (fwd_ms * 1e-3), 1),
+           "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "kernels": {}}
+    tot_f, tot_ms = 0.0, 0.0
+    for k, elems in shapes.items():
+        fl, ms = 2.0 * T * elems, acc.get(k, 0.0)
+        tot_f, tot_ms = tot_f + fl, tot_ms + ms
+        if ms > 0:
+            out["kernels"][k] = {"bound": "mfma", "flops": fl, "ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1),
+                                 "frac": round(fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    if tot_ms > 0:
+        out["kernels"]["layer_gemms"] = {"bound": "mfma", "flops": tot_f, "ms": round(tot_ms, 4),
+                                         "TFLOPs": round(tot_f / tot_ms / 1e9, 1),
+                                         "frac": round(tot_f / tot_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    G = m.n_q_heads // m.n_kv_heads
+    pf = 0
+    for r in range(b.n_requests):
+        nn = int(b.tok_indptr[r + 1] - b.tok_indptr[r])
+        if nn * G > 16:  # prefill path; causal half only, skipped tiles are not counted
+            pf += 4 * m.n_q_heads * m.head_dim * (nn * (int(b.kv_len[r]) - nn) + nn * (nn + 1) // 2)
+    ms = acc.get("attn_prefill", 0.0)
+    if ms > 0:
+        out["kernels"]["attn_prefill"] = {"bound": "mfma", "flops": pf, "ms": round(ms, 4), "TFLOPs": round(pf / ms / 1e9, 1),
+                                          "frac": round(pf / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    ms = acc.get("attn_decode", 0.0)
+    if ms > 0:
+        kvb = pb.work()["kv_bytes_decode"]
+        out["kernels"]["attn_decode"] = {"bound": "hbm", "bytes": kvb, "ms": round(ms, 4), "GBs": round(kvb / ms / 1e6, 1),
+                                         "frac": round(kvb / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    pb.destroy()
+    ctx.close()
+    return out
 
 
 def main():
@@ -35,6 +108,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default run only: skip the short run of the mixed workload c3 that adds the MFMA-bound kernels' "
+                         "fractions of peak (other_workloads) to the line")
     ap.add_argument("--top-k", type=int, default=256)
     ap.add_argument("--requests", type=int, default=64, help="c2 only: number of decode requests (default: the config's 64)")
     ap.add_argument("--lora-rank", type=int, default=0,
@@ -132,6 +208,25 @@ def main():
         fwd()
     ctx.synchronize()
     fwd_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # the same calls one by one, each between two events on the library's stream: the median of single calls
+    n_single = max(20, min(args.steps, 50))
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_single)]
+    with torch.cuda.stream(ctx.stream):
+        for a, b_ in evs:
+            a.record()
+            fwd()
+            b_.record()
+    ctx.synchronize()
+    fwd_median_ms = float(np.median([a.elapsed_time(b_) for a, b_ in evs]))
+    # what a serving loop pays per step on top: deserialising the batch (host checks, work lists, one H2D copy)
+    # and releasing it; never part of `value` (inputs resident, batch deserialised before the timed region)
+    ctx.synchronize()
+    t0 = time.perf_counter()
+    n_host = 10
+    for _ in range(n_host):
+        pb2 = ctx.batch_create(b, validate=False)
+        pb2.destroy()
+    batch_create_ms = (time.perf_counter() - t0) * 1e3 / n_host
 
     # per-stage durations: HIP events recorded by the library on its own stream around every stage
     ctx.set_stage_timing(True)
@@ -167,8 +262,11 @@ def main():
     attn_ms = stages.get("attn_decode", 0.0)
     achieved = attn_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
     roofline = {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": PMC_TRAFFIC_BYTES.get(args.workload),
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "traffic_source": None,
                 "algorithmic_bytes": attn_bytes, "avg_ms": round(attn_ms, 5)}
+    if (args.workload, args.requests, NL, args.lora_rank) == (PMC_TRAFFIC["workload"], PMC_TRAFFIC["requests"],
+                                                               PMC_TRAFFIC["layers"], PMC_TRAFFIC["lora_rank"]):
+        roofline["traffic"], roofline["traffic_source"] = PMC_TRAFFIC["bytes"], PMC_TRAFFIC["source"]
     if attn_b2b_ms > 0:
         roofline["forward_calls_back_to_back"] = {"avg_ms": round(attn_b2b_ms, 5),
                                                   "achieved": round(attn_bytes / (attn_b2b_ms * 1e-3) / 1e9, 1)}
@@ -216,6 +314,10 @@ def main():
                                  "achieved_TFLOPs": round(pf_flops / (pf_ms * 1e-3) / 1e12, 1),
                                  "frac": round(pf_flops / (pf_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
+    other = None
+    if args.workload == "c2" and args.requests == 64 and NL == 1 and args.lora_rank == 0 and not args.no_other_workloads:
+        other = {"c3": mixed_workload_fractions(w, args)}
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import pie_oracle as O
@@ -251,9 +353,13 @@ def main():
         "config": {"workload": desc, "tokens_per_step": T, "requests": int(b.n_requests), "dist_rows": n_dist,
                    "top_k": int(w.top_k), "layers": NL, "lora_rank": int(args.lora_rank),
                    "step": ("pie_forward (1 layer)" if NL == 1 else f"pie_forward_all ({NL} layers)") + " + pie_get_next_dist"},
-        "forward_only": {"tokens_per_s": round(T / (fwd_ms * 1e-3), 1), "ms": round(fwd_ms, 5)},
+        "forward_only": {"tokens_per_s": round(T / (fwd_ms * 1e-3), 1), "ms": round(fwd_ms, 5),
+                         "median_ms_single_calls": round(fwd_median_ms, 5)},
+        "host": {"batch_create_plus_destroy_ms": round(batch_create_ms, 4),
+                 "step_including_batch_create_ms": round(ms_per_step + batch_create_ms, 4),
+                 "note": "deserialising the batch is host work outside `value`; it can run while the GPU executes the previous step"},
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},
-        "roofline": roofline, "other_kernels": extra, "cpu_baseline": cpu,
+        "roofline": roofline, "other_kernels": extra, "other_workloads": other, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
 

@@ -46,22 +46,48 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* red) {
   return t;
 }
 
-// Top byte of the need-th largest key: walk the byte values downward from the maximum's, counting matches in
-// registers.  On return *out_b is that byte, *out_need what is still needed among the keys that carry it and
-// *out_cnt how many keys carry it (need - *out_need keys have a larger top byte).
+// Top byte of the need-th largest key.  On return *out_b is that byte, *out_need what is still needed among the keys
+// that carry it and *out_cnt how many keys carry it (need - *out_need keys have a larger top byte).
+// The byte values are walked downward from the maximum's, counting matches in registers: logits of one row share a
+// handful of sign/exponent values, so the k-th largest is almost always found within a step or two.  When it is not
+// after WALK_STEPS values (a positive maximum over a negative k-th largest lies 128 byte values apart, all the
+// exponents of tiny magnitudes in between being empty), the rest of the range is bisected instead: at most eight
+// more counts, whatever the distribution.  Every count is uniform over the workgroup, so the control flow is too.
+#define WALK_STEPS 4
 template <typename KeyT, int PER, int THREADS>
 __device__ __forceinline__ void walk_top_byte(const KeyT (&keys)[PER], uint32_t need, int top_byte_max, uint32_t* red,
                                               int* out_b, uint32_t* out_need, uint32_t* out_cnt) {
   constexpr int TOP = sizeof(KeyT) * 8 - 8;
-  int b = top_byte_max;
-  uint32_t cnt = 0;
-  for (;; --b) {
+  auto count_in = [&](int lo, int hi) {  // keys whose top byte lies in [lo, hi]
     uint32_t c = 0;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) c += ((int)(keys[i] >> TOP) == b && keys[i] != 0) ? 1u : 0u;
-    cnt = block_sum<THREADS>(c, red);
-    if (cnt >= need || b == 0) break;
+    for (int i = 0; i < PER; ++i) {
+      const int tb = (int)(keys[i] >> TOP);
+      c += (tb >= lo && tb <= hi && keys[i] != 0) ? 1u : 0u;
+    }
+    return block_sum<THREADS>(c, red);
+  };
+  int b = top_byte_max;
+  uint32_t cnt = 0;
+  bool found = false;
+  for (int step = 0; step < WALK_STEPS; ++step, --b) {
+    cnt = count_in(b, b);
+    if (cnt >= need || b == 0) { found = true; break; }
     need -= cnt;
+  }
+  if (!found) {
+    // the answer is the largest byte value t <= hi with count_in(t, hi) >= need (0 when there are fewer keys)
+    const int hi = b;
+    int lo = 0, up = hi;
+    while (lo < up) {
+      const int mid = (lo + up + 1) >> 1;
+      if (count_in(mid, hi) >= need) lo = mid;
+      else up = mid - 1;
+    }
+    b = lo;
+    const uint32_t above = b < hi ? count_in(b + 1, hi) : 0u;
+    need -= above;
+    cnt = count_in(b, b);
   }
   *out_b = b;
   *out_need = need;

@@ -373,6 +373,60 @@ def test_top_k_ties_in_long_rows(vocab, k):
     np.testing.assert_allclose(gp, 1.0 / vocab, rtol=1e-5)
 
 
+def crafted_logit_rows(vocab, rows):
+    """A context whose get_next_dist returns exactly the given logit rows (bf16 values): no final norm, Embed r is
+    the r-th unit vector and column r of the LM head holds row r."""
+    H = 128
+    m = small_model(hidden=H, vocab=vocab)
+    w = W.build_workload("crafted", m, [W.RequestSpec(1, 3) for _ in range(len(rows))], n_kv_pages=16, seed=45,
+                         std=0.05, top_k=256)
+    w.head.g_final = None
+    w.head.w_lm[:] = 0
+    for r, z in enumerate(rows):
+        w.head.w_lm[:, r] = W.to_bf16_bits(np.asarray(z, dtype=np.float32))
+    ctx = make_ctx(w, max_top_k=256, max_dist_rows=len(rows))
+    unit = np.zeros((len(rows), H), dtype=np.float32)
+    unit[np.arange(len(rows)), np.arange(len(rows))] = 1.0
+    ids = np.arange(len(rows), dtype=np.int32)
+    ctx.embed_write(ids, W.to_bf16_bits(unit))
+    return ctx, w, ids
+
+
+def test_top_k_across_the_sign_boundary_is_exact_and_no_slower():
+    """Rows whose maximum is positive and whose k-th largest is negative (the order keys of the two lie 128 top-byte
+    values apart), and rows shifted to mean -8 with a handful of positive logits: same exact result as the oracle's
+    full sort, and the top-k kernels take about as long as on a N(0,1) row."""
+    V, k = 128256, 256
+    rng = np.random.default_rng(46)
+    plain = rng.standard_normal(V)
+    shifted = rng.standard_normal(V) - 8.0
+    shifted[rng.choice(V, 5, replace=False)] = rng.random(5) * 3 + 0.5       # k-th largest is about -5
+    mixed = rng.standard_normal(V) * 0.5 - 3.0
+    mixed[rng.choice(V, 100, replace=False)] = rng.random(100) * 2 + 1.0     # 100 positives, the rest negative
+    tiny = np.where(rng.random(V) < 0.5, 1.0, -1.0) * 10.0 ** rng.uniform(-30, 0, V)  # every exponent in use
+    rows = [plain, shifted, mixed, tiny]
+    ctx, w, ids = crafted_logit_rows(V, rows)
+    gi, gp = ctx.get_next_dist(ids, k, 1.0)
+    z = np.stack([dec(W.to_bf16_bits(np.asarray(r, dtype=np.float32))) for r in rows])
+    oi, op = O.top_k_dist(z, k, 1.0)
+    assert np.array_equal(gi, oi)  # crafted logits are exact on both sides: no tie slack needed
+    np.testing.assert_allclose(gp, op, rtol=2e-3, atol=1e-12)
+    # one row at a time, stage-timed: the walk from the maximum's top byte must not take longer across the boundary
+    ctx.set_stage_timing(True)
+    t = []
+    for r in range(len(rows)):
+        samples = []
+        for _ in range(7):
+            ctx.get_next_dist(ids[r:r + 1], k, 1.0)
+            samples.append(ctx.stage_times()["topk"])
+        t.append(float(np.median(samples)))
+    ctx.set_stage_timing(False)
+    print(f"    top-k of one row of {V}: N(0,1) {t[0] * 1e3:.1f} us, mean -8 with 5 positives {t[1] * 1e3:.1f} us, "
+          f"100 positives over negatives {t[2] * 1e3:.1f} us, all exponents {t[3] * 1e3:.1f} us", flush=True)
+    assert max(t[1:]) <= 2.0 * t[0]
+    ctx.close()
+
+
 # ---------------------------------------------------------------- error paths (detected on the host)
 def test_error_codes():
     from paper_2510_24051_amd import Pie, PieError
