@@ -439,21 +439,24 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restric
 }
 
 // ------------------------------------------------------------------------------------------------
-// gemm_large, asynchronous-copy version (K a multiple of 128)
+// gemm_large, asynchronous-copy version (K a multiple of 64)
 //
-// Same 256x256x64 tile and 8 waves of 128x64 as above, but both operand tiles are copied global -> LDS by
-// direct-to-LDS loads (no VGPR staging, no LDS store instructions): each wave instruction moves 1 KiB, the
-// activation rows land pre-swizzled (16-byte chunk c of row r at position c ^ ((r >> 1) & 7), conflict-free for
-// the 64-bank LDS when 16 consecutive rows read the same chunk), the weight tiles land in operand order.  Two
-// LDS stages as separate arrays so that the compiler's wait counters keep the copy of tile t+1 in flight while
-// tile t is computed; the surplus copy of the last round re-reads the last tile.  Workgroup ids are remapped so
-// that each XCD (id % 8) works on a contiguous range of a grouped tile order (8 row tiles per group) and its L2
-// sees a few activation and weight panels at a time.
+// Same 256x256x64 tile and 8 waves of 128x64 as above.  The activation tile is copied global -> LDS by direct-to-LDS
+// loads (no VGPR staging, no LDS store instructions): each wave instruction moves 1 KiB and the rows land
+// pre-swizzled (16-byte chunk c of row r at position c ^ ((r >> 1) & 7), conflict-free for the 64-bank LDS when 16
+// consecutive rows read the same chunk); three stages as separate arrays (the compiler's wait counters then know
+// which copy a read may alias), copies two k steps ahead, one fence-free barrier per k step.
+// The weight operands do not pass through LDS: a wave reads the tiles of its two column blocks straight from
+// global memory into MFMA B operands (the tiled weight layout makes each a contiguous 1 KiB load; the two waves
+// that share a column block meet in the vector cache), one k step ahead, refilling each register set right after
+// the MFMAs that consumed it.  Why: LDS delivers 64 bytes per clock and compute unit for 16-byte reads (measured),
+// and with both operands in LDS a 128x64 wave tile reads 6 KiB per 8 MFMAs, 96 bytes per clock at the full matrix
+// rate: the kernel was bound by LDS reads at 2/3 of that rate (LDS 93% busy in the counters).  Without the weights
+// it reads 4 KiB per 8 MFMAs; the matrix pipe went from 62% to 72% busy, of which the lower clock under the higher
+// load gives back a part (8320 x 28672 x 4096: 1.70 -> 1.58 ms on one box).
+// Workgroup ids are remapped so that each XCD (id % 8) works on a contiguous range of a grouped tile order (8 row
+// tiles per group) and its L2 sees a few activation and weight panels at a time.
 // ------------------------------------------------------------------------------------------------
-#define LDS_DMA16(gptr, lptr)                                                                       \
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),           \
-                                   (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
-
 // BM = 256, or 128 for products of at most 128 rows (half the accumulators and half the activation copies per wave).
 template <int MODE, bool PARTIAL, int BM>
 __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __restrict__ A, int lda, int M,
@@ -462,12 +465,12 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
                                                                int kts_per_split, float* __restrict__ part) {
   static_assert(BM == 256 || BM == 128, "tile height");
   constexpr int MI = BM / 64;  // 32-row accumulator blocks per wave, and activation copy instructions per wave
-  __shared__ __align__(16) bf16_t As0[BM * LG_BK], As1[BM * LG_BK], Bs0[LG_BN * LG_BK], Bs1[LG_BN * LG_BK];
+  __shared__ __align__(16) bf16_t As0[BM * LG_BK], As1[BM * LG_BK], As2[BM * LG_BK];  // three activation stages
   constexpr int GROUP_M = 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
-  const int KB = K / 16, KT = K / LG_BK;  // KT is even
-  // split K: workgroup row blockIdx.y takes k tiles [kt0, kt1), an even count
+  const int KB = K / 16, KT = K / LG_BK;
+  // split K: workgroup row blockIdx.y takes k tiles [kt0, kt1)
   const int kt0 = PARTIAL ? blockIdx.y * kts_per_split : 0;
   const int kt1 = PARTIAL ? min(KT, kt0 + kts_per_split) : KT;
   int pid = blockIdx.x;
@@ -491,70 +494,108 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // copy instruction j of an operand covers LDS bytes [j KiB, (j + 1) KiB)
-  //   A (j = wave * MI + jj): rows j*8 .. j*8+7, lane -> row j*8 + lane/8, stored chunk lane%8
-  //   W (j = wave * 4 + jj): block j/4, k-step j%4 (1 KiB contiguous in the tiled weight)
-  const bf16_t* ap[MI];
-  const bf16_t* bp[4];
+  {
+#if __HIP_DEVICE_COMPILE__  // (the buffer-descriptor builtins exist for the device target only)
+    // Both operands are addressed through buffer descriptors (base in scalar registers, a 32-bit byte offset per
+    // lane, the k step as a scalar offset): a request is one instruction without 64-bit address arithmetic, reads
+    // past the end return zeros, and the direct-to-LDS copies are buffer loads, not global (flat-encoded) loads:
+    // with those in flight the compiler waits for all outstanding vector memory operations before every use of a
+    // register that a load returns, which would drain the weight loads requested ahead at every step.
+    constexpr int RSRC_FLAGS = 0x00020000;  // raw dword buffer, gfx9 family
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(A), 0, (int)(((int64_t)(M - 1) * lda + K) * 2), RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(Wp), 0, (int)((int64_t)NB * 32 * K * 2), RSRC_FLAGS);
+    // copy instruction j = wave * MI + jj of a stage covers LDS bytes [j KiB, (j + 1) KiB): rows j*8 .. j*8+7 of
+    // the tile, lane -> row j*8 + lane/8, stored chunk lane%8
+    int aoff[MI], woff[2];  // byte offsets of this lane's pieces at k step 0
 #pragma unroll
-  for (int jj = 0; jj < MI; ++jj) {
-    const int j = wave * MI + jj;
-    const int r = j * 8 + (lane >> 3);
-    const int kc = (lane & 7) ^ ((r >> 1) & 7);
-    int gr = m0 + r;
-    gr = gr < M ? gr : M - 1;  // rows past M re-read a valid row; their results are never stored
-    ap[jj] = A + (int64_t)gr * lda + kc * 8;
-  }
-#pragma unroll
-  for (int jj = 0; jj < 4; ++jj) {
-    const int j = wave * 4 + jj;
-    int nb = nb0 + (j >> 2);
-    nb = nb < NB ? nb : NB - 1;
-    bp[jj] = Wp + packed_tile_offset(nb, j & 3, KB) + lane * 8;
-  }
-  auto issue = [&](bf16_t* As, bf16_t* Bs, int kt) {
-    const int k = kt < kt1 ? kt : kt1 - 1;
-#pragma unroll
-    for (int jj = 0; jj < MI; ++jj) LDS_DMA16(ap[jj] + (int64_t)k * LG_BK, As + (wave * MI + jj) * 512);
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) LDS_DMA16(bp[jj] + (int64_t)k * 2048, Bs + (wave * 4 + jj) * 512);
-  };
-  auto load_frags = [&](const bf16_t* As, const bf16_t* Bs, int s, bf16x8 (&af)[MI], bf16x8 (&bfr)[2]) {
-    const int kc = s * 2 + (lane >> 5);
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-      const int r = wm * (BM / 2) + i * 32 + (lane & 31);
-      af[i] = *reinterpret_cast<const bf16x8*>(As + r * LG_BK + ((kc ^ ((r >> 1) & 7)) << 3));
+    for (int jj = 0; jj < MI; ++jj) {
+      const int r = (wave * MI + jj) * 8 + (lane >> 3);
+      const int kc = (lane & 7) ^ ((r >> 1) & 7);
+      int gr = m0 + r;
+      gr = gr < M ? gr : M - 1;  // rows past M re-read a valid row; their results are never stored
+      aoff[jj] = (int)(((int64_t)gr * lda + kc * 8) * 2);
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + ((wn * 2 + j) * 4 + s) * 512 + lane * 8);
-  };
-  auto compute = [&](const bf16_t* As, const bf16_t* Bs) {
-    bf16x8 af[2][MI], bfr[2][2];
-    load_frags(As, Bs, 0, af[0], bfr[0]);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (s + 1 < 4) load_frags(As, Bs, s + 1, af[(s + 1) & 1], bfr[(s + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(af[s & 1][i], bfr[s & 1][j], acc[i][j]);
-      __builtin_amdgcn_sched_barrier(0);
+    for (int j = 0; j < 2; ++j) {
+      int nb = nb0 + wn * 2 + j;
+      nb = nb < NB ? nb : NB - 1;  // a column block past the matrix re-reads a valid one; its results are dropped
+      woff[j] = (int)((packed_tile_offset(nb, 0, KB) + lane * 8) * 2);
     }
-  };
-  issue(As0, Bs0, kt0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  for (int kt = kt0; kt < kt1; kt += 2) {
-    issue(As1, Bs1, kt + 1);
-    compute(As0, Bs0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    issue(As0, Bs0, kt + 2);
-    compute(As1, Bs1);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    u32x4 wreg[4][2];  // the weight operands of one k step: [16-wide contraction step][column block]
+    auto issue_a = [&](bf16_t* As, int kt) {
+      const int k = kt < kt1 ? kt : kt1 - 1;  // past the end: a copy nobody reads, so that the wait counts stay uniform
+#pragma unroll
+      for (int jj = 0; jj < MI; ++jj)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (__attribute__((address_space(3))) void*)(As + (wave * MI + jj) * 512),
+                                                 16, aoff[jj], k * (LG_BK * 2), 0, 0);
+    };
+    auto load_w = [&](int kt, const int s) {
+      const int k = kt < kt1 ? kt : kt1 - 1;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) wreg[s][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, woff[j], (k * 4 + s) * 1024, 0);
+    };
+    auto load_a = [&](const bf16_t* As, int s, bf16x8 (&af)[MI]) {
+      const int kc = s * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const int r = wm * (BM / 2) + i * 32 + (lane & 31);
+        af[i] = *reinterpret_cast<const bf16x8*>(As + r * LG_BK + ((kc ^ ((r >> 1) & 7)) << 3));
+      }
+    };
+    // One k step on stage Acur; the copy of k step kt + 2 goes to Afill (read last in k step kt - 1, which every wave
+    // has left).  The step's barrier sits before its last 16-wide contraction step instead of at its end: by then a
+    // wave has read everything it needs from Acur, so after the barrier the first operands of the next k step can be
+    // read from Anext while the last MFMAs of this one run, and no step starts with the matrix cores waiting for
+    // LDS.  Vector memory operations complete in order: at the barrier the newest MI + 6 (the copy issued at the top
+    // of the step and the weight loads of its first three contraction steps) may still be in flight, everything
+    // older has arrived, in particular this wave's part of the activation tile of k step kt + 1.
+    bf16x8 af[2][MI];
+    auto step = [&](const bf16_t* Acur, const bf16_t* Anext, bf16_t* Afill, int kt) {
+      issue_a(Afill, kt + 2);
+      __builtin_amdgcn_sched_barrier(0);  // the copies go out first: the wait counts rely on the request order
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (s + 1 < 4) {
+          load_a(Acur, s + 1, af[(s + 1) & 1]);
+        } else {
+          PIE_S_WAIT_LGKMCNT0();  // this wave's last reads of Acur have returned
+          PIE_S_WAIT_VMCNT(MI + 6);
+          wg_barrier();
+          load_a(Anext, 0, af[0]);
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            Pack16 w;
+            w.u = wreg[s][j];
+            acc[i][j] = mfma32(af[s & 1][i], w.h, acc[i][j]);
+          }
+        load_w(kt + 1, s);  // refill the registers just consumed with the next k step's weights
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    issue_a(As0, kt0);
+    issue_a(As1, kt0 + 1);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) load_w(kt0, s);
+    PIE_S_WAIT_VMCNT(MI + 8);  // the first activation tile has arrived
+    wg_barrier();
+    load_a(As0, 0, af[0]);
+    int kt = kt0;
+    for (; kt + 3 <= kt1; kt += 3) {  // whole revolutions of the three stages; the one or two steps left over follow
+      step(As0, As1, As2, kt);
+      step(As1, As2, As0, kt + 1);
+      step(As2, As0, As1, kt + 2);
+    }
+    if (kt < kt1) {
+      step(As0, As1, As2, kt);
+      if (kt + 1 < kt1) step(As1, As2, As0, kt + 1);
+    }
+    PIE_S_WAIT_VMCNT(0);  // the surplus copies of the last steps land before the workgroup gives up its LDS
+#endif
   }
   if (PARTIAL) {
     // raw partial sums: part[split][m][n_packed]
@@ -755,15 +796,17 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   // Very wide outputs (the LM head) give the tiled kernel at least one tile per CU even with a single row
   // block; above 64 rows it beats streaming the weights past 4-8 row blocks per wave (measured at 128256 x 4096:
   // 0.26 ms for up to 256 rows against 0.30 ms at 128 rows and 0.46 ms at 256 rows).
-  const bool wide = W.K % 128 == 0 && (W.NB + 7) / 8 >= n_cus && M > 64;
-  if (M <= 256 && !wide && W.K % 128 == 0) {
+  // the tiled kernel steps 64 contraction elements at a time and addresses both operands with 32-bit byte offsets
+  const bool tiled_ok = W.K % LG_BK == 0 && (int64_t)M * lda * 2 < ((int64_t)1 << 32) &&
+                        (int64_t)W.NB * 32 * W.K * 2 < ((int64_t)1 << 32);
+  const bool wide = tiled_ok && (W.NB + 7) / 8 >= n_cus && M > 64;
+  if (M <= 256 && !wide && tiled_ok) {
     // One row of 256-column tiles (128 rows high up to 128 rows, else 256) with K split so that the tiles fill the
     // chip once; each split keeps at least TILED_MIN_KTS k tiles, or the pipeline fill and the partial sums
     // outweigh the work.
     const int tiles_n = (W.NB + 7) / 8, KT = W.K / LG_BK, NP = W.NB * 32;
     int splits = std::max(1, n_cus / tiles_n);
     int kts = (KT + splits - 1) / splits;
-    kts += kts & 1;
     kts = std::max(kts, TILED_MIN_KTS);
     splits = (KT + kts - 1) / kts;
     if (splits > 1 && (size_t)splits * M * NP <= ws_elems) {
@@ -786,7 +829,7 @@ static hipError_t run_mode(const bf16_t* A, int lda, int M, const PackedWeight& 
   if constexpr (MODE != EPI_SWIGLU) {  // (eight row blocks of gate/up pairs would not fit the register file)
     if (M <= 256 && !wide) return run_skinny<8, MODE>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   }
-  if (W.K % 128 == 0) {
+  if (tiled_ok) {
     const int tiles_n = (W.NB + 7) / 8;
     // A ragged last row block that would open one more round of tiles (a round = one tile per CU) costs a whole
     // round for a fraction of a tile's work: those rows go through the weight-streaming kernel instead.
