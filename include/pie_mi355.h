@@ -41,9 +41,10 @@ enum {
 
 /* Model shape: a Llama-family decoder layer (Implementation section: the handlers support the
  * Llama family) - RMSNorm, grouped-query attention with rotary positions, SwiGLU MLP, no biases.
- * Supported: head_dim 64 or 128, page_size 16 (KvPage sizes of 8-32 tokens are named in the
- * Resources paragraph), n_q_heads a multiple of n_kv_heads with ratio <= 8, hidden / mlp_dim /
- * vocab multiples of 32. */
+ * Supported: head_dim 64 or 128, page_size 16 or 32 (KvPage sizes of 8-32 tokens are named in the
+ * Resources paragraph; a page of 32 is stored as two consecutive 16-token blocks, and the page counts
+ * and page bytes reported by pie_batch_work are then in 16-token blocks), n_q_heads a multiple of
+ * n_kv_heads with ratio <= 8, hidden / mlp_dim / vocab multiples of 32. */
 typedef struct {
   int32_t hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, vocab, page_size;
   float rms_eps, rope_theta;
@@ -122,7 +123,7 @@ pie_status pie_kv_read(pie_ctx* ctx, int32_t layer, const int32_t* page_ids, con
 
 /* `mask_kvpage(q, tgt, mask)` (Table 1, Forward row: masks the KV cache in a token-level manner): sets the
  * token-level mask of each target KvPage; bit s of visible_bits[k] says whether the token in slot s of page
- * page_ids[k] stays visible (bits at and above page_size are ignored).  The mask replaces the page's previous
+ * page_ids[k] stays visible (bits at and above page_size are ignored; a page of 32 tokens uses all 32 bits).  The mask replaces the page's previous
  * one, holds in every layer, and is honoured, on top of a call's own mask, by every batch deserialised
  * afterwards (pie_batch_create reads the masks; a batch created earlier keeps what it saw).  A fresh context has
  * every token visible.  Host arrays [n]; no GPU work.  Errors: PIE_EINVAL, PIE_ERANGE. */

@@ -10,7 +10,7 @@
 #include "../../include/pie_mi355.h"
 #include "common.h"
 
-#define PAGE 16  // tokens per KvPage the kernels are built for
+#define PAGE 16  // tokens per block of the KvPage pool the kernels are built for (a KvPage is one or two blocks)
 
 // ---- tiled weights ---------------------------------------------------------------------------
 struct PackedWeight {
@@ -120,6 +120,7 @@ struct pie_ctx {
   hipStream_t stream = nullptr;
   int device = 0;
   int wave_slots = 2048;  // waves the chip keeps resident for the decode-attention kernel
+  int blocks_per_page = 1;  // a KvPage is this many consecutive 16-token blocks of the pool (page_size / 16)
   bool host_only = false; // pie_create_planner: deserialises and plans batches, owns nothing on a device
   bf16_t* embeds = nullptr;
   bf16_t* kv = nullptr;

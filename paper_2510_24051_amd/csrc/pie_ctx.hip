@@ -70,7 +70,9 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
                                   int planner_wave_slots = 0) {
   if (!m || !p || !out) return fail(nullptr, PIE_EINVAL, "pie_create: null argument");
   *out = nullptr;
-  if (m->page_size != PAGE) return fail(nullptr, PIE_EUNSUPPORTED, "page_size %d: kernels are built for %d", m->page_size, PAGE);
+  if (m->page_size != PAGE && m->page_size != 2 * PAGE)
+    return fail(nullptr, PIE_EUNSUPPORTED, "page_size %d: the kernels work on blocks of %d tokens and take pages of %d or %d", m->page_size, PAGE, PAGE, 2 * PAGE);
+  const int F = m->page_size / PAGE;  // 16-token blocks per KvPage
   if (m->head_dim != 64 && m->head_dim != 128) return fail(nullptr, PIE_EUNSUPPORTED, "head_dim %d: need 64 or 128", m->head_dim);
   if (m->n_kv_heads <= 0 || m->n_q_heads % m->n_kv_heads != 0 || m->n_q_heads / m->n_kv_heads > 8)
     return fail(nullptr, PIE_EUNSUPPORTED, "need n_q_heads = group * n_kv_heads with group <= 8");
@@ -87,7 +89,7 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
   if (p->max_adapters < 0 || p->max_lora_rank < 0 || (p->max_adapters > 0) != (p->max_lora_rank > 0) ||
       p->max_lora_rank > 1024)
     return fail(nullptr, PIE_EINVAL, "max_adapters and max_lora_rank (<= 1024) must both be 0 or both be positive");
-  if ((int64_t)p->n_kv_pages * m->n_kv_heads > INT32_MAX)
+  if ((int64_t)p->n_kv_pages * F * m->n_kv_heads > INT32_MAX)
     return fail(nullptr, PIE_EUNSUPPORTED, "n_kv_pages * n_kv_heads must fit 31 bits (page-head block indices are int32)");
 
   pie_ctx* c = new pie_ctx();
@@ -102,7 +104,8 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
     c->wave_slots = planner_wave_slots;
     c->layers.resize(m->n_layers);
     c->embed_pos.assign((size_t)p->n_embeds, -1);
-    c->page_mask.assign((size_t)p->n_kv_pages, 0xFFFFu);
+    c->page_mask.assign((size_t)p->n_kv_pages * F, 0xFFFFu);
+    c->blocks_per_page = F;
     if (p->max_adapters > 0) c->lora.assign((size_t)p->max_adapters * m->n_layers * PIE_N_PROJ, LoraPair());
     *out = c;
     return PIE_OK;
@@ -125,7 +128,8 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
   const int H = m->hidden, QD = m->n_q_heads * m->head_dim, KD = m->n_kv_heads * m->head_dim, I = m->mlp_dim;
   const size_t T = (size_t)p->max_batch_tokens;
   c->layers.resize(m->n_layers);
-  c->kv_layer_elems = (size_t)p->n_kv_pages * m->n_kv_heads * 2 * PAGE * m->head_dim;
+  c->blocks_per_page = F;
+  c->kv_layer_elems = (size_t)p->n_kv_pages * F * m->n_kv_heads * 2 * PAGE * m->head_dim;
   auto chk = [&](hipError_t x) { if (e == hipSuccess) e = x; };
   chk(dev_alloc(&c->embeds, (size_t)p->n_embeds * H, true, c->stream));
   chk(dev_alloc(&c->kv, c->kv_layer_elems * m->n_layers, true, c->stream));
@@ -143,7 +147,7 @@ static pie_status pie_create_impl(const pie_model_desc* m, const pie_pool_desc* 
     chk(dev_alloc(&c->lora_z, c->lora_z_rows * 3 * round_up(p->max_lora_rank, 16), false, c->stream));
   }
   c->embed_pos.assign((size_t)p->n_embeds, -1);
-  c->page_mask.assign((size_t)p->n_kv_pages, 0xFFFFu);
+  c->page_mask.assign((size_t)p->n_kv_pages * F, 0xFFFFu);
   chk(dev_alloc(&c->act, T * I, false, c->stream));
   // split-K workspace: only batches of <= 256 rows use it; 8 partial copies of the widest output
   {
@@ -424,6 +428,17 @@ extern "C" pie_status pie_embed_read(pie_ctx* c, const int32_t* ids, int32_t n, 
   return embed_copy(c, ids, n, dst, 0);
 }
 
+// KvPages of 2 x 16 tokens are stored as two consecutive 16-token blocks: page p, slot s -> block 2p + s / 16, slot s % 16.
+static void to_blocks(const pie_ctx* c, const int32_t* pages, const int32_t* slots, int n, std::vector<int32_t>& bp,
+                      std::vector<int32_t>& bs) {
+  bp.resize(n);
+  bs.resize(n);
+  for (int i = 0; i < n; ++i) {
+    bp[i] = pages[i] * c->blocks_per_page + slots[i] / PAGE;
+    bs[i] = slots[i] % PAGE;
+  }
+}
+
 static pie_status kv_copy(pie_ctx* c, int32_t layer, const int32_t* pages, const int32_t* slots, int32_t n, void* k,
                           void* v, int to_pool) {
   if (!c) return PIE_EINVAL;
@@ -433,7 +448,13 @@ static pie_status kv_copy(pie_ctx* c, int32_t layer, const int32_t* pages, const
   if (n == 0) return PIE_OK;
   for (int i = 0; i < n; ++i) {
     if (pages[i] < 0 || pages[i] >= c->p.n_kv_pages) return fail(c, PIE_ERANGE, "page id %d at %d outside [0, %d)", pages[i], i, c->p.n_kv_pages);
-    if (slots[i] < 0 || slots[i] >= PAGE) return fail(c, PIE_ERANGE, "slot %d at %d outside [0, %d)", slots[i], i, PAGE);
+    if (slots[i] < 0 || slots[i] >= c->m.page_size) return fail(c, PIE_ERANGE, "slot %d at %d outside [0, %d)", slots[i], i, c->m.page_size);
+  }
+  std::vector<int32_t> bp, bs;  // pages of two 16-token blocks: (page, slot) -> (block, slot within the block)
+  if (c->blocks_per_page > 1) {
+    to_blocks(c, pages, slots, n, bp, bs);
+    pages = bp.data();
+    slots = bs.data();
   }
   pie_status st = stage_ids(c, pages, slots, n);
   if (st != PIE_OK) return st;
@@ -444,11 +465,11 @@ static pie_status kv_copy(pie_ctx* c, int32_t layer, const int32_t* pages, const
 }
 extern "C" pie_status pie_kv_write(pie_ctx* c, int32_t layer, const int32_t* pages, const int32_t* slots, int32_t n,
                                    const void* k, const void* v) {
-  return kv_copy(c, layer, pages, slots, n, const_cast<void*>(k), const_cast<void*>(v), 1);
+  return guarded(c, "pie_kv_write", [&]() { return kv_copy(c, layer, pages, slots, n, const_cast<void*>(k), const_cast<void*>(v), 1); });
 }
 extern "C" pie_status pie_kv_read(pie_ctx* c, int32_t layer, const int32_t* pages, const int32_t* slots, int32_t n,
                                   void* k, void* v) {
-  return kv_copy(c, layer, pages, slots, n, k, v, 0);
+  return guarded(c, "pie_kv_read", [&]() { return kv_copy(c, layer, pages, slots, n, k, v, 0); });
 }
 
 extern "C" pie_status pie_mask_kvpage(pie_ctx* c, const int32_t* page_ids, const uint32_t* visible_bits, int32_t n) {
@@ -457,7 +478,9 @@ extern "C" pie_status pie_mask_kvpage(pie_ctx* c, const int32_t* page_ids, const
   for (int i = 0; i < n; ++i)
     if (page_ids[i] < 0 || page_ids[i] >= c->p.n_kv_pages)
       return fail(c, PIE_ERANGE, "page id %d at %d outside [0, %d)", page_ids[i], i, c->p.n_kv_pages);
-  for (int i = 0; i < n; ++i) c->page_mask[page_ids[i]] = (uint16_t)(visible_bits[i] & 0xFFFFu);
+  const int F = c->blocks_per_page;
+  for (int i = 0; i < n; ++i)
+    for (int f = 0; f < F; ++f) c->page_mask[(size_t)page_ids[i] * F + f] = (uint16_t)((visible_bits[i] >> (PAGE * f)) & 0xFFFFu);
   return PIE_OK;
 }
 
@@ -468,21 +491,28 @@ static pie_status pie_copy_kvpage_impl(pie_ctx* c, const int32_t* src_pages, con
   if (n < 0 || (n > 0 && (!src_pages || !src_slots || !dst_pages || !dst_slots)))
     return fail(c, PIE_EINVAL, "pie_copy_kvpage: null argument");
   if (n == 0) return PIE_OK;
+  const int PS = c->m.page_size;
   std::unordered_set<int64_t> src, dst;
   src.reserve((size_t)n * 2);
   dst.reserve((size_t)n * 2);
   for (int i = 0; i < n; ++i) {
     if (src_pages[i] < 0 || src_pages[i] >= c->p.n_kv_pages || dst_pages[i] < 0 || dst_pages[i] >= c->p.n_kv_pages)
       return fail(c, PIE_ERANGE, "page id at %d outside [0, %d)", i, c->p.n_kv_pages);
-    if (src_slots[i] < 0 || src_slots[i] >= PAGE || dst_slots[i] < 0 || dst_slots[i] >= PAGE)
-      return fail(c, PIE_ERANGE, "slot at %d outside [0, %d)", i, PAGE);
-    src.insert((int64_t)src_pages[i] * PAGE + src_slots[i]);
-    if (!dst.insert((int64_t)dst_pages[i] * PAGE + dst_slots[i]).second)
+    if (src_slots[i] < 0 || src_slots[i] >= PS || dst_slots[i] < 0 || dst_slots[i] >= PS)
+      return fail(c, PIE_ERANGE, "slot at %d outside [0, %d)", i, PS);
+    src.insert((int64_t)src_pages[i] * PS + src_slots[i]);
+    if (!dst.insert((int64_t)dst_pages[i] * PS + dst_slots[i]).second)
       return fail(c, PIE_ECONFLICT, "token (page %d, slot %d) is written twice by one copy", dst_pages[i], dst_slots[i]);
   }
   for (int64_t t : dst)
     if (src.count(t)) return fail(c, PIE_ECONFLICT, "token (page %lld, slot %lld) is both read and written by one copy",
-                                  (long long)(t / PAGE), (long long)(t % PAGE));
+                                  (long long)(t / PS), (long long)(t % PS));
+  std::vector<int32_t> sbp, sbs, dbp, dbs;
+  if (c->blocks_per_page > 1) {
+    to_blocks(c, src_pages, src_slots, n, sbp, sbs);
+    to_blocks(c, dst_pages, dst_slots, n, dbp, dbs);
+    src_pages = sbp.data(); src_slots = sbs.data(); dst_pages = dbp.data(); dst_slots = dbs.data();
+  }
   const int32_t* arrs[4] = {src_pages, src_slots, dst_pages, dst_slots};
   if ((size_t)n * 4 > c->ids_cap) {
     (void)hipStreamSynchronize(c->stream);
@@ -564,6 +594,31 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   if (b->tok_indptr[0] != 0 || b->tok_indptr[R] != T) return fail(c, PIE_EINVAL, "tok_indptr must run from 0 to n_tokens");
   if (b->page_indptr[0] != 0) return fail(c, PIE_EINVAL, "page_indptr must start at 0");
 
+  // KvPages of 32 tokens are two consecutive 16-token blocks of the pool: the page tables are rewritten in blocks
+  // (page p -> blocks 2p, 2p + 1) and everything below, like the kernels, works on 16-token blocks.
+  const int F = c->blocks_per_page;
+  const int n_pool_blocks = c->p.n_kv_pages * F;
+  std::vector<int32_t> blk_indptr, blk_ids;
+  pie_forward_batch in_blocks;
+  if (F > 1) {
+    blk_indptr.assign(R + 1, 0);
+    for (int r = 0; r < R; ++r) {
+      const int p0 = b->page_indptr[r], p1 = b->page_indptr[r + 1];
+      if (p1 < p0) return fail(c, PIE_EINVAL, "bad page_indptr");
+      const int need = (b->kv_len[r] + c->m.page_size - 1) / c->m.page_size;
+      if (p1 - p0 < need) return fail(c, PIE_EINVAL, "request %d: %d pages listed, kv_len %d needs %d", r, p1 - p0, b->kv_len[r], need);
+      for (int p = p0; p < p1; ++p) {
+        if (b->page_ids[p] < 0 || b->page_ids[p] >= c->p.n_kv_pages)
+          return fail(c, PIE_ERANGE, "request %d: page id %d outside [0, %d)", r, b->page_ids[p], c->p.n_kv_pages);
+        for (int f = 0; f < F; ++f) blk_ids.push_back(b->page_ids[p] * F + f);
+      }
+      blk_indptr[r + 1] = (int32_t)blk_ids.size();
+    }
+    in_blocks = *b;
+    in_blocks.page_indptr = blk_indptr.data();
+    in_blocks.page_ids = blk_ids.data();
+    b = &in_blocks;
+  }
   std::vector<int32_t> tok_adapter;  // host only: adapter of each token's request
   std::vector<int32_t> used_adapters, lora_rows, lora_tile_ad;
   if (b->adapter_ids) {
@@ -595,8 +650,8 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     const int n_pages = (L + PAGE - 1) / PAGE;
     if (p1 - p0 < n_pages) return fail(c, PIE_EINVAL, "request %d: %d pages listed, kv_len %d needs %d", r, p1 - p0, L, n_pages);
     for (int p = p0; p < p1; ++p)
-      if (b->page_ids[p] < 0 || b->page_ids[p] >= c->p.n_kv_pages)
-        return fail(c, PIE_ERANGE, "request %d: page id %d outside [0, %d)", r, b->page_ids[p], c->p.n_kv_pages);
+      if (b->page_ids[p] < 0 || b->page_ids[p] >= n_pool_blocks)
+        return fail(c, PIE_ERANGE, "request %d: page id %d outside [0, %d)", r, b->page_ids[p], n_pool_blocks);
     ReqInfo& q = reqs[r];
     q.tok0 = t0; q.n_new = n_new; q.kv_len = L;
     q.visit0 = (int32_t)visit_phys.size();
@@ -855,7 +910,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
     }
     if (filled > 0) close_wave();
     // the kernel trusts this plan: check what it assumes before anything is launched from it
-    const int64_t n_blocks = (int64_t)c->p.n_kv_pages * Hkv;
+    const int64_t n_blocks = (int64_t)n_pool_blocks * Hkv;
     for (size_t w = 0; w < dwaves.size(); ++w) {
       const DecodeWave& dw = dwaves[w];
       int pairs = 0;
@@ -976,7 +1031,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   pb->rows_cap = std::max(rows_cap, 1);
   pb->work[0] = kv_bytes; pb->work[1] = kv_bytes_dec; pb->work[2] = flops; pb->work[3] = (int64_t)visit_phys.size();
   {  // distinct pages the decode path visits: a stamp per pool page kept in the context (no clearing, no hashing)
-    if (c->page_stamp.size() != (size_t)c->p.n_kv_pages) c->page_stamp.assign(c->p.n_kv_pages, 0u);
+    if (c->page_stamp.size() != (size_t)n_pool_blocks) c->page_stamp.assign(n_pool_blocks, 0u);
     if (++c->page_stamp_id == 0u) {  // wrapped: start over
       std::fill(c->page_stamp.begin(), c->page_stamp.end(), 0u);
       c->page_stamp_id = 1u;

@@ -176,3 +176,54 @@ def test_kvpage_error_codes():
     _, stored, y = gpu_forward(ctx, w)  # still usable
     res = O.forward(w.model, w.weights, *oracle_pools(w), w.batch, round_intermediates=True)
     assert_close(dec(y), res.y[stored], "after errors")
+
+
+# ---------------------------------------------------------------- KvPages of 32 tokens
+def test_pages_of_32_tokens_forward_masks_and_copies():
+    """KvPages of 32 tokens (stored as two 16-token blocks): a ragged mixed batch with bitmaps, a shared prefix,
+    token-level page masks over all 32 slots and token-level copies across the two halves of a page, all against the
+    oracle, which takes the page size as it is."""
+    m = W.ModelDesc(hidden=128, n_q_heads=8, n_kv_heads=2, head_dim=128, mlp_dim=256, vocab=512, page_size=32,
+                    rms_eps=1e-5, rope_theta=1e4, n_layers=1)
+    P = 32
+    reqs = [W.RequestSpec(1, 70), W.RequestSpec(1, 31), W.RequestSpec(1, 32, mask=W.causal_bitmap),
+            W.RequestSpec(2, 100, mask=random_mask(0.5)), W.RequestSpec(45, 37), W.RequestSpec(35, 0, mask=W.causal_bitmap),
+            W.RequestSpec(1, 2 * P + 3, prefix_group=0, prefix_len=2 * P),
+            W.RequestSpec(1, 2 * P + 40, prefix_group=0, prefix_len=2 * P),
+            W.RequestSpec(1, 700, mask=random_mask(0.02)), W.RequestSpec(1, 15, in_place=True)]
+    w = W.build_workload("p32", m, reqs, n_kv_pages=64, seed=930, std=0.05, top_k=8)
+    b = w.batch
+    ctx = make_ctx(w)
+    # pool round trip through (page, slot) with slots up to 31
+    k0, v0 = ctx.kv_read(0, w.prior.page_ids, w.prior.slots)
+    assert np.array_equal(k0, w.prior.k_bits) and np.array_equal(v0, w.prior.v_bits) and w.prior.slots.max() == 31
+    rng = np.random.default_rng(5)
+    pages = np.unique(b.page_ids)[::2].astype(np.int32)
+    bits = rng.integers(0, 1 << 32, size=len(pages), dtype=np.uint64).astype(np.uint32)
+    bits[0] = 0xFFFF0000  # the lower half of a page hidden, the upper half visible
+    ctx.mask_kvpage(pages, bits)
+    kv, emb = oracle_pools(w)
+    O.mask_kvpage([kv], pages, bits)
+    # token-level copies from a prior page into a spare one, crossing the 16-token halves
+    spare = int(np.setdiff1d(np.arange(w.n_kv_pages), b.page_ids)[0])
+    src_page = int(b.page_ids[0])
+    ss = np.array([3, 15, 16, 31], np.int32)
+    ds = np.array([16, 0, 31, 15], np.int32)
+    sp, dp = np.full(4, src_page, np.int32), np.full(4, spare, np.int32)
+    ctx.copy_kvpage(sp, ss, dp, ds)
+    O.copy_kvpage([kv], sp, ss, dp, ds)
+    gk, gv = ctx.kv_read(0, dp, ds)
+    ok, ov = kv.read(dp, ds)
+    assert np.array_equal(gk, ok) and np.array_equal(gv, ov)
+    pb, stored, y_bits = gpu_forward(ctx, w)
+    res = O.forward(m, w.weights, kv, emb, b, round_intermediates=True)
+    assert_close(dec(y_bits), res.y[stored], "pages of 32 tokens: y")
+    from gpu_helpers import appended_positions, assert_bf16_close
+    ap, asl = appended_positions(w)
+    k_gpu, v_gpu = ctx.kv_read(0, ap, asl)
+    assert_bf16_close(k_gpu, res.k_new, "pages of 32 tokens: appended K", ulps=2)
+    assert_bf16_close(v_gpu, res.v_new, "pages of 32 tokens: appended V", ulps=2)
+    # the shared prefix is still read once for both requests
+    work = pb.work()
+    assert work["kv_bytes_requested"] < work["kv_bytes_decode"]
+    ctx.close()

@@ -1,5 +1,6 @@
 """Host logic of the library without a GPU: batch deserialisation, its error codes and the attention launch plan,
 through a planner context (pie_create_planner makes no HIP call)."""
+import copy
 import numpy as np
 import pytest
 
@@ -305,3 +306,40 @@ def test_a_batch_belongs_to_the_context_that_created_it():
     pb.destroy()
     a.close()
     b.close()
+
+
+def test_pages_of_32_tokens_plan_like_two_blocks_of_16():
+    """A KvPage of 32 tokens is two consecutive 16-token blocks: the plan of a batch over pages of 32 equals the plan
+    of the same requests over pages of 16 whose tables name blocks 2p, 2p + 1; page sizes other than 16 and 32 are
+    refused."""
+    m32 = W.ModelDesc(hidden=128, n_q_heads=8, n_kv_heads=2, head_dim=128, mlp_dim=256, vocab=0, page_size=32)
+    reqs = [W.RequestSpec(1, 70), W.RequestSpec(1, 31, mask=W.causal_bitmap), W.RequestSpec(45, 37),
+            W.RequestSpec(1, 67, prefix_group=0, prefix_len=64), W.RequestSpec(1, 90, prefix_group=0, prefix_len=64),
+            W.RequestSpec(1, 600, mask=W.sink_window_mask(4, 40))]
+    w32 = W.build_workload("p32", m32, reqs, n_kv_pages=64, seed=12, with_head=False)
+    b32 = w32.batch
+    b16 = copy.copy(b32)
+    b16.page_ids = np.stack([b32.page_ids * 2, b32.page_ids * 2 + 1], axis=1).reshape(-1).astype(np.int32)
+    b16.page_indptr = (b32.page_indptr * 2).astype(np.int32)
+    m16 = copy.copy(m32)
+    m16.page_size = 16
+    c32 = Pie.planner(m32, 64, w32.n_embeds, int(b32.n_tokens), int(b32.n_requests))
+    c16 = Pie.planner(m16, 128, w32.n_embeds, int(b32.n_tokens), int(b32.n_requests))
+    p32, p16 = c32.batch_create(b32, validate=True), c16.batch_create(b16, validate=True)
+    assert p32.work() == p16.work() and p32.plan_info() == p16.plan_info()
+    assert (p32.prefill_work() == p16.prefill_work()).all()
+    # a page mask over all 32 slots hides the same tokens as the two 16-bit halves on the blocks
+    c32.mask_kvpage([int(b32.page_ids[0])], [0xFFFF0000])
+    c16.mask_kvpage([int(b32.page_ids[0]) * 2, int(b32.page_ids[0]) * 2 + 1], [0x0000, 0xFFFF])
+    q32, q16 = c32.batch_create(b32), c16.batch_create(b16)
+    assert q32.work() == q16.work() and q32.work() != p32.work()
+    for pb in (p32, p16, q32, q16):
+        pb.destroy()
+    c32.close()
+    c16.close()
+    for bad in (8, 24, 48):
+        mb = copy.copy(m32)
+        mb.page_size = bad
+        with pytest.raises(PieError) as e:
+            Pie.planner(mb, 64, 64, 8, 8)
+        assert e.value.status == -7
