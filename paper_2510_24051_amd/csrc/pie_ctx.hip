@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <unordered_map>
 #include <unordered_set>
 
 #include "internal.h"
@@ -941,7 +942,16 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   // query blocks of one (request, kv head) read the same K/V pages, so they go to one XCD, next to each other in
   // its list (heavy blocks first), and that XCD's L2 serves all but the first read of a page.  The groups are
   // spread over the XCDs by cost, largest first onto the least loaded; while that leaves the XCDs uneven, groups
-  // are cut into interleaved parts.  Lists are padded with empty slots to one length and interleaved.
+  // are cut into interleaved parts.  Requests whose page tables begin with the same physical page (a shared
+  // prefix) form one family: the groups of a family for one kv head follow the family's first group onto its XCD
+  // and sit next to each other there, so the shared K/V pages come from HBM once and from that L2 afterwards.
+  // Lists are padded with empty slots to one length and interleaved.
+  std::vector<int32_t> family(R);  // the first request whose visit list starts with the same physical block
+  {
+    std::unordered_map<int32_t, int32_t> first_with;
+    for (int r = 0; r < R; ++r)
+      family[r] = reqs[r].n_visit > 0 ? first_with.emplace(visit_phys[reqs[r].visit0], r).first->second : r;
+  }
   auto pcost = [&](const PrefillItem& it) {
     const ReqInfo& q = reqs[it.r];
     return q.wpr ? (int64_t)q.n_visit * PAGE : (int64_t)(q.kv_len - q.n_new + std::min(q.n_new, it.qb * 32 + 32));
@@ -960,7 +970,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
   std::vector<PrefillItem> pwork;
   if (!pitems.empty()) {
     constexpr int N_XCD = 8;
-    struct Unit { int32_t first, count, hk, part; int64_t cost; };
+    struct Unit { int32_t first, count, hk, part; int64_t cost; int32_t fam, order; };
     std::vector<int32_t> lists[N_XCD];
     for (int parts = 1;; parts *= 2) {
       std::vector<Unit> units;
@@ -974,7 +984,7 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
           for (int pt = 0; pt < parts; ++pt) {
             int64_t cst = 0;
             for (size_t i = i0 + pt; i < i1; i += parts) cst += pcost(pitems[i]) + 64;
-            if (cst > 0) units.push_back(Unit{(int32_t)i0, (int32_t)(i1 - i0), hk, pt, cst});
+            if (cst > 0) units.push_back(Unit{(int32_t)i0, (int32_t)(i1 - i0), hk, pt, cst, family[pitems[i0].r], 0});
           }
         i0 = i1;
       }
@@ -982,12 +992,24 @@ static pie_status pie_batch_create_impl(pie_ctx* c, const pie_forward_batch* b, 
       int64_t load[N_XCD] = {0}, total = 0;
       for (auto& l : lists) l.clear();
       std::vector<Unit> per_xcd[N_XCD];
-      for (const Unit& u : units) {
+      std::unordered_map<int64_t, std::pair<int, int>> home;  // (family, kv head, part) -> (XCD, rank on that XCD)
+      for (Unit u : units) {
+        const int64_t key = ((int64_t)u.fam * Hkv + u.hk) * parts + u.part;
+        auto it = home.find(key);
         int best = 0;
-        for (int x = 1; x < N_XCD; ++x) if (load[x] < load[best]) best = x;
+        if (it != home.end()) {
+          best = it->second.first;
+          u.order = it->second.second;
+        } else {
+          for (int x = 1; x < N_XCD; ++x) if (load[x] < load[best]) best = x;
+          u.order = (int)per_xcd[best].size();
+          home.emplace(key, std::make_pair(best, u.order));
+        }
         load[best] += u.cost; total += u.cost;
         per_xcd[best].push_back(u);
       }
+      for (auto& v : per_xcd)  // a family's groups next to each other, families in the order their first group arrived
+        std::stable_sort(v.begin(), v.end(), [](const Unit& x, const Unit& y) { return x.order < y.order; });
       const int64_t worst = *std::max_element(load, load + N_XCD);
       if (worst * N_XCD > total + total / 8 && parts < longest) continue;  // more than 1/8 over the mean: cut finer
       pwork.clear();

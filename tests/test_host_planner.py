@@ -343,3 +343,35 @@ def test_pages_of_32_tokens_plan_like_two_blocks_of_16():
         with pytest.raises(PieError) as e:
             Pie.planner(mb, 64, 64, 8, 8)
         assert e.value.status == -7
+
+
+def test_prefill_requests_over_a_shared_prefix_share_an_xcd():
+    """Prefill requests whose page tables begin with the same physical pages (a shared prefix): for every kv head
+    their query blocks all run on one XCD, next to each other in its list, so the prefix's K/V pages are fetched
+    from HBM once and served by that XCD's L2 afterwards; unrelated requests spread as before."""
+    m = small_model(128, 16, 8)
+    fam = [W.RequestSpec(96, 512 + 16 * i, prefix_group=0, prefix_len=512) for i in range(5)]
+    fam2 = [W.RequestSpec(64, 256, prefix_group=1, prefix_len=256) for i in range(3)]
+    solo = [W.RequestSpec(128, 300 + 40 * i) for i in range(24)]
+    reqs = solo[:10] + fam + solo[10:] + fam2
+    pages = sum((r.n_new + r.prior_len + 15) // 16 for r in reqs) + 8
+    w = W.build_workload("fam", m, reqs, n_kv_pages=pages, seed=4300, std=0.02, with_head=False)
+    ctx = planner_for(w)
+    pb = ctx.batch_create(w.batch, validate=True)
+    info = pb.plan_info()
+    work = pb.prefill_work()[:info["prefill_workgroups"]]
+    fam_of = {10 + i: "a" for i in range(5)}
+    fam_of.update({len(reqs) - 3 + i: "b" for i in range(3)})
+    xcds, load = {}, np.zeros(8)
+    for i, (r, qb, hk) in enumerate(work.tolist()):
+        if r >= 0:
+            xcds.setdefault((fam_of.get(r, r), hk), set()).add(i % 8)
+            load[i % 8] += 1
+    assert all(len(v) == 1 for v in xcds.values()), {k: v for k, v in xcds.items() if len(v) > 1}
+    assert load.max() <= 1.3 * load.mean()
+    for x in range(8):  # a family's blocks for one kv head are contiguous in the XCD's list
+        seq = [(fam_of.get(int(r), int(r)), int(h)) for r, q, h in work[x::8] if r >= 0]
+        changes = sum(1 for a, c in zip(seq, seq[1:]) if a != c)
+        assert changes == len(set(seq)) - 1
+    pb.destroy()
+    ctx.close()
