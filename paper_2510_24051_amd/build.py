@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpie_mi355.so")
+PROBE = os.path.join(HERE, "pie_probe")  # stand-alone microbenchmarks of the chip's ceilings (csrc/probe_ceilings.hip)
 SOURCES = ["pie_ctx.hip", "gemm.hip", "attention.hip", "elementwise.hip", "dist.hip", "lora.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -37,8 +38,12 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    r = subprocess.run([hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", os.path.join(CSRC, "probe_ceilings.hip"),
+                        "-o", PROBE], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for probe_ceilings.hip:\n{r.stdout}\n{r.stderr}")
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {PROBE}")
     return LIB
 
 
