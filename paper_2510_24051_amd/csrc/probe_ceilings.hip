@@ -156,19 +156,30 @@ __global__ __launch_bounds__(512) void lds_kernel(unsigned* out, int iters) {
   if (acc.x == 0x12345 && acc.y == 77) out[tid] = acc.z;
 }
 
-// 5: every wave chains MFMAs on four independent accumulators, operands fixed in registers
+// 5: every wave chains MFMAs on four independent accumulators, operands fixed in registers.  RANDOM: the four MFMAs of
+// a round take four different operand pairs of hashed, roughly unit-scale values of both signs, so consecutive MFMAs
+// toggle the operand paths the way a contraction over real data does; otherwise one pair of small smooth values.
+template <bool RANDOM>
 __global__ __launch_bounds__(512) void mfma_kernel(float* out, int iters) {
-  bf16x8 a, b;
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(0.001f * (threadIdx.x + i));
-    b[i] = (__bf16)(0.002f * (threadIdx.x - i));
-  }
+  bf16x8 a[4], b[4];
+  for (int j = 0; j < 4; ++j)
+    for (int i = 0; i < 8; ++i) {
+      if (RANDOM) {
+        unsigned h = (threadIdx.x * 8 + i) * 2654435761u + j * 40503u + blockIdx.x * 97u;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        a[j][i] = (__bf16)(((int)(h & 0xFFFF) - 32768) * (1.0f / 16384.0f));
+        b[j][i] = (__bf16)(((int)(h >> 16) - 32768) * (1.0f / 16384.0f));
+      } else {
+        a[j][i] = (__bf16)(0.001f * (threadIdx.x + i));
+        b[j][i] = (__bf16)(0.002f * (threadIdx.x - i));
+      }
+    }
   f32x16 c[4];
   for (int j = 0; j < 4; ++j)
     for (int v = 0; v < 16; ++v) c[j][v] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[j], 0, 0, 0);
+    for (int j = 0; j < 4; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], c[j], 0, 0, 0);
   }
   float s = 0.f;
   for (int j = 0; j < 4; ++j)
@@ -257,10 +268,14 @@ int main() {
     float* out;
     CHECK(hipMalloc(&out, 1 << 16));
     const int iters = 200000;
-    const float ms = best_ms([&] { mfma_kernel<<<cus, 512>>>(out, iters); }, 3);
-    const double flops = (double)cus * 8 * iters * 4 * 2.0 * 32 * 32 * 16;
-    printf("bf16 MFMA 32x32x16 on registers: %.0f TFLOP/s (%.1f%% of 2500); at 32 cycles per MFMA and SIMD that is a clock of %.2f GHz\n",
-           flops / ms / 1e9, flops / ms / 1e9 / 25.0, (double)iters * 4 * 2 * 32 / (ms * 1e6));
+    for (int random = 0; random < 2; ++random) {
+      const float ms = random ? best_ms([&] { mfma_kernel<true><<<cus, 512>>>(out, iters); }, 3)
+                              : best_ms([&] { mfma_kernel<false><<<cus, 512>>>(out, iters); }, 3);
+      const double flops = (double)cus * 8 * iters * 4 * 2.0 * 32 * 32 * 16;
+      printf("bf16 MFMA 32x32x16 on registers, %s: %.0f TFLOP/s (%.1f%% of 2500); at 32 cycles per MFMA and SIMD that is a clock of %.2f GHz\n",
+             random ? "hashed operands of both signs, four pairs in rotation" : "one pair of small smooth operands",
+             flops / ms / 1e9, flops / ms / 1e9 / 25.0, (double)iters * 4 * 2 * 32 / (ms * 1e6));
+    }
     CHECK(hipFree(out));
   }
   CHECK(hipDeviceSynchronize());
