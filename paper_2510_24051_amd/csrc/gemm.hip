@@ -721,6 +721,13 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
   // next weight stream pushes it out to HBM; beyond 8 splits that costs more than the extra workgroups gain
   // (c2 forward -2.5 us, c5 -8 us against 16 and 12 splits).
   if (splits > max_splits) splits = max_splits;
+  // The QKV product does as well with half as many splits while three quarters of the CUs still get a workgroup
+  // (8B shape at 64 rows: the same 18 us with 192 workgroups as with 384; 70B shape at 16 rows: 36 against 37 us),
+  // and every split less is an M x N partial less for the rotary step to read and to be written out of the caches
+  // underneath the attention kernel (8B: -1.5 and -1 us).  The output and down projections lose more than the
+  // kernels after them gain (70B shape: +2 and +8 us), so they keep their splits.
+  if (MODE == EPI_STORE_BF16)
+    while (splits >= 4 && splits % 2 == 0 && wg_n * (splits / 2) * 4 >= n_cus * 3) splits /= 2;
   if (splits < 1) splits = 1;
   const int NP = W.NB * 32;
   while (splits > 1 && (size_t)splits * M * NP > ws_elems) --splits;

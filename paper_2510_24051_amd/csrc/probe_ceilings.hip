@@ -235,6 +235,46 @@ int main() {
     const double bytes = (double)bl.size() * 8192;
     printf("gather of %d (page, head) blocks of 8 KiB, %d waves x %d pairs: %.0f GB/s (%.1f%% of 8000), %.1f us for %.1f MB\n",
            (int)bl.size(), n_waves, per, bytes / ms / 1e6, bytes / ms / 1e6 / 80.0, ms * 1e3, bytes / 1e6);
+    // the same gather right after other kernels have streamed 1.5 GiB of other memory (what a serving step does
+    // between two decode-attention launches: weights and the LM head), and right after a kernel has written 16 MiB
+    {
+      unsigned char* other;
+      CHECK(hipMalloc(&other, (size_t)1536 << 20));
+      fill_kernel<<<2048, 256>>>((unsigned int*)other, ((size_t)1536 << 20) / 4);
+      CHECK(hipDeviceSynchronize());
+      float best_after_read = 1e30f, sum_after_read = 0.f, best_after_write = 1e30f;
+      const int reps = 6;
+      for (int r = 0; r < reps; ++r) {
+        read_kernel<<<8192, 256>>>((const u32x4*)other, ((size_t)1536 << 20) / 16, sink);
+        CHECK(hipEventRecord(g_e0));
+        gather_kernel<<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
+        CHECK(hipEventRecord(g_e1));
+        CHECK(hipEventSynchronize(g_e1));
+        float t;
+        CHECK(hipEventElapsedTime(&t, g_e0, g_e1));
+        best_after_read = std::min(best_after_read, t);
+        sum_after_read += t;
+      }
+      printf("the same gather right after a 1.5 GiB read of other memory: %.1f us (best), %.1f us (mean of %d)\n",
+             best_after_read * 1e3, sum_after_read / reps * 1e3, reps);
+      printf("the same gather right after a kernel that wrote");
+      for (size_t kib : {64, 1024, 4096, 16384, 65536}) {
+        best_after_write = 1e30f;
+        for (int r = 0; r < reps; ++r) {
+          fill_kernel<<<(unsigned)std::min<size_t>(2048, kib), 256>>>((unsigned int*)other, (kib << 10) / 4);
+          CHECK(hipEventRecord(g_e0));
+          gather_kernel<<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
+          CHECK(hipEventRecord(g_e1));
+          CHECK(hipEventSynchronize(g_e1));
+          float t;
+          CHECK(hipEventElapsedTime(&t, g_e0, g_e1));
+          best_after_write = std::min(best_after_write, t);
+        }
+        printf(" %zu KiB: %.1f us;", kib, best_after_write * 1e3);
+      }
+      printf(" (best of %d each)\n", reps);
+      CHECK(hipFree(other));
+    }
     CHECK(hipFree(d));
   }
   // 3. re-read of buffers that fit the caches (five passes after one that brings the buffer in)
