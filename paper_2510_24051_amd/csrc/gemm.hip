@@ -21,13 +21,18 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 // three dependent memory round trips instead of one per element.
 // FULL: all 32 rows of the tile exist (the caller's uniform test), so no per-row predicates are needed; with them
 // every element is its own predicated block and the loads cannot be batched.
-template <int MODE, bool FULL = false>
+// NT: non-temporal stores (see gemm_skinny_kernel).
+template <int MODE, bool FULL = false, bool NT = false>
 __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, const f32x16& acc2, int m0, int n0,
                                          int M_rows, int N, int lane) {
   const int M = FULL ? 0x7fffffff : M_rows;
   const int n = n0 + (lane & 31);
   const int g = lane >> 5;
   if (n >= N) return;
+  auto st = [](auto* p, auto v) {
+    if (NT) store_nt(p, v);
+    else *p = v;
+  };
   int rows[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) rows[v] = m0 + (v >> 2) * 8 + g * 4 + (v & 3);
@@ -35,18 +40,18 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
     bf16_t* out = reinterpret_cast<bf16_t*>(e.out);
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = f32_to_bf16(acc[v]);
+      if (rows[v] < M) st(out + (int64_t)rows[v] * e.ldo + n, f32_to_bf16(acc[v]));
   } else if (MODE == EPI_STORE_F32) {
     float* out = reinterpret_cast<float*>(e.out);
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = acc[v];
+      if (rows[v] < M) st(out + (int64_t)rows[v] * e.ldo + n, acc[v]);
   } else if (MODE == EPI_SWIGLU) {  // acc = gate block, acc2 = up block; n0 is the gate block's packed column
     bf16_t* out = reinterpret_cast<bf16_t*>(e.out);
     const int nc = (n0 >> 1) + (lane & 31);
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + nc] = f32_to_bf16(silu_f(acc[v]) * acc2[v]);
+      if (rows[v] < M) st(out + (int64_t)rows[v] * e.ldo + nc, f32_to_bf16(silu_f(acc[v]) * acc2[v]));
   } else if (MODE == EPI_RESID_EMBED) {
     float r[16];
     if (e.resid != nullptr) {  // wide residual stream of an inner layer
@@ -62,7 +67,7 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
     float* out = reinterpret_cast<float*>(e.out);
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = r[v] + acc[v];
+      if (rows[v] < M) st(out + (int64_t)rows[v] * e.ldo + n, r[v] + acc[v]);
   } else if (MODE == EPI_RESID_OUT) {
     float r[16];
     if (e.out != nullptr) {  // inner layer: the sum stays wide and feeds the next layer
@@ -71,7 +76,7 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
       float* out = reinterpret_cast<float*>(e.out);
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        if (rows[v] < M) out[(int64_t)rows[v] * e.ldo + n] = r[v] + acc[v];
+        if (rows[v] < M) st(out + (int64_t)rows[v] * e.ldo + n, r[v] + acc[v]);
     } else {
       int id[16];
 #pragma unroll
@@ -80,7 +85,7 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
       for (int v = 0; v < 16; ++v) r[v] = id[v] >= 0 ? e.resid[(int64_t)rows[v] * e.H + n] : 0.f;
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        if (id[v] >= 0) e.embeds[(int64_t)id[v] * e.H + n] = f32_to_bf16(r[v] + acc[v]);
+        if (id[v] >= 0) st(e.embeds + (int64_t)id[v] * e.H + n, f32_to_bf16(r[v] + acc[v]));
     }
   }
 }
@@ -96,6 +101,11 @@ template <int MB, int MODE, bool PARTIAL, int NBW, int WAVES = 4>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                           const bf16_t* __restrict__ Wp, int N, int NB, int K,
                                                           int iters_per_split, EpiArgs epi, float* __restrict__ part) {
+  // Non-temporal stores for what is written just before a kernel that streams from HBM for a long time: the QKV sums
+  // (a small rotary kernel, then decode attention) and the LM head's own logits (33 MB at 64 rows, which otherwise
+  // compete with its weight stream: 205 -> 193 us).  The other products are followed by a small kernel that reads
+  // what they wrote at once, and that one is a microsecond or two slower when the lines have left the caches.
+  constexpr bool SK_NT = MODE == EPI_STORE_BF16 || MODE == EPI_STORE_F32 || (PARTIAL && MODE == EPI_RESID_OUT);
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);  // [2][MB*32][SK_BK], 16-byte chunks swizzled by row
   constexpr int BM = MB * 32;
@@ -232,7 +242,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
         f32x16 up;
 #pragma unroll
         for (int v = 0; v < 16; ++v) up[v] = xch[((pair * MB + i) * 16 + v) * 64 + lane];
-        epi_tile<MODE>(epi, acc[0][i], up, i * 32, nb0 * 32, M, NB * 32, lane);
+        epi_tile<MODE, false, SK_NT>(epi, acc[0][i], up, i * 32, nb0 * 32, M, NB * 32, lane);
       }
     }
     return;
@@ -248,17 +258,21 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           int m = i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          if (m < M && nb0 + j < NB) P[(int64_t)m * (NB * 32) + (nb0 + j) * 32 + (lane & 31)] = acc[j][i][v];
+          if (m < M && nb0 + j < NB) {
+            float* dst = P + (int64_t)m * (NB * 32) + (nb0 + j) * 32 + (lane & 31);
+            if (SK_NT) store_nt(dst, acc[j][i][v]);
+            else *dst = acc[j][i][v];
+          }
         }
   } else {
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
       if (MODE == EPI_SWIGLU) {
-        epi_tile<MODE>(epi, acc[0][i], acc[NBW - 1][i], i * 32, nb0 * 32, M, NB * 32, lane);
+        epi_tile<MODE, false, SK_NT>(epi, acc[0][i], acc[NBW - 1][i], i * 32, nb0 * 32, M, NB * 32, lane);
       } else {
 #pragma unroll
         for (int j = 0; j < NBW; ++j)
-          if (nb0 + j < NB) epi_tile<MODE>(epi, acc[j][i], acc[j][i], i * 32, (nb0 + j) * 32, M, N, lane);
+          if (nb0 + j < NB) epi_tile<MODE, false, SK_NT>(epi, acc[j][i], acc[j][i], i * 32, (nb0 + j) * 32, M, N, lane);
       }
     }
   }

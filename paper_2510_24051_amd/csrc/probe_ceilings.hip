@@ -57,6 +57,17 @@ __global__ void fill_kernel(unsigned int* p, size_t n) {
   }
 }
 
+// the same fill with non-temporal stores (the lines are not meant to stay in the caches)
+__global__ void fill_nt_kernel(unsigned int* p, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    unsigned int x = (unsigned int)i * 2654435761u;
+    x ^= x >> 15;
+    __builtin_nontemporal_store(x * 2246822519u, p + i);
+  }
+}
+
 // 1, 3: every thread reads 16 bytes per step, a wave 1 KiB contiguous, eight steps in flight
 __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src, size_t n_vec, u32x4* __restrict__ sink) {
   const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
@@ -273,6 +284,36 @@ int main() {
         printf(" %zu KiB: %.1f us;", kib, best_after_write * 1e3);
       }
       printf(" (best of %d each)\n", reps);
+      printf("the same with non-temporal stores in the writing kernel:");
+      for (size_t kib : {1024, 4096, 16384, 65536}) {
+        best_after_write = 1e30f;
+        float best_fill = 1e30f, best_fill_nt = 1e30f;
+        for (int r = 0; r < reps; ++r) {
+          CHECK(hipEventRecord(g_e1));
+          fill_nt_kernel<<<(unsigned)std::min<size_t>(2048, kib), 256>>>((unsigned int*)other, (kib << 10) / 4);
+          CHECK(hipEventRecord(g_e0));
+          gather_kernel<<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
+          hipEvent_t e2;
+          CHECK(hipEventCreate(&e2));
+          CHECK(hipEventRecord(e2));
+          CHECK(hipEventSynchronize(e2));
+          float t, tf;
+          CHECK(hipEventElapsedTime(&t, g_e0, e2));
+          CHECK(hipEventElapsedTime(&tf, g_e1, g_e0));
+          CHECK(hipEventDestroy(e2));
+          best_after_write = std::min(best_after_write, t);
+          best_fill_nt = std::min(best_fill_nt, tf);
+          CHECK(hipEventRecord(g_e1));
+          fill_kernel<<<(unsigned)std::min<size_t>(2048, kib), 256>>>((unsigned int*)other, (kib << 10) / 4);
+          CHECK(hipEventRecord(g_e0));
+          CHECK(hipEventSynchronize(g_e0));
+          CHECK(hipEventElapsedTime(&tf, g_e1, g_e0));
+          best_fill = std::min(best_fill, tf);
+        }
+        printf(" %zu KiB: gather %.1f us (the fill itself %.1f us, with plain stores %.1f us);", kib, best_after_write * 1e3,
+               best_fill_nt * 1e3, best_fill * 1e3);
+      }
+      printf("\n");
       CHECK(hipFree(other));
     }
     CHECK(hipFree(d));
