@@ -485,6 +485,11 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
   const int wm = wave >> 2, wn = wave & 3;
   const int KB = K / 16, KT = K / LG_BK;
   // split K: workgroup row blockIdx.y takes k tiles [kt0, kt1)
+  // Non-temporal stores for the logits and for the partial sums of the down projection, the last product before the
+  // LM head (see gemm_skinny_kernel; LM head at 128 rows 259 -> 238 us, at 256 rows 278 -> 262 us).  The partial sums
+  // of the QKV product are stored plainly here: at 65 to 256 rows the rotary step that sums them loses what the
+  // attention kernel gains.
+  constexpr bool LG_NT = MODE == EPI_STORE_F32 || (PARTIAL && MODE == EPI_RESID_OUT) || (!PARTIAL && MODE == EPI_SWIGLU);
   const int kt0 = PARTIAL ? blockIdx.y * kts_per_split : 0;
   const int kt1 = PARTIAL ? min(KT, kt0 + kts_per_split) : KT;
   int pid = blockIdx.x;
@@ -623,7 +628,11 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          if (m < M && nb < NB) P[(int64_t)m * NP + nb * 32 + (lane & 31)] = acc[i][j][v];
+          if (m < M && nb < NB) {
+            float* dst = P + (int64_t)m * NP + nb * 32 + (lane & 31);
+            if (LG_NT) store_nt(dst, acc[i][j][v]);
+            else *dst = acc[i][j][v];
+          }
         }
       }
     return;
@@ -637,12 +646,12 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
       const int mt = m0 + wm * (BM / 2) + i * 32;
       if (MODE == EPI_SWIGLU) {
         int nb = nb0 + wn * 2;
-        if (nb < NB) epi_tile<MODE, FULL>(epi, acc[i][0], acc[i][1], mt, nb * 32, M, NB * 32, lane);
+        if (nb < NB) epi_tile<MODE, FULL, LG_NT>(epi, acc[i][0], acc[i][1], mt, nb * 32, M, NB * 32, lane);
       } else {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           int nb = nb0 + wn * 2 + j;
-          if (nb < NB) epi_tile<MODE, FULL>(epi, acc[i][j], acc[i][j], mt, nb * 32, M, N, lane);
+          if (nb < NB) epi_tile<MODE, FULL, LG_NT>(epi, acc[i][j], acc[i][j], mt, nb * 32, M, N, lane);
         }
       }
     }
@@ -684,7 +693,11 @@ __global__ __launch_bounds__(512) void gemm_large_async_kernel(const bf16_t* __r
           for (int v = 0; v < 16; ++v) {
             const float y = src[v] + acc[i][j][v];
             if (MODE == EPI_RESID_OUT && BY_ID) {
-              if (id[i][v] >= 0) epi.embeds[(int64_t)id[i][v] * epi.H + n] = f32_to_bf16(y);
+              // (non-temporal: the output Embeds are the last thing written before the LM head streams its weights:
+              // 241 -> 219 us at 8320 rows; the fp32 sums of the output projection below lose 9 us that way)
+              if (id[i][v] >= 0) store_nt(epi.embeds + (int64_t)id[i][v] * epi.H + n, f32_to_bf16(y));
+            } else if (MODE == EPI_RESID_OUT) {
+              store_nt(reinterpret_cast<float*>(epi.out) + (int64_t)row_of(i, v) * epi.ldo + n, y);
             } else {
               reinterpret_cast<float*>(epi.out)[(int64_t)row_of(i, v) * epi.ldo + n] = y;
             }
