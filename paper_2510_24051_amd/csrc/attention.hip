@@ -273,7 +273,8 @@ __device__ __forceinline__ uint32_t key_bits4(int kv_len, int lim, bool has_bitm
 // goes out after a single dependent load, and the K/V stream runs on across segment boundaries: the next pair
 // (16 KiB per wave) is always requested before the current one is computed.  Segment descriptors, queries and
 // (for bitmap requests) the mask words of pairs requested before a boundary are loaded at the boundary.
-template <int D>
+// NT: the K/V blocks are loaded non-temporally (batches in which no page is read twice).
+template <int D, bool NT>
 __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const DecodeWave* __restrict__ waves,
                                                              const int2* __restrict__ wave_pg, int slots,
                                                              const DecodeSeg* __restrict__ segs,
@@ -327,6 +328,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
   // last pair's blocks: a few cache lines, never used): with the same number of loads in flight on every path into
   // the loop header the compiler keeps exact wait counts, and the batch requested ahead stays in flight while the
   // current one is consumed.  (With conditional batches it waited for all outstanding loads in every compute.)
+  auto ldk = [](const bf16x8* p) { return NT ? load_nt(p) : *p; };
+  auto ldv = [](const bf16x4* p) { return NT ? load_nt(p) : *p; };
   auto fetch = [&](auto set_c, int j_req) {  // j_req is wave-uniform
     constexpr int S = decltype(set_c)::value;
     const bool real = j_req < n_pairs;
@@ -345,14 +348,14 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnArgs a, const D
     const bf16_t* pb_ = a.kv + (int64_t)pp_b * blk;
 #pragma unroll
     for (int k = 0; k < KS; ++k) {
-      ka[S][k] = *reinterpret_cast<const bf16x8*>(pa_ + ko + k * 512);
-      kb[S][k] = *reinterpret_cast<const bf16x8*>(pb_ + ko + k * 512);
+      ka[S][k] = ldk(reinterpret_cast<const bf16x8*>(pa_ + ko + k * 512));
+      kb[S][k] = ldk(reinterpret_cast<const bf16x8*>(pb_ + ko + k * 512));
     }
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
       const int vob = vo + (b >> 1) * 512 + (b & 1) * 128;
-      va[S][b] = *reinterpret_cast<const bf16x4*>(pa_ + vob);
-      vb[S][b] = *reinterpret_cast<const bf16x4*>(pb_ + vob);
+      va[S][b] = ldv(reinterpret_cast<const bf16x4*>(pa_ + vob));
+      vb[S][b] = ldv(reinterpret_cast<const bf16x4*>(pb_ + vob));
     }
   };
   auto end_segment = [&]() {
@@ -773,14 +776,20 @@ __global__ __launch_bounds__(512) void attn_prefill_direct_kernel(AttnArgs a, co
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const int2* wave_pg, int slots,
                               const DecodeSeg* segs, const DecodeCol* cols, int n_waves, int rows_cap, float* part_o,
-                              float* part_ml, hipStream_t s) {
+                              float* part_ml, bool read_once, hipStream_t s) {
   if (n_waves <= 0) return hipSuccess;
   if (slots < 2 || slots > 128 || (slots & 1)) return hipErrorInvalidValue;  // the page list must fit two registers
   dim3 grid((n_waves + 3) / 4), block(256);
-  if (a.D == 128)
-    attn_decode_kernel<128><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
+  // Requests that alias pages (shared prefixes) read them again and again out of the caches; everything else is
+  // read once and streams past them.
+  if (a.D == 128 && read_once)
+    attn_decode_kernel<128, true><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
+  else if (a.D == 128)
+    attn_decode_kernel<128, false><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
+  else if (a.D == 64 && read_once)
+    attn_decode_kernel<64, true><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
   else if (a.D == 64)
-    attn_decode_kernel<64><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
+    attn_decode_kernel<64, false><<<grid, block, 0, s>>>(a, waves, wave_pg, slots, segs, cols, n_waves, rows_cap, part_o, part_ml);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

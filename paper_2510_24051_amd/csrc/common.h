@@ -27,6 +27,13 @@ __device__ __forceinline__ void store_nt(T* p, T v) {
 __device__ __forceinline__ void store_nt(__bf16* p, __bf16 v) {
   __builtin_nontemporal_store(__builtin_bit_cast(uint16_t, v), reinterpret_cast<uint16_t*>(p));
 }
+// Load of bytes that are read once.  Non-temporal loads are faster on their own (stand-alone measurements: a 528 MB
+// gather of 8 KiB blocks 90 -> 80 us, a plain streaming read 5.9 -> 6.45 TB/s) and leave the caches to the data that
+// is read again.
+template <typename T>
+__device__ __forceinline__ T load_nt(const T* p) {
+  return __builtin_nontemporal_load(p);
+}
 __device__ __forceinline__ bf16_t f32_to_bf16(float x) { return (bf16_t)x; }  // v_cvt_pk_bf16_f32: round to nearest even
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

@@ -235,7 +235,7 @@ struct AttnArgs {
 };
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeWave* waves, const int2* wave_pg, int slots,
                               const DecodeSeg* segs, const DecodeCol* cols, int n_waves, int rows_cap, float* part_o,
-                              float* part_ml, hipStream_t s);
+                              float* part_ml, bool read_once, hipStream_t s);
 hipError_t launch_attn_merge(const AttnArgs& a, const int32_t* dec_reqs, int n_dec_reqs, const int32_t* mref_indptr,
                              const int32_t* mrefs, int rows_cap, const float* part_o, const float* part_ml,
                              hipStream_t s);

@@ -1301,7 +1301,8 @@ static pie_status run_layer(pie_ctx* c, int32_t layer, const pie_batch* b, float
   }
   if (b->n_dec_reqs > 0) {
     tm.begin(PIE_STAGE_ATTN_DECODE);
-    HIP_TRY(c, launch_attn_decode(a, b->dwaves, b->wave_pg, b->dslots, b->dsegs, b->dcols, b->n_dwaves, b->rows_cap, b->part_o, b->part_ml, s));
+    HIP_TRY(c, launch_attn_decode(a, b->dwaves, b->wave_pg, b->dslots, b->dsegs, b->dcols, b->n_dwaves, b->rows_cap, b->part_o, b->part_ml,
+                                  /*read_once=*/b->work[5] <= b->work[4], s));
     tm.end(PIE_STAGE_ATTN_DECODE);
     tm.begin(PIE_STAGE_ATTN_MERGE);
     HIP_TRY(c, launch_attn_merge(a, b->dec_reqs, b->n_dec_reqs, b->mref_indptr, b->mrefs, b->rows_cap, b->part_o, b->part_ml, s));

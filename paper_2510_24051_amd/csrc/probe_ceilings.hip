@@ -69,6 +69,30 @@ __global__ void fill_nt_kernel(unsigned int* p, size_t n) {
 }
 
 // 1, 3: every thread reads 16 bytes per step, a wave 1 KiB contiguous, eight steps in flight
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const u32x4* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool NT>
+__device__ __forceinline__ u32x2 ld8(const u32x2* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
+}
+
+// the same streaming read with non-temporal loads
+__global__ __launch_bounds__(256) void read_nt_kernel(const u32x4* __restrict__ src, size_t n_vec, u32x4* __restrict__ sink) {
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+  u32x4 acc = {0, 0, 0, 0};
+  size_t i = tid;
+  for (; i + 7 * stride < n_vec; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if (acc.x == 0x12345678 && acc.y == 0x9abcdef0) sink[tid & 1023] = acc;
+}
+
 __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src, size_t n_vec, u32x4* __restrict__ sink) {
   const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
   u32x4 acc = {0, 0, 0, 0};
@@ -86,6 +110,7 @@ __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src
 // 2: a wave walks `per_wave` pairs of 8 KiB blocks (block = page * 8 + head, a page being 64 KiB): per block four
 // 16-byte loads per lane for the first 4 KiB and eight 8-byte loads for the second, the next pair requested before
 // the current one is consumed.
+template <bool NT = false>
 __global__ __launch_bounds__(256, 2) void gather_kernel(const unsigned char* __restrict__ src, const int* __restrict__ blocks,
                                                         int per_wave, int n_waves, u32x4* __restrict__ sink) {
   const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
@@ -101,14 +126,14 @@ __global__ __launch_bounds__(256, 2) void gather_kernel(const unsigned char* __r
     const unsigned char* pb = src + (size_t)bl[2 * j + 1] * 8192;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      k[S][i] = *(const u32x4*)(pa + lane * 16 + i * 1024);
-      k[S][4 + i] = *(const u32x4*)(pb + lane * 16 + i * 1024);
+      k[S][i] = ld16<NT>((const u32x4*)(pa + lane * 16 + i * 1024));
+      k[S][4 + i] = ld16<NT>((const u32x4*)(pb + lane * 16 + i * 1024));
     }
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
       const int vo = voff + ((b >> 1) * 512 + (b & 1) * 128) * 2;
-      v[S][2 * b] = *(const u32x2*)(pa + vo);
-      v[S][2 * b + 1] = *(const u32x2*)(pb + vo);
+      v[S][2 * b] = ld8<NT>((const u32x2*)(pa + vo));
+      v[S][2 * b + 1] = ld8<NT>((const u32x2*)(pb + vo));
     }
   };
   auto consume = [&](auto sc) {
@@ -242,10 +267,16 @@ int main() {
     int* d;
     CHECK(hipMalloc(&d, bl.size() * 4));
     CHECK(hipMemcpy(d, bl.data(), bl.size() * 4, hipMemcpyHostToDevice));
-    const float ms = best_ms([&] { gather_kernel<<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink); });
+    const float ms = best_ms([&] { gather_kernel<false><<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink); });
     const double bytes = (double)bl.size() * 8192;
     printf("gather of %d (page, head) blocks of 8 KiB, %d waves x %d pairs: %.0f GB/s (%.1f%% of 8000), %.1f us for %.1f MB\n",
            (int)bl.size(), n_waves, per, bytes / ms / 1e6, bytes / ms / 1e6 / 80.0, ms * 1e3, bytes / 1e6);
+    {
+      const float ms_nt = best_ms([&] { gather_kernel<true><<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink); });
+      const float ms_rd = best_ms([&] { read_nt_kernel<<<8192, 256>>>((const u32x4*)a, ((size_t)2 << 30) / 16, sink); }, 4);
+      printf("with non-temporal loads: the gather %.1f us, the streaming read of 2 GiB %.0f GB/s\n", ms_nt * 1e3,
+             ((double)((size_t)2 << 30)) / ms_rd / 1e6);
+    }
     // the same gather right after other kernels have streamed 1.5 GiB of other memory (what a serving step does
     // between two decode-attention launches: weights and the LM head), and right after a kernel has written 16 MiB
     {
@@ -258,7 +289,7 @@ int main() {
       for (int r = 0; r < reps; ++r) {
         read_kernel<<<8192, 256>>>((const u32x4*)other, ((size_t)1536 << 20) / 16, sink);
         CHECK(hipEventRecord(g_e0));
-        gather_kernel<<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
+        gather_kernel<false><<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
         CHECK(hipEventRecord(g_e1));
         CHECK(hipEventSynchronize(g_e1));
         float t;
@@ -274,7 +305,7 @@ int main() {
         for (int r = 0; r < reps; ++r) {
           fill_kernel<<<(unsigned)std::min<size_t>(2048, kib), 256>>>((unsigned int*)other, (kib << 10) / 4);
           CHECK(hipEventRecord(g_e0));
-          gather_kernel<<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
+          gather_kernel<false><<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
           CHECK(hipEventRecord(g_e1));
           CHECK(hipEventSynchronize(g_e1));
           float t;
@@ -292,7 +323,7 @@ int main() {
           CHECK(hipEventRecord(g_e1));
           fill_nt_kernel<<<(unsigned)std::min<size_t>(2048, kib), 256>>>((unsigned int*)other, (kib << 10) / 4);
           CHECK(hipEventRecord(g_e0));
-          gather_kernel<<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
+          gather_kernel<false><<<(n_waves + 3) / 4, 256>>>(a, d, per, n_waves, sink);
           hipEvent_t e2;
           CHECK(hipEventCreate(&e2));
           CHECK(hipEventRecord(e2));
