@@ -175,7 +175,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
         int kb = it * 8 + s;
         kb = kb < KB ? kb : KB - 1;  // tail steps read a valid tile; their A operand is zero
         const int nbj = nb0 + j < NB ? nb0 + j : NB - 1;  // a missing second block re-reads a valid one
-        breg[slot][j][s] = *reinterpret_cast<const bf16x8*>(Wp + packed_tile_offset(nbj, kb, KB) + lane * 8);
+        breg[slot][j][s] = load_nt(reinterpret_cast<const bf16x8*>(Wp + packed_tile_offset(nbj, kb, KB) + lane * 8));  // read once
       }
   };
 
