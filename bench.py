@@ -27,7 +27,7 @@ MFMA_RIDGE_ROWS = 312  # rows above which a bf16 GEMM stops being bound by strea
 # once-streamed weight matrix of known size gives, plus WRITE_SIZE), taken in a profiling session of its own on
 # exactly the default configuration (workload c2, 64 requests, one layer, no adapters): reported only when this run
 # is that configuration, with the file that holds the counters named beside it; any other run reports null.
-PMC_TRAFFIC = {"workload": "c2", "requests": 64, "layers": 1, "lora_rank": 0, "bytes": 524.6e6 + 5.1e6,
+PMC_TRAFFIC = {"workload": "c2", "requests": 64, "layers": 1, "lora_rank": 0, "bytes": 527.5e6 + 5.1e6,
                "source": "profiles/c2_decode_pmc.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this command)"}
 
 
