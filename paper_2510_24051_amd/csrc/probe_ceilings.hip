@@ -277,6 +277,15 @@ int main() {
       printf("with non-temporal loads: the gather %.1f us, the streaming read of 2 GiB %.0f GB/s\n", ms_nt * 1e3,
              ((double)((size_t)2 << 30)) / ms_rd / 1e6);
     }
+    // fixed and marginal cost of the gather: the same number of waves with shorter and longer lists
+    {
+      printf("gather with non-temporal loads, %d waves, pairs per wave -> time:", n_waves);
+      for (int pw : {2, 4, 8, 16}) {
+        const float ms = best_ms([&] { gather_kernel<true><<<(n_waves + 3) / 4, 256>>>(a, d, pw, n_waves, sink); });
+        printf(" %d: %.1f us (%.0f MB);", pw, ms * 1e3, (double)n_waves * pw * 16384 / 1e6);
+      }
+      printf("\n");
+    }
     // the same gather right after other kernels have streamed 1.5 GiB of other memory (what a serving step does
     // between two decode-attention launches: weights and the LM head), and right after a kernel has written 16 MiB
     {
