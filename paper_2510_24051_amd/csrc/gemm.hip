@@ -96,8 +96,11 @@ __device__ __forceinline__ void epi_tile(const EpiArgs& e, const f32x16& acc, co
 #define SK_BK 128  // contraction elements per main-loop iteration (8 MFMA steps)
 #define SK_MAX_SPLITS 8
 
-// WAVES: waves per workgroup, 4 or (unsplit gate/up at widths that give too few workgroups of four) 2.
-template <int MB, int MODE, bool PARTIAL, int NBW, int WAVES = 4>
+// WAVES: waves per workgroup.  KS: the contraction is split KS ways INSIDE the workgroup (unsplit gate/up at widths
+// that give too few waves otherwise): waves w and w + WAVES / KS own the same column block and each takes a K-th of
+// the contraction, with an activation tile of its own per iteration; the sums meet through LDS at the end, so twice
+// as many waves stream weights and no partial sums leave the workgroup.
+template <int MB, int MODE, bool PARTIAL, int NBW, int WAVES = 4, int KS = 1>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                           const bf16_t* __restrict__ Wp, int N, int NB, int K,
                                                           int iters_per_split, EpiArgs epi, float* __restrict__ part) {
@@ -107,17 +110,24 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
   // what they wrote at once, and that one is a microsecond or two slower when the lines have left the caches.
   constexpr bool SK_NT = MODE == EPI_STORE_BF16 || MODE == EPI_STORE_F32 || (PARTIAL && MODE == EPI_RESID_OUT);
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);  // [2][MB*32][SK_BK], 16-byte chunks swizzled by row
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);  // [2][KS][MB*32][SK_BK], 16-byte chunks swizzled by row
+  static_assert(KS == 1 || (!PARTIAL && WAVES % KS == 0), "the in-workgroup split replaces the split across workgroups");
   constexpr int BM = MB * 32;
   constexpr int NT = WAVES * 64;
-  constexpr int A_ELEMS = BM * SK_BK;
+  constexpr int WPS = WAVES / KS;            // waves per K slice
+  constexpr int A_SLICE = BM * SK_BK;        // elements of one slice's activation tile
+  constexpr int A_ELEMS = KS * A_SLICE;      // elements of one stage
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ks = wave / WPS;                 // this wave's K slice
   const int KB = K / 16;
   const int total_iters = (K + SK_BK - 1) / SK_BK;
-  const int it0 = blockIdx.y * iters_per_split;
-  const int it1 = min(total_iters, it0 + iters_per_split);
+  // With KS > 1 the host launches one workgroup per column group over the whole contraction, whose iteration count
+  // is a multiple of KS: slice s covers iterations s * it1 .. (s + 1) * it1 and `it` below counts within the slice.
+  const int it0 = KS > 1 ? 0 : blockIdx.y * iters_per_split;
+  const int it1 = KS > 1 ? total_iters / KS : min(total_iters, it0 + iters_per_split);
+  const int slice_it0 = KS > 1 ? ks * it1 : 0;  // first global iteration of this wave's slice
   // a wave owns NBW adjacent 32-column blocks (SWIGLU: a gate/up pair)
-  int nb0 = (blockIdx.x * WAVES + wave) * NBW;
+  int nb0 = (blockIdx.x * WPS + wave % WPS) * NBW;
   const bool wave_active = nb0 < NB;
   if (!wave_active) nb0 = 0;  // keep loads in bounds; results are dropped
 
@@ -130,7 +140,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
       for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
 
   // A tile loader: BM rows x 16 chunks (16 B) per iteration; chunk c of row r is stored at chunk (c ^ (r & 15))
-  constexpr int A_CHUNKS = BM * 16;
+  constexpr int A_CHUNKS = KS * BM * 16;     // the tiles of all slices, slice by slice
   constexpr int A_PER_THREAD = (A_CHUNKS + NT - 1) / NT;
   // The activation chunks travel in the same ring of three register sets as the weights, requested two iterations
   // ahead and stored to LDS one iteration ahead: the memory counter completes in order, so waiting for the chunks
@@ -139,7 +149,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
   // row blocks of one column block per wave (64-row layer products: 0.244 -> 0.239 ms per forward call): with one
   // row block the extra registers cost the third wave per SIMD, and with two column blocks per wave (LM head) the
   // kernel got 2-3% slower.
-  constexpr bool A_RING = MB >= 2 && NBW == 1;
+  constexpr bool A_RING = MB >= 2 && NBW == 1 && (KS == 1 || WAVES >= 8);  // (few chunks per thread: the ring still fits two waves per SIMD)
   constexpr int A_SETS = A_RING ? 3 : 1;
   u32x4 areg[A_SETS][A_PER_THREAD];
   // Loads always read an in-bounds address (row and k clamped); chunks outside the matrix are zeroed when the
@@ -149,8 +159,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
       const int c = min(tid + j * NT, A_CHUNKS - 1);
-      const int r = min(c >> 4, M - 1), kc = c & 15;
-      const int k = min(it * SK_BK + kc * 8, K - 8);
+      const int sl = c / (BM * 16), cc = c % (BM * 16);
+      const int r = min(cc >> 4, M - 1), kc = cc & 15;
+      const int k = min(((KS > 1 ? sl * it1 : 0) + it) * SK_BK + kc * 8, K - 8);
       areg[slot][j] = *reinterpret_cast<const u32x4*>(A + (int64_t)r * lda + k);
     }
   };
@@ -159,10 +170,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
 #pragma unroll
     for (int j = 0; j < A_PER_THREAD; ++j) {
       const int c = tid + j * NT;
-      const int r = c >> 4, kc = c & 15;
-      const bool inside = r < M && it * SK_BK + kc * 8 < K;
+      const int sl = c / (BM * 16), cc = c % (BM * 16);
+      const int r = cc >> 4, kc = cc & 15;
+      const bool inside = r < M && ((KS > 1 ? sl * it1 : 0) + it) * SK_BK + kc * 8 < K;
       if (c < A_CHUNKS)
-        *reinterpret_cast<u32x4*>(As + buf * A_ELEMS + r * SK_BK + ((kc ^ (r & 15)) << 3)) =
+        *reinterpret_cast<u32x4*>(As + buf * A_ELEMS + sl * A_SLICE + r * SK_BK + ((kc ^ (r & 15)) << 3)) =
             inside ? areg[slot][j] : u32x4{0, 0, 0, 0};
     }
   };
@@ -172,7 +184,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
     for (int j = 0; j < NBW; ++j)
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
-        int kb = it * 8 + s;
+        int kb = (slice_it0 + it) * 8 + s;
         kb = kb < KB ? kb : KB - 1;  // tail steps read a valid tile; their A operand is zero
         const int nbj = nb0 + j < NB ? nb0 + j : NB - 1;  // a missing second block re-reads a valid one
         breg[slot][j][s] = load_nt(reinterpret_cast<const bf16x8*>(Wp + packed_tile_offset(nbj, kb, KB) + lane * 8));  // read once
@@ -192,7 +204,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
       if (A_RING) load_a(it + 2, (SLOT + 2) % 3);
       load_b(it + 2, (SLOT + 2) % 3);
     }
-    const bf16_t* Ab = As + cur * A_ELEMS;
+    const bf16_t* Ab = As + cur * A_ELEMS + ks * A_SLICE;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       const int kc = s * 2 + (lane >> 5);
@@ -227,16 +239,35 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16_t* _
   if constexpr (!PARTIAL && MODE == EPI_SWIGLU && NBW == 1) {
     // One block per wave: the gate block sits in the even waves, its up block in the wave after it, which hands
     // its sums over through LDS (the activation stages are free once the main loop has passed its last barrier).
-    float* xch = reinterpret_cast<float*>(smem_raw);  // [WAVES / 2 pairs][MB][16][64]
-    const int pair = wave >> 1;
-    if (wave & 1) {
+    float* xch = reinterpret_cast<float*>(smem_raw);  // [WPS / 2 pairs][MB][16][64]
+    if constexpr (KS > 1) {
+      // the slices' sums first: slices 1.. leave theirs behind the exchange area, slice 0 adds them in slice order
+      float* red = xch + (WPS / 2) * MB * 16 * 64;  // [KS - 1][WPS][MB][16][64]
+      if (ks > 0) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) red[((((ks - 1) * WPS + wave % WPS) * MB + i) * 16 + v) * 64 + lane] = acc[0][i][v];
+      }
+      __syncthreads();
+      if (ks == 0) {
+#pragma unroll
+        for (int sl = 1; sl < KS; ++sl)
+#pragma unroll
+          for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[0][i][v] += red[((((sl - 1) * WPS + wave) * MB + i) * 16 + v) * 64 + lane];
+      }
+    }
+    const int pair = (wave % WPS) >> 1;
+    if ((wave & 1) && ks == 0) {
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) xch[((pair * MB + i) * 16 + v) * 64 + lane] = acc[0][i][v];
     }
     __syncthreads();
-    if (!(wave & 1) && wave_active) {
+    if (!(wave & 1) && ks == 0 && wave_active) {
 #pragma unroll
       for (int i = 0; i < MB; ++i) {
         f32x16 up;
@@ -733,10 +764,10 @@ static hipError_t set_lds_limit_once(const void* kern, size_t bytes, uint32_t& d
   return e;
 }
 
-template <int MB, int MODE, int NBW, int WAVES = 4>
+template <int MB, int MODE, int NBW, int WAVES = 4, int KS = 1>
 static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeight& W, const EpiArgs& epi, float* ws,
                                size_t ws_elems, int n_cus, hipStream_t s, int* defer, int max_splits = SK_MAX_SPLITS) {
-  const int wg_n = (W.NB + WAVES * NBW - 1) / (WAVES * NBW);
+  const int wg_n = (W.NB + (WAVES / KS) * NBW - 1) / ((WAVES / KS) * NBW);
   const int total_iters = (W.K + SK_BK - 1) / SK_BK;
   // Split K so that one round of workgroups fills the chip without spilling into a second, mostly empty round:
   // the kernel keeps `occ` workgroups per CU resident (register-limited).
@@ -760,17 +791,18 @@ static hipError_t run_skinny_n(const bf16_t* A, int lda, int M, const PackedWeig
   while (splits > 1 && (size_t)splits * M * NP > ws_elems) --splits;
   int ips = (total_iters + splits - 1) / splits;
   splits = (total_iters + ips - 1) / ips;
-  size_t smem = (size_t)2 * MB * 32 * SK_BK * sizeof(bf16_t);
+  size_t smem = (size_t)2 * KS * MB * 32 * SK_BK * sizeof(bf16_t);
   dim3 grid(wg_n, splits), block(WAVES * 64);
   if (splits == 1) {
-    auto kern = gemm_skinny_kernel<MB, MODE, false, NBW, WAVES>;
+    auto kern = gemm_skinny_kernel<MB, MODE, false, NBW, WAVES, KS>;
     static uint32_t lds_set = 0;
     hipError_t e = set_lds_limit_once((const void*)kern, smem, lds_set);
     if (e != hipSuccess) return e;
     kern<<<grid, block, smem, s>>>(A, lda, M, W.data, W.N, W.NB, W.K, ips, epi, nullptr);
     return hipGetLastError();
   }
-  auto kern = gemm_skinny_kernel<MB, MODE, true, NBW, WAVES>;
+  if constexpr (KS > 1) return hipErrorInvalidValue;  // (the in-workgroup split is launched unsplit only)
+  auto kern = gemm_skinny_kernel<MB, MODE, true, NBW, WAVES, 1>;
   static uint32_t lds_set_partial = 0;
   hipError_t e = set_lds_limit_once((const void*)kern, smem, lds_set_partial);
   if (e != hipSuccess) return e;
@@ -797,8 +829,15 @@ static hipError_t run_skinny(const bf16_t* A, int lda, int M, const PackedWeight
         return run_skinny_n<MB, MODE, 1>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer, 1);
       // the 8B width gets there with workgroups of one pair (two waves): 448 of them; as fast as the split
       // version and without its 29 MB of partial sums (the down projection after it gains 1 us)
-      if ((W.NB + 1) / 2 >= n_cus + n_cus / 2)
+      if ((W.NB + 1) / 2 >= n_cus + n_cus / 2) {
+        // With two row blocks a two-wave workgroup fetches as many activation bytes (through the L2) as weight
+        // bytes.  Eight waves, two pairs times two K slices, share each slice's activation tile between two pairs
+        // and put twice as many waves on the weight stream: 53 -> 47 us at 64 rows.  (Four waves, one pair times two
+        // slices, measured the same as two; with one row block the two-wave form stays ahead.)
+        if (MB == 2 && W.K % (2 * SK_BK) == 0)
+          return run_skinny_n<MB, MODE, 1, 8, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer, 1);
         return run_skinny_n<MB, MODE, 1, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer, 1);
+      }
     }
     return run_skinny_n<MB, MODE, 2>(A, lda, M, W, epi, ws, ws_elems, n_cus, s, defer);
   } else {
