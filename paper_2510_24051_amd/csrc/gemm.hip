@@ -494,11 +494,11 @@ __global__ __launch_bounds__(512) void gemm_large_kernel(const bf16_t* __restric
 // The weight operands do not pass through LDS: a wave reads the tiles of its two column blocks straight from
 // global memory into MFMA B operands (the tiled weight layout makes each a contiguous 1 KiB load; the two waves
 // that share a column block meet in the vector cache), one k step ahead, refilling each register set right after
-// the MFMAs that consumed it.  Why: LDS delivers 64 bytes per clock and compute unit for 16-byte reads (measured),
-// and with both operands in LDS a 128x64 wave tile reads 6 KiB per 8 MFMAs, 96 bytes per clock at the full matrix
-// rate: the kernel was bound by LDS reads at 2/3 of that rate (LDS 93% busy in the counters).  Without the weights
-// it reads 4 KiB per 8 MFMAs; the matrix pipe went from 62% to 72% busy, of which the lower clock under the higher
-// load gives back a part (8320 x 28672 x 4096: 1.70 -> 1.58 ms on one box).
+// the MFMAs that consumed it.  Why: with both operands in LDS a 128x64 wave tile issues and waits for 6 LDS reads
+// per 8 MFMAs, without the weights 4, and every instruction issued beside the MFMAs takes matrix time (LDS bandwidth
+// itself is not short: 240-250 bytes per clock and compute unit with many reads in flight, the kernel uses a fifth
+// of it).  The matrix pipe went from 62% to 72% busy, of which the lower clock under the higher load gives back a
+// part (8320 x 28672 x 4096: 1.70 -> 1.58 ms on one box).
 // Workgroup ids are remapped so that each XCD (id % 8) works on a contiguous range of a grouped tile order (8 row
 // tiles per group) and its L2 sees a few activation and weight panels at a time.
 // ------------------------------------------------------------------------------------------------

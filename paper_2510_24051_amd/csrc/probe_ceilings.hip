@@ -7,6 +7,8 @@
 //   3. re-read of a buffer that fits the last-level cache
 //   4. LDS reads per compute unit, 16 and 8 bytes per lane (the operand reads of the tiled GEMM and prefill attention)
 //   5. chained bf16 MFMA 32x32x16 on registers (the matrix rate the clock sustains under load)
+//   6. the same MFMA loop with independent vector arithmetic (fused multiply-adds, exponentials) issued beside it:
+//      how much of the vector work hides under the matrix work (prefill attention's softmax beside its products)
 // Standalone program: allocates its own buffers, prints one line per measurement, touches nothing of the library.
 #include <hip/hip_runtime.h>
 
@@ -159,37 +161,49 @@ __global__ __launch_bounds__(256, 2) void gather_kernel(const unsigned char* __r
   if (acc.x == 0x12345678 && acc.y == 0x9abcdef0) sink[(wave * 64 + lane) & 1023] = acc;
 }
 
-// 4: eight waves per compute unit read LDS and nothing else.  MODE 0: 16 bytes per lane, 1 KiB contiguous per
-// instruction; 1: 16 bytes per lane in the tiled GEMM's swizzled activation layout (rows of 128 bytes, 16-byte chunk
-// c of row r at position c ^ ((r >> 1) & 7)); 2: 8 bytes per lane contiguous; 3: rows of 128 bytes without the swizzle.
-template <int MODE>
-__global__ __launch_bounds__(512) void lds_kernel(unsigned* out, int iters) {
+// 4: WAVES waves per compute unit read LDS and nothing else, eight reads in flight per wave (issued back to back, one
+// wait for the batch: a loop that waits for every read before it issues the next measures the LDS latency, about a
+// quarter of this rate with eight waves).  MODE 0: 16 bytes per lane, 1 KiB contiguous per instruction; 1: 16 bytes
+// per lane in the tiled GEMM's swizzled activation layout (rows of 128 bytes, 16-byte chunk c of row r at position
+// c ^ ((r >> 1) & 7)); 2: 8 bytes per lane contiguous; 3: rows of 128 bytes without the swizzle.
+template <int MODE, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void lds_kernel(unsigned* out, int iters) {
   __shared__ __align__(16) unsigned char lds[65536];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < 65536 / 4; i += 512) ((unsigned*)lds)[i] = i;
+  for (int i = tid; i < 65536 / 4; i += WAVES * 64) ((unsigned*)lds)[i] = i;
   __syncthreads();
-  u32x4 acc = {0, 0, 0, 0};
+  unsigned acc = 0;
   int base;
   if (MODE == 0) base = lane * 16;
   else if (MODE == 1) { const int r = lane & 31, g = lane >> 5; base = r * 128 + ((g ^ ((r >> 1) & 7)) << 4); }
   else if (MODE == 2) base = lane * 8;
   else base = (lane & 31) * 128 + (lane >> 5) * 16;
-  base += wave * 4096;
-  for (int it = 0; it < iters; ++it) {
+  base += (wave & 7) * 4096;
+  unsigned ad[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int off = (base + (MODE == 1 ? u * 32 : u * 1024) + it * 64) & 65535 & ~15;
-      if (MODE == 2) {
-        const u32x2 v = *(volatile u32x2*)(lds + off);
-        acc.x ^= v.x;
-        acc.y ^= v.y;
-      } else {
-        const u32x4 v = *(const volatile u32x4*)(lds + off);
-        acc ^= v;
-      }
+  for (int u = 0; u < 8; ++u) ad[u] = (unsigned)(base + (MODE == 1 ? u * 32 : u * 1024)) & 65535u & ~15u;
+  for (int it = 0; it < iters; ++it) {
+    if (MODE == 2) {
+      u32x2 v0, v1, v2, v3, v4, v5, v6, v7;
+      asm volatile(
+          "ds_read_b64 %0, %8\n ds_read_b64 %1, %9\n ds_read_b64 %2, %10\n ds_read_b64 %3, %11\n"
+          "ds_read_b64 %4, %12\n ds_read_b64 %5, %13\n ds_read_b64 %6, %14\n ds_read_b64 %7, %15\n"
+          "s_waitcnt lgkmcnt(0)\n"
+          : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3), "=&v"(v4), "=&v"(v5), "=&v"(v6), "=&v"(v7)
+          : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7]));
+      acc ^= v0.x ^ v1.x ^ v2.x ^ v3.x ^ v4.x ^ v5.x ^ v6.x ^ v7.x;
+    } else {
+      u32x4 v0, v1, v2, v3, v4, v5, v6, v7;
+      asm volatile(
+          "ds_read_b128 %0, %8\n ds_read_b128 %1, %9\n ds_read_b128 %2, %10\n ds_read_b128 %3, %11\n"
+          "ds_read_b128 %4, %12\n ds_read_b128 %5, %13\n ds_read_b128 %6, %14\n ds_read_b128 %7, %15\n"
+          "s_waitcnt lgkmcnt(0)\n"
+          : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3), "=&v"(v4), "=&v"(v5), "=&v"(v6), "=&v"(v7)
+          : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7]));
+      acc ^= v0.x ^ v1.x ^ v2.x ^ v3.x ^ v4.x ^ v5.x ^ v6.x ^ v7.x;
     }
   }
-  if (acc.x == 0x12345 && acc.y == 77) out[tid] = acc.z;
+  if (acc == 0x12345) out[tid] = acc;
 }
 
 // 5: every wave chains MFMAs on four independent accumulators, operands fixed in registers.  RANDOM: the four MFMAs of
@@ -221,6 +235,34 @@ __global__ __launch_bounds__(512) void mfma_kernel(float* out, int iters) {
   for (int j = 0; j < 4; ++j)
     for (int v = 0; v < 16; ++v) s += c[j][v];
   if (s == 12345.678f) out[threadIdx.x] = s;
+}
+
+// 6: sixteen MFMAs on four independent accumulators per iteration and, after them, NV independent vector operations
+// on eight registers (fused multiply-adds, or base-2 exponentials).  One or two waves per SIMD.
+template <int NV, bool EXP>
+__global__ __launch_bounds__(512) void coissue_kernel(float* out, int iters) {
+  bf16x8 a, b;
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(0.01f * (threadIdx.x % 7 + i));
+    b[i] = (__bf16)(0.02f * (threadIdx.x % 5 + i));
+  }
+  f32x16 acc[4];
+  for (int n = 0; n < 4; ++n)
+    for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+  float x[8];
+  for (int i = 0; i < 8; ++i) x[i] = 0.001f * (threadIdx.x + i);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int m = 0; m < 16; ++m) acc[m % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[m % 4], 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) x[j % 8] = EXP ? __builtin_amdgcn_exp2f(x[j % 8]) : __builtin_fmaf(x[j % 8], 0.999f, 0.001f);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float sum = 0;
+  for (int n = 0; n < 4; ++n)
+    for (int v = 0; v < 16; ++v) sum += acc[n][v];
+  for (int i = 0; i < 8; ++i) sum += x[i];
+  if (sum == 12345.678f) out[threadIdx.x] = sum;
 }
 
 int main() {
@@ -372,15 +414,24 @@ int main() {
     const int iters = 20000;
     const char* names[4] = {"16 bytes per lane, contiguous", "16 bytes per lane, swizzled 128-byte rows (tiled GEMM operand)",
                             "8 bytes per lane, contiguous", "16 bytes per lane, 128-byte rows without swizzle"};
-    float ms[4];
-    ms[0] = best_ms([&] { lds_kernel<0><<<cus, 512>>>(out, iters); }, 3);
-    ms[1] = best_ms([&] { lds_kernel<1><<<cus, 512>>>(out, iters); }, 3);
-    ms[2] = best_ms([&] { lds_kernel<2><<<cus, 512>>>(out, iters); }, 3);
-    ms[3] = best_ms([&] { lds_kernel<3><<<cus, 512>>>(out, iters); }, 3);
-    for (int m = 0; m < 4; ++m) {
-      const double bytes_cu = (double)iters * 8 * 8 * 64 * (m == 2 ? 8 : 16);
-      printf("LDS read, %s: %.1f GB/s per compute unit = %.1f bytes per clock at %.2f GHz\n", names[m],
-             bytes_cu / (ms[m] * 1e6), bytes_cu / (ms[m] * 1e6) / (prop.clockRate / 1e6), prop.clockRate / 1e6);
+    for (int waves : {8, 16}) {
+      float ms[4];
+      if (waves == 8) {
+        ms[0] = best_ms([&] { lds_kernel<0, 8><<<cus, 512>>>(out, iters); }, 3);
+        ms[1] = best_ms([&] { lds_kernel<1, 8><<<cus, 512>>>(out, iters); }, 3);
+        ms[2] = best_ms([&] { lds_kernel<2, 8><<<cus, 512>>>(out, iters); }, 3);
+        ms[3] = best_ms([&] { lds_kernel<3, 8><<<cus, 512>>>(out, iters); }, 3);
+      } else {
+        ms[0] = best_ms([&] { lds_kernel<0, 16><<<cus, 1024>>>(out, iters); }, 3);
+        ms[1] = best_ms([&] { lds_kernel<1, 16><<<cus, 1024>>>(out, iters); }, 3);
+        ms[2] = best_ms([&] { lds_kernel<2, 16><<<cus, 1024>>>(out, iters); }, 3);
+        ms[3] = best_ms([&] { lds_kernel<3, 16><<<cus, 1024>>>(out, iters); }, 3);
+      }
+      for (int m = 0; m < 4; ++m) {
+        const double bytes_cu = (double)iters * 8 * waves * 64 * (m == 2 ? 8 : 16);
+        printf("LDS read, %d waves per compute unit, eight reads in flight each, %s: %.1f GB/s per compute unit = %.1f bytes per clock at %.2f GHz\n",
+               waves, names[m], bytes_cu / (ms[m] * 1e6), bytes_cu / (ms[m] * 1e6) / (prop.clockRate / 1e6), prop.clockRate / 1e6);
+      }
     }
     CHECK(hipFree(out));
   }
@@ -396,6 +447,26 @@ int main() {
       printf("bf16 MFMA 32x32x16 on registers, %s: %.0f TFLOP/s (%.1f%% of 2500); at 32 cycles per MFMA and SIMD that is a clock of %.2f GHz\n",
              random ? "hashed operands of both signs, four pairs in rotation" : "one pair of small smooth operands",
              flops / ms / 1e9, flops / ms / 1e9 / 25.0, (double)iters * 4 * 2 * 32 / (ms * 1e6));
+    }
+    CHECK(hipFree(out));
+  }
+  // 6. MFMA with vector arithmetic beside it
+  {
+    float* out;
+    CHECK(hipMalloc(&out, 1 << 16));
+    const int iters = 20000;
+    for (int waves : {4, 8}) {
+      const dim3 block(waves * 64);
+      const float base = best_ms([&] { coissue_kernel<0, false><<<cus, block>>>(out, iters); }, 3);
+      struct Case { const char* what; int nv; float ms; } cases[4] = {
+          {"64 fused multiply-adds", 64, best_ms([&] { coissue_kernel<64, false><<<cus, block>>>(out, iters); }, 3)},
+          {"128 fused multiply-adds", 128, best_ms([&] { coissue_kernel<128, false><<<cus, block>>>(out, iters); }, 3)},
+          {"16 exponentials", 16, best_ms([&] { coissue_kernel<16, true><<<cus, block>>>(out, iters); }, 3)},
+          {"64 exponentials", 64, best_ms([&] { coissue_kernel<64, true><<<cus, block>>>(out, iters); }, 3)}};
+      printf("MFMA + vector work, %d wave(s) per SIMD: 16 MFMAs alone %.1f ns per iteration\n", waves / 4, base * 1e6 / iters);
+      for (const Case& c : cases)
+        printf("MFMA + vector work, %d wave(s) per SIMD: 16 MFMAs + %s: %.1f ns per iteration, %.2f ns more per vector instruction of the SIMD\n",
+               waves / 4, c.what, c.ms * 1e6 / iters, (c.ms - base) * 1e6 / iters / (c.nv * (waves / 4)));
     }
     CHECK(hipFree(out));
   }
