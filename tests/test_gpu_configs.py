@@ -87,6 +87,16 @@ def test_c2_decode_full(literal):
     compare_config(w, what="c2 literal" if literal else "c2", literal=literal)
 
 
+@pytest.mark.parametrize("n_requests", [17, 45])
+def test_8b_shape_ragged_row_counts(n_requests):
+    """The 8B-shaped layer with row counts that leave the last 32-row block of the weight-streaming GEMMs ragged:
+    17 rows (one block, two-wave gate/up workgroups) and 45 rows (two blocks, the eight-wave gate/up workgroups that
+    split K inside the workgroup).  Shorter contexts than configuration 2 keep the oracle quick."""
+    w = W.c2_decode(seed=2100 + n_requests, n_requests=n_requests, ctx_lo=40, ctx_hi=700, n_kv_pages=4096,
+                    with_head=False)
+    compare_config(w, what=f"8B shape, {n_requests} rows")
+
+
 def c3_rows(b, whole_requests, n_sample):
     rng = np.random.default_rng(3)
     n_prefill_tok = int(b.tok_indptr[8])
