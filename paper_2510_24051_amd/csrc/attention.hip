@@ -562,7 +562,8 @@ __global__ __launch_bounds__(64 * G, 2) void attn_prefill_kernel(AttnArgs a, con
   const int i_tok = it.qb * 32 + qcol;
   const bool valid = i_tok < rq.n_new;
   const int i_ld = valid ? i_tok : rq.n_new - 1;
-  const bool has_bitmap = rq.wpr > 0;
+  // requests with a bitmap are always listed in the launch with pair weights (their rows may see few keys)
+  const bool has_bitmap = LO && rq.wpr > 0;
   bf16x8 qf[D / 16];
   load_q<D>(a.q + (int64_t)(rq.tok0 + i_ld) * a.q_stride + (hk * G + hg) * D, valid, g, qf);
   AttnState<D> st;
